@@ -1,0 +1,403 @@
+"""CPU oracle for the Chorus hot path. TEST INFRASTRUCTURE ONLY.
+
+Plain numpy, float64 throughout, written from the paper's definitions. Nothing
+here is blocked, fused or reordered; numpy matmul / argmax / tanh serve as steps.
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
+module; the product path never does, and this module imports nothing from it.
+
+What the paper fixes and what it leaves open
+--------------------------------------------
+* Stage-1 retrieval (Sec. 3.1, "Full Reuse"): top-1 cosine similarity against the
+  cached prompt embeddings, a hit when the score reaches the threshold tau
+  (the formal fallback rule is m < tau => K1 = K2 = 0, Sec. 3.1 "Stage Boundary
+  Determination").
+* Stage boundaries (Eq. 1) and the TGAA decay (Eq. 4): the paper gives only
+  properties (monotone in m, 0 <= K1 <= K2 <= N, factors >= 1, decreasing in step
+  and in m). `denoise_schedule` is one concrete map with those properties; its
+  VALUES are "parity unpinned" against the paper, its properties are tested.
+* TGAA key amplification (Eq. 2) and output amplification (Eq. 3): implemented
+  literally (K' built by scaling the selected key rows).
+* Hierarchical masks and latent fusion (Eq. 5, Eq. 6): fusion is implemented as
+  written, M*L + (1-M)*SL with a binary M.
+* The DiT block itself is only drawn (Fig. 2) and described in prose (Sec. 2.1):
+  self-attention, cross-attention on the prompt, timestep injection, FFN. Its
+  arithmetic here is the Wan2.1-shaped block the benchmark configurations name
+  (AdaLN modulation, RMSNorm on q/k, 3-D RoPE, tanh-GELU FFN); each choice is
+  stated at the function that makes it.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+F64 = np.float64
+
+# --------------------------------------------------------------------------
+# Stage-1 retrieval (Sec. 3.1 "Full Reuse"; appendix: cosine top-1 over the cache)
+# --------------------------------------------------------------------------
+
+
+def cosine_scores(cache_emb, query):
+    """s_j = <q, c_j> / (|q| |c_j|); a zero-norm vector scores -inf."""
+    c = np.asarray(cache_emb, F64)
+    q = np.asarray(query, F64)
+    if c.shape[0] == 0:
+        return np.zeros(0, F64)
+    dots = c @ q
+    nq = math.sqrt(float(q @ q))
+    nc = np.sqrt(np.einsum("ij,ij->i", c, c))
+    denom = nq * nc
+    s = np.full(c.shape[0], -np.inf, F64)
+    ok = denom > 0
+    s[ok] = dots[ok] / denom[ok]
+    return s
+
+
+def cache_lookup(cache_emb, query, tau):
+    """Returns (index, score m, hit). Lowest index wins ties; empty cache is a miss
+    with index -1 and score -inf."""
+    s = cosine_scores(cache_emb, query)
+    if s.size == 0:
+        return -1, -math.inf, False
+    j = int(np.argmax(s))  # numpy returns the first maximum
+    m = float(s[j])
+    return j, m, bool(m >= tau)
+
+
+# --------------------------------------------------------------------------
+# Stage boundaries and TGAA decay (Eq. 1, Eq. 4) -- values parity unpinned
+# --------------------------------------------------------------------------
+
+DEFAULT_SCHED = dict(a1=0.25, b1=0.25, a2=0.25, b2=0.25, r3=1, Gamma_k=1.5, Gamma_o=1.5, lam=0.5,
+                     gamma_override=0.0)
+
+
+def denoise_schedule(m, tau, N, params=None):
+    """(K1, K2, plan) with plan[i] = (stage, gamma_k, gamma_o) for step i (0-based).
+
+    m < tau  =>  K1 = K2 = 0 and every step is a plain stage-3 step.
+    Otherwise s = clip((m - tau)/(1 - tau), 0, 1) and
+      K1 = clip(floor(N (a1 + b1 s) + 1e-9), 0, N - r3)
+      K2 = clip(K1 + floor(N (a2 + b2 s) + 1e-9), K1, N - r3)
+    so both grow with m and at least r3 steps stay full compute (Sec. 1: the last
+    stage always recomputes everything).
+    For a computed step i >= K1:  w = max(0, 1 - (i - K1)/max(1, K2 - K1)),
+      gamma = max(1, 1 + (Gamma - 1)(1 - lam s) w)
+    which decreases with the step, decreases with m and never drops below 1
+    (the three principles under Eq. 4). Reused steps (i < K1) run no attention; their
+    factors are reported as 1. gamma_override > 0 replaces the factors of the
+    stage-2 steps by that constant.
+    """
+    p = dict(DEFAULT_SCHED)
+    if params:
+        p.update(params)
+    N = int(N)
+    if not (m >= tau):  # also catches NaN and -inf
+        return 0, 0, [(3, 1.0, 1.0) for _ in range(N)]
+    s = min(max((float(m) - tau) / (1.0 - tau), 0.0), 1.0) if tau < 1.0 else 1.0
+    hi = max(N - int(p["r3"]), 0)
+    K1 = min(max(int(math.floor(N * (p["a1"] + p["b1"] * s) + 1e-9)), 0), hi)
+    K2 = min(max(K1 + int(math.floor(N * (p["a2"] + p["b2"] * s) + 1e-9)), K1), hi)
+    plan = []
+    for i in range(N):
+        if i < K1:
+            plan.append((1, 1.0, 1.0))
+            continue
+        stage = 2 if i < K2 else 3
+        w = max(0.0, 1.0 - (i - K1) / max(1, K2 - K1))
+        gk = max(1.0, 1.0 + (p["Gamma_k"] - 1.0) * (1.0 - p["lam"] * s) * w)
+        go = max(1.0, 1.0 + (p["Gamma_o"] - 1.0) * (1.0 - p["lam"] * s) * w)
+        if stage == 2 and p["gamma_override"] > 0:
+            gk = go = float(p["gamma_override"])
+        plan.append((stage, gk, go))
+    return K1, K2, plan
+
+
+# --------------------------------------------------------------------------
+# Pointwise pieces of the block
+# --------------------------------------------------------------------------
+
+LN_EPS = 1e-6
+
+
+def layernorm(x, eps=LN_EPS):
+    """LayerNorm over the last axis, no affine, biased variance."""
+    x = np.asarray(x, F64)
+    mu = x.mean(-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(-1, keepdims=True)
+    return (x - mu) / np.sqrt(var + eps)
+
+
+def rmsnorm(z, gain, eps=LN_EPS):
+    """z / sqrt(mean(z^2) + eps) * gain over the whole last axis (all heads together)."""
+    z = np.asarray(z, F64)
+    return z / np.sqrt((z * z).mean(-1, keepdims=True) + eps) * np.asarray(gain, F64)
+
+
+def gelu_tanh(x):
+    x = np.asarray(x, F64)
+    return 0.5 * x * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (x + 0.044715 * x ** 3)))
+
+
+def linear(x, w, b):
+    """y = x W^T + b with W stored [out, in]."""
+    return np.asarray(x, F64) @ np.asarray(w, F64).T + np.asarray(b, F64)
+
+
+def rope_group_sizes(dh):
+    """Head dims are split into consecutive (t, h, w) groups."""
+    s = dh // 6
+    return dh - 4 * s, 2 * s, 2 * s
+
+
+def token_positions(token_idx, grid):
+    """Original token id n -> (t, h, w) on the token grid (T, Hg, Wg), row-major."""
+    _, Hg, Wg = grid
+    n = np.asarray(token_idx, np.int64)
+    return n // (Hg * Wg), (n // Wg) % Hg, n % Wg
+
+
+def rope3d(z, token_idx, grid, H, dh, theta=10000.0):
+    """3-D rotary embedding on z [L, H*dh]. In a group of size g, the pair
+    (2p, 2p+1) of every head rotates by pos * theta^(-2p/g), pos being the token's
+    t, h or w coordinate for the first, second, third group."""
+    z = np.asarray(z, F64)
+    L = z.shape[0]
+    zh = z.reshape(L, H, dh).copy()
+    pos = token_positions(token_idx, grid)
+    off = 0
+    for g, pcoord in zip(rope_group_sizes(dh), pos):
+        for p in range(g // 2):
+            ang = pcoord.astype(F64) * theta ** (-2.0 * p / g)
+            c, s = np.cos(ang)[:, None], np.sin(ang)[:, None]
+            a = zh[:, :, off + 2 * p].copy()
+            b = zh[:, :, off + 2 * p + 1].copy()
+            zh[:, :, off + 2 * p] = a * c - b * s
+            zh[:, :, off + 2 * p + 1] = a * s + b * c
+        off += g
+    return zh.reshape(L, H * dh)
+
+
+def softmax_rows(logits):
+    m = logits.max(-1, keepdims=True)
+    e = np.exp(logits - m)
+    return e / e.sum(-1, keepdims=True)
+
+
+def attention(q, k, v, H, dh, return_probs=False):
+    """softmax(q k^T / sqrt(dh)) v per head; q [Lq, H*dh], k, v [Lk, H*dh]."""
+    Lq, Lk = q.shape[0], k.shape[0]
+    qh = q.reshape(Lq, H, dh).transpose(1, 0, 2)
+    kh = k.reshape(Lk, H, dh).transpose(1, 0, 2)
+    vh = v.reshape(Lk, H, dh).transpose(1, 0, 2)
+    out = np.empty((H, Lq, dh), F64)
+    probs = []
+    for h in range(H):
+        p = softmax_rows(qh[h] @ kh[h].T / math.sqrt(dh))
+        out[h] = p @ vh[h]
+        if return_probs:
+            probs.append(p)
+    o = out.transpose(1, 0, 2).reshape(Lq, H * dh)
+    return (o, probs) if return_probs else o
+
+
+def tgaa_amplify_keys(k, key_scale):
+    """Eq. 2, first line: K'[j, :] = g_j K[j, :] with g_j = gamma_k on the differential
+    tokens and 1 elsewhere (key_scale is that per-token vector; None leaves K as is)."""
+    if key_scale is None:
+        return k
+    return np.asarray(key_scale, F64)[:, None] * k
+
+
+# --------------------------------------------------------------------------
+# The DiT block (Sec. 2.1, Fig. 2; TGAA per Eq. 2 and Eq. 3)
+# --------------------------------------------------------------------------
+
+
+def dit_block(x, w, shape, text_ctx, t_mod, token_idx=None, key_scale=None, gamma_o=1.0,
+              rows=None, return_branches=False):
+    """One block forward on the rows of x [Ls, D]; returns the new x.
+
+    shape: dict/obj with D, H, dh, grid. token_idx: original token ids of the rows
+    (None = identity) -- they fix the RoPE positions, so a compacted subset keeps
+    its true (t, h, w). Every row of x takes part as a key/value of self-attention:
+    in stage 2 the caller passes only the selected tokens, which is the paper's
+    "select the regions to be computed" (Sec. 3.3.3).
+
+    e = mod_table + t_mod gives (shift, scale, gate) for the self-attention and FFN
+    branches. The six steps:
+      1. h = LN(x)(1 + scale_sa) + shift_sa;  q, k, v = linear(h)
+      2. q, k RMS-normalised over the full width with learned gains
+      3. 3-D RoPE on q, k
+      4. x += gate_sa * linear_o(softmax(q k^T / sqrt(dh)) v)
+      5. cross-attention on the text context with TGAA: queries from an affine
+         LayerNorm of x, q/k RMS-normalised, keys amplified AFTER normalisation
+         (Eq. 2; a scale applied before a per-token norm would cancel), and
+         x += gamma_o * cross_attn(x) (Eq. 3, the bias of the output projection
+         is part of cross_attn)
+      6. x += gate_ffn * linear_2(gelu_tanh(linear_1(LN(x)(1 + scale_ffn) + shift_ffn)))
+
+    rows: optional index array; then only those rows are carried through (their
+    self-attention still sees all Ls keys) and [len(rows), D] is returned. This is
+    the same arithmetic restricted to some output rows, used at sizes where a full
+    block is out of reach.
+    """
+    D, H, dh = shape.D, shape.H, shape.dh
+    grid = shape.grid
+    x = np.asarray(x, F64)
+    Ls = x.shape[0]
+    if token_idx is None:
+        token_idx = np.arange(Ls)
+    token_idx = np.asarray(token_idx, np.int64)
+    e = np.asarray(w["mod_table"], F64) + np.asarray(t_mod, F64)
+    sh1, sc1, g1, sh2, sc2, g2 = e
+    sel = np.arange(Ls) if rows is None else np.asarray(rows, np.int64)
+
+    # 1-3: self-attention inputs
+    h = layernorm(x) * (1.0 + sc1) + sh1
+    wq, wk, wv = (np.asarray(w["w_qkv"], F64)[i * D:(i + 1) * D] for i in range(3))
+    bq, bk, bv = (np.asarray(w["b_qkv"], F64)[i * D:(i + 1) * D] for i in range(3))
+    q = rope3d(rmsnorm(linear(h[sel], wq, bq), w["g_q"]), token_idx[sel], grid, H, dh)
+    k = rope3d(rmsnorm(linear(h, wk, bk), w["g_k"]), token_idx, grid, H, dh)
+    v = linear(h, wv, bv)
+    # 4
+    y_sa = linear(attention(q, k, v, H, dh), w["w_o"], w["b_o"])
+    xr = x[sel] + g1 * y_sa
+    # 5: cross-attention with TGAA
+    hc = layernorm(xr) * np.asarray(w["ln3_w"], F64) + np.asarray(w["ln3_b"], F64)
+    qc = rmsnorm(linear(hc, w["w_cq"], w["b_cq"]), w["g_cq"])
+    ctx = np.asarray(text_ctx, F64)
+    wck, wcv = np.asarray(w["w_ckv"], F64)[:D], np.asarray(w["w_ckv"], F64)[D:]
+    bck, bcv = np.asarray(w["b_ckv"], F64)[:D], np.asarray(w["b_ckv"], F64)[D:]
+    kc = rmsnorm(linear(ctx, wck, bck), w["g_ck"])
+    vc = linear(ctx, wcv, bcv)
+    kc_amp = tgaa_amplify_keys(kc, key_scale)
+    y_ca = linear(attention(qc, kc_amp, vc, H, dh), w["w_co"], w["b_co"])
+    xr = xr + gamma_o * y_ca
+    # 6: FFN
+    h2 = layernorm(xr) * (1.0 + sc2) + sh2
+    y_ffn = linear(gelu_tanh(linear(h2, w["w_1"], w["b_1"])), w["w_2"], w["b_2"])
+    out = xr + g2 * y_ffn
+    if return_branches:
+        return out, dict(y_sa=y_sa, y_ca=y_ca, y_ffn=y_ffn, g1=g1, g2=g2)
+    return out
+
+
+# --------------------------------------------------------------------------
+# Selective region path (Sec. 3.3; Eq. 6)
+# --------------------------------------------------------------------------
+
+
+def region_compact(mask_see):
+    """Ascending token ids where the visible mask is set."""
+    return np.flatnonzero(np.asarray(mask_see) != 0).astype(np.int64)
+
+
+def gather_rows(x, idx):
+    return np.asarray(x)[np.asarray(idx, np.int64)].copy()
+
+
+def scatter_rows(dst, src, idx):
+    out = np.array(dst, copy=True)
+    out[np.asarray(idx, np.int64)] = src
+    return out
+
+
+def expand_token_mask(mask_tok, grid, patch, C):
+    """Token-grid mask [T*Hg*Wg] -> latent-shaped [C, T*pt, Hg*ph, Wg*pw]."""
+    T, Hg, Wg = grid
+    pt, ph, pw = patch
+    m = np.asarray(mask_tok).reshape(T, Hg, Wg)
+    m = np.repeat(np.repeat(np.repeat(m, pt, 0), ph, 1), pw, 2)
+    return np.broadcast_to(m[None], (C,) + m.shape)
+
+
+def region_blend(L, SL, mask_edit_tok, grid, patch):
+    """Eq. 6: L <- M_edit * L + (1 - M_edit) * SL, M_edit binary, given per token."""
+    L = np.asarray(L)
+    SL = np.asarray(SL)
+    M = (expand_token_mask(mask_edit_tok, grid, patch, L.shape[0]) != 0).astype(L.dtype)
+    return M * L + (1 - M) * SL
+
+
+# --------------------------------------------------------------------------
+# Step glue: declared stand-ins that close the denoising loop around the blocks
+# (the paper's sampler is DPM++ with default settings, Sec. 4.1; its coefficients
+#  are not given, so an Euler flow-matching update stands in)
+# --------------------------------------------------------------------------
+
+
+def patchify(latent, patch):
+    """[C, T, Hl, Wl] -> [L, C*pt*ph*pw]; token order (t, hg, wg), feature order (c, dt, dy, dx)."""
+    C, T, Hl, Wl = latent.shape
+    pt, ph, pw = patch
+    z = np.asarray(latent).reshape(C, T // pt, pt, Hl // ph, ph, Wl // pw, pw)
+    return z.transpose(1, 3, 5, 0, 2, 4, 6).reshape((T // pt) * (Hl // ph) * (Wl // pw), C * pt * ph * pw)
+
+
+def unpatchify(tokens, latent_shape, patch):
+    C, T, Hl, Wl = latent_shape
+    pt, ph, pw = patch
+    z = np.asarray(tokens).reshape(T // pt, Hl // ph, Wl // pw, C, pt, ph, pw)
+    return z.transpose(3, 0, 4, 1, 5, 2, 6).reshape(C, T, Hl, Wl)
+
+
+def text_project(text_emb, gw):
+    """Raw text embeddings [Lt, text_dim] -> context [Lt, D]: linear, tanh-GELU, linear."""
+    return linear(gelu_tanh(linear(text_emb, gw["w_text1"], gw["b_text1"])), gw["w_text2"], gw["b_text2"])
+
+
+def patch_embed(patches, gw):
+    return linear(patches, gw["w_patch"], gw["b_patch"])
+
+
+def head(x, gw, t_head):
+    """Output head: LN(x)(1 + scale) + shift with (shift, scale) = head_table + t_head, then linear to a patch."""
+    sh, sc = np.asarray(gw["head_table"], F64) + np.asarray(t_head, F64)
+    return linear(layernorm(x) * (1.0 + sc) + sh, gw["w_head"], gw["b_head"])
+
+
+def denoise_step(latent, blocks, gw, shape, text_ctx, t_mod, t_head, dsigma,
+                 mask_see=None, mask_edit=None, SL=None, key_scale=None, gamma_o=1.0):
+    """One computed denoising step (stage 2 when masks are given, else stage 3).
+
+    Stage 2 (Sec. 3.3): the tokens in M_see are compacted, run through every block
+    (self-attention over exactly those tokens), the sampler updates only them, and
+    Eq. 6 merges the result with the source latent SL under M_edit.
+    """
+    lat = np.asarray(latent, F64)
+    patch = shape.patch
+    Ltok = shape.L
+    idx = np.arange(Ltok) if mask_see is None else region_compact(mask_see)
+    toks = patchify(lat, patch)
+    x = patch_embed(gather_rows(toks, idx), gw)
+    for w in blocks:
+        x = dit_block(x, w, shape, text_ctx, t_mod, token_idx=idx, key_scale=key_scale, gamma_o=gamma_o)
+    v = head(x, gw, t_head)
+    toks_new = scatter_rows(toks, gather_rows(toks, idx) + dsigma * v, idx)
+    out = unpatchify(toks_new, lat.shape, patch)
+    if mask_edit is not None:
+        out = region_blend(out, np.asarray(SL, F64), mask_edit, shape.grid, patch)
+    return out
+
+
+def run_schedule(plan, sigmas, latent0, SL, blocks, gw, shape, text_ctx, t_mods, t_heads,
+                 mask_see=None, mask_edit=None, key_scale_of=None):
+    """The three-stage loop (Sec. 3.1): stage-1 steps take the source latent as is,
+    stage-2 steps run the selective region path, stage-3 steps run everything.
+    key_scale_of(gamma_k) builds the per-text-token key scale for a step."""
+    lat = np.asarray(latent0, F64)
+    for i, (stage, gk, go) in enumerate(plan):
+        if stage == 1:
+            lat = np.asarray(SL, F64).copy()
+            continue
+        ks = key_scale_of(gk) if key_scale_of is not None else None
+        ds = sigmas[i + 1] - sigmas[i]
+        if stage == 2:
+            lat = denoise_step(lat, blocks, gw, shape, text_ctx, t_mods[i], t_heads[i], ds,
+                               mask_see=mask_see, mask_edit=mask_edit, SL=SL, key_scale=ks, gamma_o=go)
+        else:
+            lat = denoise_step(lat, blocks, gw, shape, text_ctx, t_mods[i], t_heads[i], ds,
+                               key_scale=ks, gamma_o=go)
+    return lat

@@ -1,0 +1,497 @@
+"""Pins for the CPU oracle: every function is checked against something other than
+itself -- brute force in pure Python on tiny inputs, closed forms, invariants the
+paper states, and torch-CPU library routines as a third opinion. CPU only."""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as TF
+
+import synth
+from oracle import chorus_oracle as O
+
+T64 = torch.float64
+
+
+# ------------------------------------------------------------------ lookup
+
+def _brute_lookup(cache, q):
+    best, bj = -math.inf, -1
+    nq = math.sqrt(sum(float(a) * float(a) for a in q))
+    for j, row in enumerate(cache):
+        d = sum(float(a) * float(b) for a, b in zip(row, q))
+        nc = math.sqrt(sum(float(a) * float(a) for a in row))
+        s = d / (nq * nc) if nq * nc > 0 else -math.inf
+        if s > best:
+            best, bj = s, j
+    return bj, best
+
+
+def test_lookup_brute_force():
+    cache = synth.cache_embeddings(8, 256, seed=0)
+    q = synth.cache_query(cache, seed=0, near=5)
+    j, m, hit = O.cache_lookup(cache, q, 0.75)
+    bj, bm = _brute_lookup(cache, q)
+    assert j == bj == 5
+    assert abs(m - bm) < 1e-12
+    assert hit == (bm >= 0.75)
+
+
+def test_lookup_self_query_and_numpy_argmax():
+    cache = synth.cache_embeddings(64, 128, seed=1)
+    for j in (0, 17, 63):
+        jj, m, hit = O.cache_lookup(cache, cache[j], 0.75)
+        assert jj == j and abs(m - 1.0) < 1e-6 and hit
+    q = synth.cache_query(cache, seed=1, near=None)
+    jj, m, hit = O.cache_lookup(cache, q, 0.75)
+    # rows are unit norm, so cosine ranking == dot ranking
+    assert jj == int(np.argmax(cache.astype(np.float64) @ q.astype(np.float64)))
+    assert not hit  # uniform query in 128-d: cosine far below 0.75
+
+
+def test_lookup_scale_invariance_and_non_unit_rows():
+    # cosine, not dot: a long row must not win on length alone
+    cache = np.array([[10.0, 10.0], [1.0, 0.0], [0.0, 3.0]], np.float32)
+    j, m, _ = O.cache_lookup(cache, np.array([2.0, 0.1], np.float32), 0.5)
+    assert j == 1
+    j2, m2, _ = O.cache_lookup(cache * 8.0, np.array([2.0, 0.1], np.float32) * 0.25, 0.5)
+    assert j2 == 1 and abs(m - m2) < 1e-12
+
+
+def test_lookup_ties_empty_single_zero_norm():
+    cache = synth.cache_embeddings(16, 32, seed=2)
+    cache[11] = cache[3]
+    j, m, _ = O.cache_lookup(cache, cache[3], 0.75)
+    assert j == 3  # lowest index among equal maxima
+    assert O.cache_lookup(np.zeros((0, 32), np.float32), cache[0], 0.75) == (-1, -math.inf, False)
+    j, m, hit = O.cache_lookup(cache[:1], cache[0], 0.75)
+    assert j == 0 and hit
+    z = cache.copy()
+    z[0] = 0
+    s = O.cosine_scores(z, cache[1])
+    assert s[0] == -math.inf and np.isfinite(s[1:]).all()
+    j, m, hit = O.cache_lookup(cache, np.zeros(32, np.float32), 0.75)
+    assert m == -math.inf and not hit
+
+
+def test_lookup_threshold_is_inclusive():
+    # Sec. 3.1: the miss condition is m < tau, so m == tau is a hit
+    cache = np.array([[1.0, 0.0], [0.0, 1.0]], np.float32)
+    j, m, hit = O.cache_lookup(cache, np.array([1.0, 0.0], np.float32), 1.0)
+    assert (j, m, hit) == (0, 1.0, True)
+
+
+# ---------------------------------------------------------------- schedule
+
+@pytest.mark.parametrize("N", [1, 4, 8, 50])
+@pytest.mark.parametrize("tau", [0.65, 0.75])
+def test_schedule_properties(N, tau):
+    prev = (0, 0)
+    prev_first_gamma = None
+    for m in np.linspace(0.0, 1.0, 201):
+        K1, K2, plan = O.denoise_schedule(float(m), tau, N)
+        assert len(plan) == N
+        assert 0 <= K1 <= K2 <= N                      # Eq. 1 bounds
+        if m < tau:
+            assert (K1, K2) == (0, 0)                  # fallback rule
+            assert all(p == (3, 1.0, 1.0) for p in plan)
+            continue
+        assert K1 >= prev[0] and K2 >= prev[1]         # monotone in m
+        prev = (K1, K2)
+        stages = [p[0] for p in plan]
+        assert stages == [1] * K1 + [2] * (K2 - K1) + [3] * (N - K2)
+        assert K2 <= N - 1 or N == 0                   # at least one full-compute step
+        gk = [p[1] for p in plan[K1:]]
+        go = [p[2] for p in plan[K1:]]
+        assert all(g >= 1.0 for g in gk + go)          # clamp
+        assert all(a >= b for a, b in zip(gk, gk[1:]))  # decreasing with the step
+        assert all(a >= b for a, b in zip(go, go[1:]))
+        if gk:
+            if prev_first_gamma is not None:
+                assert gk[0] <= prev_first_gamma + 1e-12  # decreasing with m
+            prev_first_gamma = gk[0]
+
+
+def test_schedule_four_step_plan_and_override():
+    K1, K2, plan = O.denoise_schedule(0.8, 0.75, 4)
+    assert (K1, K2) == (1, 2) and [p[0] for p in plan] == [1, 2, 3, 3]
+    assert plan[1][1] > 1.0 and plan[2][1:] == (1.0, 1.0) and plan[3][1:] == (1.0, 1.0)
+    _, _, plan = O.denoise_schedule(0.8, 0.75, 4, dict(gamma_override=1.5))
+    assert plan[1] == (2, 1.5, 1.5)
+    # NaN / -inf scores (empty cache) fall back to plain generation
+    assert O.denoise_schedule(-math.inf, 0.75, 4)[:2] == (0, 0)
+    assert O.denoise_schedule(float("nan"), 0.75, 4)[:2] == (0, 0)
+
+
+# ------------------------------------------------- pointwise vs torch / closed forms
+
+def test_layernorm_rms_gelu_linear_vs_torch():
+    x = synth.normal(3, "p.x", (37, 96), 1.7, 0.3).astype(np.float64)
+    xt = torch.from_numpy(x)
+    np.testing.assert_allclose(O.layernorm(x), TF.layer_norm(xt, (96,), eps=1e-6).numpy(), rtol=0, atol=1e-12)
+    ln = O.layernorm(x)
+    assert np.abs(ln.mean(-1)).max() < 1e-12 and np.abs(ln.var(-1) - 1).max() < 1e-5
+    g = synth.normal(3, "p.g", (96,), 0.2, 1.0).astype(np.float64)
+    np.testing.assert_allclose(O.rmsnorm(x, g), TF.rms_norm(xt, (96,), torch.from_numpy(g), eps=1e-6).numpy(),
+                               rtol=0, atol=1e-12)
+    r = O.rmsnorm(x * 100, np.ones(96))
+    np.testing.assert_allclose(np.sqrt((r * r).mean(-1)), 1.0, atol=1e-8)
+    np.testing.assert_allclose(O.gelu_tanh(x), TF.gelu(xt, approximate="tanh").numpy(), rtol=0, atol=1e-14)
+    assert abs(float(O.gelu_tanh(np.array(0.0)))) == 0.0 and abs(float(O.gelu_tanh(np.array(10.0))) - 10.0) < 1e-9
+    w = synth.normal(3, "p.w", (40, 96)).astype(np.float64)
+    b = synth.normal(3, "p.b", (40,)).astype(np.float64)
+    np.testing.assert_allclose(O.linear(x, w, b), TF.linear(xt, torch.from_numpy(w), torch.from_numpy(b)).numpy(),
+                               rtol=0, atol=1e-11)
+    # triple loop on a corner
+    y = O.linear(x, w, b)
+    for i, j in ((0, 0), (36, 39), (5, 17)):
+        assert abs(y[i, j] - (sum(x[i, k] * w[j, k] for k in range(96)) + b[j])) < 1e-11
+
+
+def _rope_complex(z, token_idx, grid, H, dh, theta=10000.0):
+    """Independent formulation: each (even, odd) pair is a complex number multiplied by e^{i pos w}."""
+    L = z.shape[0]
+    zc = z.reshape(L, H, dh // 2, 2)
+    zc = zc[..., 0] + 1j * zc[..., 1]
+    T, Hg, Wg = grid
+    n = np.asarray(token_idx)
+    coords = (n // (Hg * Wg), (n // Wg) % Hg, n % Wg)
+    s = dh // 6
+    sizes = (dh - 4 * s, 2 * s, 2 * s)
+    freqs = []
+    for g, c in zip(sizes, coords):
+        inv = theta ** (-np.arange(0, g, 2, dtype=np.float64) / g)
+        freqs.append(np.exp(1j * c[:, None].astype(np.float64) * inv[None]))
+    rot = np.concatenate(freqs, axis=1)  # [L, dh/2]
+    out = zc * rot[:, None, :]
+    return np.stack([out.real, out.imag], -1).reshape(L, H * dh)
+
+
+@pytest.mark.parametrize("dh,H", [(64, 4), (128, 2)])
+def test_rope(dh, H):
+    assert O.rope_group_sizes(128) == (44, 42, 42) and O.rope_group_sizes(64) == (24, 20, 20)
+    grid = (4, 6, 5)
+    L = 4 * 6 * 5
+    z = synth.normal(4, f"rope{dh}", (L, H * dh)).astype(np.float64)
+    idx = np.arange(L)
+    r = O.rope3d(z, idx, grid, H, dh)
+    np.testing.assert_allclose(r, _rope_complex(z, idx, grid, H, dh), atol=1e-12)
+    np.testing.assert_array_equal(r[0], z[0])                      # position (0,0,0) is the identity
+    np.testing.assert_allclose((r * r).sum(-1), (z * z).sum(-1), rtol=1e-12)  # rotation keeps norms
+    # relative-position property: <R(p) q, R(p') k> depends only on p - p'
+    q = z[7:8].repeat(L, 0)
+    k = z[9:10].repeat(L, 0)
+    rq, rk = O.rope3d(q, idx, grid, H, dh), O.rope3d(k, idx, grid, H, dh)
+    pos = np.stack(O.token_positions(idx, grid), -1)
+    ix = lambda t, h, w: (t * 6 + h) * 5 + w
+    a, b, c, d = ix(1, 2, 1), ix(2, 4, 3), ix(2, 3, 2), ix(3, 5, 4)   # b - a == d - c == (1, 2, 2)
+    assert ((pos[b] - pos[a]) == (pos[d] - pos[c])).all()
+    for hh in range(H):
+        sl = slice(hh * dh, (hh + 1) * dh)
+        assert abs(rq[a, sl] @ rk[b, sl] - rq[c, sl] @ rk[d, sl]) < 1e-10
+        assert abs(rq[a, sl] @ rk[b, sl] - rq[a, sl] @ rk[d, sl]) > 1e-6   # and does depend on the offset
+    # compacted subset keeps original positions
+    sub = np.array([3, 50, 51, 119])
+    np.testing.assert_array_equal(O.rope3d(z[sub], sub, grid, H, dh), r[sub])
+
+
+def test_token_positions():
+    t, h, w = O.token_positions(np.array([0, 1, 52, 30 * 52, 21 * 30 * 52 - 1]), (21, 30, 52))
+    assert list(t) == [0, 0, 0, 1, 20] and list(h) == [0, 0, 1, 0, 29] and list(w) == [0, 1, 0, 0, 51]
+
+
+# --------------------------------------------------------------- attention
+
+def _brute_attention(q, k, v, H, dh):
+    Lq, Lk = q.shape[0], k.shape[0]
+    out = np.zeros((Lq, H * dh))
+    for h in range(H):
+        for i in range(Lq):
+            logits = [sum(q[i, h * dh + c] * k[j, h * dh + c] for c in range(dh)) / math.sqrt(dh) for j in range(Lk)]
+            mx = max(logits)
+            e = [math.exp(l - mx) for l in logits]
+            s = sum(e)
+            for c in range(dh):
+                out[i, h * dh + c] = sum(e[j] / s * v[j, h * dh + c] for j in range(Lk))
+    return out
+
+
+def test_attention_brute_force_and_sdpa():
+    H, dh, Lq, Lk = 2, 8, 5, 7
+    q = synth.normal(5, "a.q", (Lq, H * dh), 2.0).astype(np.float64)
+    k = synth.normal(5, "a.k", (Lk, H * dh), 2.0).astype(np.float64)
+    v = synth.normal(5, "a.v", (Lk, H * dh)).astype(np.float64)
+    o, probs = O.attention(q, k, v, H, dh, return_probs=True)
+    np.testing.assert_allclose(o, _brute_attention(q, k, v, H, dh), atol=1e-12)
+    for p in probs:
+        np.testing.assert_allclose(p.sum(-1), 1.0, atol=1e-14)   # rows sum to 1
+    tq, tk, tv = (torch.from_numpy(a).reshape(-1, H, dh).transpose(0, 1) for a in (q, k, v))
+    ref = TF.scaled_dot_product_attention(tq, tk, tv).transpose(0, 1).reshape(Lq, H * dh).numpy()
+    np.testing.assert_allclose(o, ref, atol=1e-12)
+
+
+def test_attention_closed_forms():
+    H, dh, Lq, Lk = 3, 4, 6, 9
+    v = synth.normal(6, "c.v", (Lk, H * dh)).astype(np.float64)
+    q = synth.normal(6, "c.q", (Lq, H * dh)).astype(np.float64)
+    # equal logits -> mean of V
+    o = O.attention(q, np.zeros((Lk, H * dh)), v, H, dh)
+    np.testing.assert_allclose(o, np.broadcast_to(v.mean(0), o.shape), atol=1e-14)
+    # one key -> V
+    o = O.attention(q, q[:1], v[:1], H, dh)
+    np.testing.assert_allclose(o, np.broadcast_to(v[0], o.shape), atol=1e-14)
+    # a dominating key -> its V
+    k = np.zeros((Lk, H * dh))
+    k[4] = 1e3 * np.sign(q[2])
+    o = O.attention(q[2:3], k, v, H, dh)
+    np.testing.assert_allclose(o[0], v[4], atol=1e-9)
+
+
+# ------------------------------------------------------------------- TGAA
+
+def _cross_inputs(seed=7, Lq=10, Lt=6, H=2, dh=8):
+    q = synth.normal(seed, "t.q", (Lq, H * dh), 1.5).astype(np.float64)
+    k = synth.normal(seed, "t.k", (Lt, H * dh), 1.5).astype(np.float64)
+    v = synth.normal(seed, "t.v", (Lt, H * dh)).astype(np.float64)
+    return q, k, v, H, dh
+
+
+def test_tgaa_key_amplification():
+    q, k, v, H, dh = _cross_inputs()
+    plain = O.attention(q, k, v, H, dh)
+    # neutral amplification is plain cross-attention, bit for bit
+    np.testing.assert_array_equal(O.attention(q, O.tgaa_amplify_keys(k, np.ones(6)), v, H, dh), plain)
+    np.testing.assert_array_equal(O.attention(q, O.tgaa_amplify_keys(k, None), v, H, dh), plain)
+    # g == c on all tokens is attention with softmax scale c/sqrt(dh)
+    tq, tk, tv = (torch.from_numpy(a).reshape(-1, H, dh).transpose(0, 1) for a in (q, k, v))
+    ref = TF.scaled_dot_product_attention(tq, tk, tv, scale=1.5 / math.sqrt(dh)).transpose(0, 1).reshape(10, H * dh)
+    np.testing.assert_allclose(O.attention(q, O.tgaa_amplify_keys(k, np.full(6, 1.5)), v, H, dh), ref.numpy(), atol=1e-12)
+    # Eq. 2 on a strict subset: scaled key rows == per-column logit scale
+    g = np.ones(6)
+    g[[1, 4]] = 1.5
+    amp = O.attention(q, O.tgaa_amplify_keys(k, g), v, H, dh)
+    for h in range(H):
+        sl = slice(h * dh, (h + 1) * dh)
+        logits = (q[:, sl] @ k[:, sl].T) / math.sqrt(dh) * g[None, :]
+        p = np.exp(logits - logits.max(-1, keepdims=True))
+        p /= p.sum(-1, keepdims=True)
+        np.testing.assert_allclose(amp[:, sl], p @ v[:, sl], atol=1e-12)
+    # only the selected rows of K change
+    kp = O.tgaa_amplify_keys(k, g)
+    np.testing.assert_array_equal(kp[[0, 2, 3, 5]], k[[0, 2, 3, 5]])
+    np.testing.assert_array_equal(kp[[1, 4]], 1.5 * k[[1, 4]])
+    assert np.abs(amp - plain).max() > 1e-3
+
+
+# ------------------------------------------------------------------ block
+
+class _Shape:
+    def __init__(self, D, H, dh, grid):
+        self.D, self.H, self.dh, self.grid = D, H, dh, grid
+
+
+def _small_block(seed=0, stress=True, D=48, H=2, dh=24, F=80, Lt=5, grid=(2, 3, 4)):
+    bs = synth.BlockShape("t", D=D, H=H, dh=dh, F=F, Lt=Lt, text_dim=D, grid=grid)
+    w = synth.stress_block_weights(bs, seed) if stress else synth.block_weights(bs, seed)
+    inp = synth.block_inputs(bs, seed, x_std=1.0)
+    return bs, w, inp
+
+
+def _torch_block(x, w, bs, ctx, t_mod, token_idx, key_scale, gamma_o, key_mask=None):
+    """Third opinion: the same block composed from torch-CPU library routines in fp64
+    (layer_norm, rms_norm, linear, gelu, scaled_dot_product_attention) with the
+    complex-number RoPE above. key_mask (bool [L]) runs the DENSE masked form:
+    all tokens are queries, keys outside the mask get -inf."""
+    D, H, dh = bs.D, bs.H, bs.dh
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    x = t(x)
+    e = t(w["mod_table"]) + t(t_mod)
+    sh1, sc1, g1, sh2, sc2, g2 = e
+    h = TF.layer_norm(x, (D,), eps=1e-6) * (1 + sc1) + sh1
+    qkv = TF.linear(h, t(w["w_qkv"]), t(w["b_qkv"]))
+    q, k, v = qkv[:, :D], qkv[:, D:2 * D], qkv[:, 2 * D:]
+    q = TF.rms_norm(q, (D,), t(w["g_q"]), eps=1e-6)
+    k = TF.rms_norm(k, (D,), t(w["g_k"]), eps=1e-6)
+    q = t(_rope_complex(q.numpy(), token_idx, bs.grid, H, dh))
+    k = t(_rope_complex(k.numpy(), token_idx, bs.grid, H, dh))
+    sp = lambda a: a.reshape(-1, H, dh).transpose(0, 1)
+    am = None
+    if key_mask is not None:
+        am = torch.zeros(x.shape[0], x.shape[0], dtype=T64)
+        am[:, ~torch.from_numpy(key_mask)] = -math.inf
+    o = TF.scaled_dot_product_attention(sp(q), sp(k), sp(v), attn_mask=am).transpose(0, 1).reshape(-1, D)
+    x = x + g1 * TF.linear(o, t(w["w_o"]), t(w["b_o"]))
+    hc = TF.layer_norm(x, (D,), t(w["ln3_w"]), t(w["ln3_b"]), eps=1e-6)
+    qc = TF.rms_norm(TF.linear(hc, t(w["w_cq"]), t(w["b_cq"])), (D,), t(w["g_cq"]), eps=1e-6)
+    kv = TF.linear(t(ctx), t(w["w_ckv"]), t(w["b_ckv"]))
+    kc = TF.rms_norm(kv[:, :D], (D,), t(w["g_ck"]), eps=1e-6)
+    vc = kv[:, D:]
+    if key_scale is not None:
+        kc = kc * t(key_scale)[:, None]
+    oc = TF.scaled_dot_product_attention(sp(qc), sp(kc), sp(vc)).transpose(0, 1).reshape(-1, D)
+    x = x + gamma_o * TF.linear(oc, t(w["w_co"]), t(w["b_co"]))
+    h2 = TF.layer_norm(x, (D,), eps=1e-6) * (1 + sc2) + sh2
+    y = TF.linear(TF.gelu(TF.linear(h2, t(w["w_1"]), t(w["b_1"])), approximate="tanh"), t(w["w_2"]), t(w["b_2"]))
+    return (x + g2 * y).numpy()
+
+
+def test_block_vs_torch_composition():
+    bs, w, inp = _small_block()
+    g = np.array([1.0, 1.5, 1.0, 1.5, 1.0])
+    out = O.dit_block(inp["x"], w, bs, inp["text_ctx"], inp["t_mod"], key_scale=g, gamma_o=1.3)
+    ref = _torch_block(inp["x"], w, bs, inp["text_ctx"], inp["t_mod"], np.arange(bs.L), g, 1.3)
+    np.testing.assert_allclose(out, ref, atol=1e-10)
+    assert np.abs(out - inp["x"]).max() > 0.1  # the branches are not negligible in this variant
+
+
+def test_block_zero_gates_is_identity_and_gamma_o_linear():
+    bs, w, inp = _small_block()
+    w0 = dict(w)
+    mt = w["mod_table"].copy()
+    mt[2] = -inp["t_mod"][2]
+    mt[5] = -inp["t_mod"][5]
+    w0["mod_table"] = mt
+    out = O.dit_block(inp["x"], w0, bs, inp["text_ctx"], inp["t_mod"], gamma_o=0.0)
+    np.testing.assert_array_equal(out, inp["x"].astype(np.float64))
+    # Eq. 3: with the FFN gate closed, x_out - x_in is affine in gamma_o with slope cross_attn(x)
+    outs = [O.dit_block(inp["x"], w0, bs, inp["text_ctx"], inp["t_mod"], gamma_o=g) for g in (0.0, 1.0, 2.0)]
+    np.testing.assert_allclose(outs[2] - outs[1], outs[1] - outs[0], atol=1e-12)
+    _, br = O.dit_block(inp["x"], w0, bs, inp["text_ctx"], inp["t_mod"], gamma_o=1.0, return_branches=True)
+    np.testing.assert_allclose(outs[1] - outs[0], br["y_ca"], atol=1e-12)
+
+
+def test_block_neutral_tgaa_is_plain():
+    bs, w, inp = _small_block(seed=1)
+    a = O.dit_block(inp["x"], w, bs, inp["text_ctx"], inp["t_mod"])
+    b = O.dit_block(inp["x"], w, bs, inp["text_ctx"], inp["t_mod"], key_scale=np.ones(bs.Lt), gamma_o=1.0)
+    np.testing.assert_array_equal(a, b)
+
+
+def test_block_row_subset_equals_full():
+    bs, w, inp = _small_block(seed=2)
+    full = O.dit_block(inp["x"], w, bs, inp["text_ctx"], inp["t_mod"], gamma_o=1.5)
+    rows = np.array([0, 5, 6, 23])
+    sub = O.dit_block(inp["x"], w, bs, inp["text_ctx"], inp["t_mod"], gamma_o=1.5, rows=rows)
+    np.testing.assert_allclose(sub, full[rows], atol=1e-12)
+
+
+def test_compacted_block_equals_dense_masked():
+    """Sec. 3.3.3: selecting the region gives what a mask that merely removes the
+    other tokens from attention would give, on the selected rows."""
+    bs, w, inp = _small_block(seed=3)
+    mask = synth.exact_count_mask(bs.L, 11, seed=3)
+    idx = O.region_compact(mask)
+    assert list(idx) == sorted(idx) and len(idx) == 11 and (mask[idx] == 1).all()
+    comp = O.dit_block(inp["x"][idx], w, bs, inp["text_ctx"], inp["t_mod"], token_idx=idx, gamma_o=1.2)
+    dense = _torch_block(inp["x"], w, bs, inp["text_ctx"], inp["t_mod"], np.arange(bs.L), None, 1.2,
+                         key_mask=mask.astype(bool))
+    np.testing.assert_allclose(comp, dense[idx], atol=1e-10)
+    # all-ones mask is the unmasked block
+    allm = np.ones(bs.L, np.uint8)
+    np.testing.assert_array_equal(O.region_compact(allm), np.arange(bs.L))
+    a = O.dit_block(inp["x"], w, bs, inp["text_ctx"], inp["t_mod"], token_idx=O.region_compact(allm))
+    b = O.dit_block(inp["x"], w, bs, inp["text_ctx"], inp["t_mod"])
+    np.testing.assert_array_equal(a, b)
+
+
+# ------------------------------------------------------ gather / scatter / blend
+
+def test_gather_scatter_roundtrip():
+    x = synth.normal(8, "g.x", (20, 6))
+    mask = synth.exact_count_mask(20, 7, seed=8)
+    idx = O.region_compact(mask)
+    g = O.gather_rows(x, idx)
+    assert g.shape == (7, 6)
+    for i, n in enumerate(idx):
+        np.testing.assert_array_equal(g[i], x[n])
+    y = O.scatter_rows(np.zeros_like(x), g, idx)
+    np.testing.assert_array_equal(y[idx], x[idx])
+    assert (y[mask == 0] == 0).all()
+    assert O.region_compact(np.zeros(5, np.uint8)).size == 0
+
+
+def test_blend_ends_and_select_form():
+    grid, patch = (2, 3, 4), (1, 2, 2)
+    shp = (3, 2, 6, 8)
+    L = synth.normal(9, "b.L", shp)
+    SL = synth.normal(9, "b.SL", shp)
+    ones, zeros = np.ones(24, np.uint8), np.zeros(24, np.uint8)
+    out = O.region_blend(L, SL, zeros, grid, patch)
+    assert out.dtype == np.float32 and out.tobytes() == SL.tobytes()   # all-reuse: cached latent bit for bit
+    assert O.region_blend(L, SL, ones, grid, patch).tobytes() == L.tobytes()  # all-compute
+    m = synth.exact_count_mask(24, 9, seed=9)
+    out = O.region_blend(L, SL, m, grid, patch)
+    # explicit index loop (select form)
+    for c in range(3):
+        for t in range(2):
+            for y in range(6):
+                for x in range(8):
+                    tok = (t * 3 + y // 2) * 4 + x // 2
+                    assert out[c, t, y, x] == (L if m[tok] else SL)[c, t, y, x]
+
+
+def test_patchify_roundtrip_and_layout():
+    shp, patch = (3, 2, 4, 6), (1, 2, 2)
+    lat = np.arange(np.prod(shp), dtype=np.float64).reshape(shp)
+    tok = O.patchify(lat, patch)
+    assert tok.shape == (2 * 2 * 3, 12)
+    # token (t=1, hg=1, wg=2), feature (c=2, dy=1, dx=0)
+    n = (1 * 2 + 1) * 3 + 2
+    f = (2 * 1 + 0) * 4 + 1 * 2 + 0
+    assert tok[n, f] == lat[2, 1, 1 * 2 + 1, 2 * 2 + 0]
+    np.testing.assert_array_equal(O.unpatchify(tok, shp, patch), lat)
+
+
+# ------------------------------------------------------------- step / schedule
+
+def _tiny_model(seed=0):
+    bs = synth.BlockShape("tiny", D=32, H=2, dh=16, F=48, Lt=4, text_dim=24, grid=(2, 2, 3), C=2)
+    blocks = [synth.stress_block_weights(bs, seed, b) for b in range(2)]
+    gw = synth.glue_weights(bs, seed, std=0.2)
+    text = synth.normal(seed, "text_raw", (bs.Lt, bs.text_dim))
+    ctx = O.text_project(text, gw)
+    t_mods = [synth.normal(seed, f"tm{i}", (6, bs.D), 0.05) for i in range(4)]
+    t_heads = [synth.normal(seed, f"th{i}", (2, bs.D), 0.05) for i in range(4)]
+    return bs, blocks, gw, ctx, t_mods, t_heads
+
+
+def test_step_mask_ends():
+    """All-compute masks give the unmasked step; the step only changes M_see tokens before
+    the blend, and only M_edit tokens after it (Sec. 3.3.2)."""
+    bs, blocks, gw, ctx, t_mods, t_heads = _tiny_model()
+    lat = synth.latent(bs, 0)
+    SL = synth.latent(bs, 0, "SL")
+    ones = np.ones(bs.L, np.uint8)
+    full = O.denoise_step(lat, blocks, gw, bs, ctx, t_mods[0], t_heads[0], -0.25)
+    masked = O.denoise_step(lat, blocks, gw, bs, ctx, t_mods[0], t_heads[0], -0.25, mask_see=ones, mask_edit=ones, SL=SL)
+    np.testing.assert_array_equal(full, masked)
+    assert np.abs(full - lat).max() > 1e-3
+    see = synth.exact_count_mask(bs.L, 7, seed=1)
+    edit = see.copy()
+    edit[O.region_compact(see)[:3]] = 0      # M_edit strictly inside M_see
+    out = O.denoise_step(lat, blocks, gw, bs, ctx, t_mods[0], t_heads[0], -0.25, mask_see=see, mask_edit=edit, SL=SL)
+    Me = O.expand_token_mask(edit, bs.grid, bs.patch, bs.C).astype(bool)
+    np.testing.assert_array_equal(out[~Me], SL.astype(np.float64)[~Me])
+    assert (out[Me] != SL.astype(np.float64)[Me]).all()
+    # all-reuse edit mask returns the cached latent bit for bit
+    out0 = O.denoise_step(lat, blocks, gw, bs, ctx, t_mods[0], t_heads[0], -0.25, mask_see=see,
+                          mask_edit=np.zeros(bs.L, np.uint8), SL=SL)
+    np.testing.assert_array_equal(out0, SL.astype(np.float64))
+
+
+def test_schedule_run_stage1_and_miss():
+    bs, blocks, gw, ctx, t_mods, t_heads = _tiny_model()
+    lat = synth.latent(bs, 0)
+    SL = synth.latent(bs, 0, "SL")
+    sig = [1.0, 0.75, 0.5, 0.25, 0.0]
+    # stage-1-only prefix: after K1 reused steps the latent is the source latent
+    plan = [(1, 1.0, 1.0)]
+    np.testing.assert_array_equal(O.run_schedule(plan, sig, lat, SL, blocks, gw, bs, ctx, t_mods, t_heads), SL)
+    # a miss plan equals N plain steps
+    _, _, plan = O.denoise_schedule(0.1, 0.75, 2)
+    a = O.run_schedule(plan, sig, lat, SL, blocks, gw, bs, ctx, t_mods, t_heads)
+    b = lat
+    for i in range(2):
+        b = O.denoise_step(b, blocks, gw, bs, ctx, t_mods[i], t_heads[i], sig[i + 1] - sig[i])
+    np.testing.assert_array_equal(a, b)
