@@ -1,0 +1,153 @@
+/*
+ * chorus_ops.h -- the individual device operations chorus_dit_block_step is made
+ * of, plus the step glue around the block stack. Exported so that each kernel can
+ * be checked against the CPU oracle and timed on its own. Same conventions as
+ * chorus.h (status codes, dev pointers, stream, bf16 as uint16_t).
+ */
+#ifndef CHORUS_OPS_H
+#define CHORUS_OPS_H
+
+#include "chorus.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ------------------------------------------------------------------------
+ * C = epilogue(A W^T + bias): the QKV / O / FFN projections of the block
+ * (Sec. 2.1; the FLOPs next to attention). bf16 operands, fp32 accumulate on MFMA.
+ *   A    dev [M, K] bf16 row-major (lda = K)
+ *   W    dev [N, K] bf16 row-major (a weight matrix as stored: [out, in])
+ *   bias dev [N] fp32 or NULL
+ *   epilogue  CHORUS_EPI_*:
+ *     BF16       out bf16 [M,N] = acc + bias
+ *     GELU_BF16  out bf16 [M,N] = gelu_tanh(acc + bias)
+ *     F32        out fp32 [M,N] = acc + bias
+ *     RESID      out fp32 [M,N] += (gate0[n] + gate1[n]) * scale * (acc + bias)
+ *                (gate0/gate1 dev [N] fp32, either may be NULL = 0; both NULL = 1):
+ *                the gated residual of the AdaLN block and, with scale = gamma_o and
+ *                no gates, the TGAA output amplification of Eq. 3
+ * K % 64 == 0, N % 8 == 0, M >= 0 arbitrary.
+ * ------------------------------------------------------------------------ */
+#define CHORUS_EPI_BF16 0
+#define CHORUS_EPI_GELU_BF16 1
+#define CHORUS_EPI_F32 2
+#define CHORUS_EPI_RESID 3
+int32_t chorus_gemm_bf16(const uint16_t* A, const uint16_t* W, int64_t M, int32_t N, int32_t K, int32_t epilogue,
+                         void* out, const float* bias, const float* gate0, const float* gate1, float scale,
+                         void* stream);
+
+/* out bf16 [L, D] = LN(x) * (mul_base + mul0 + mul1) + (add0 + add1), LN over D without
+ * affine, eps 1e-6; mul_base = 1 if plus_one else 0; mul1/add1 may be NULL.
+ * AdaLN modulation: mul = scale rows of (table, t_mod), add = shift rows, plus_one = 1.
+ * Affine LayerNorm: mul0 = weight, add0 = bias, plus_one = 0.  x dev [L, D] fp32. */
+int32_t chorus_ln_modulate(const float* x, uint16_t* out, int64_t L, int32_t D, const float* mul0, const float* mul1,
+                           const float* add0, const float* add1, int32_t plus_one, void* stream);
+
+/* RMSNorm over the full width D = H*dh with a learned gain, then (rope != 0) 3-D
+ * RoPE at the token's original grid position, written head-major:
+ *   in  dev bf16, row i at in + i*ld, D values
+ *   out dev bf16 [H, Lpad, dh]; rows L..Lpad-1 are written as zeros
+ *   token_idx dev [L] int32 or NULL (identity) */
+int32_t chorus_qk_norm_rope(const uint16_t* in, int64_t ld, const float* gain, uint16_t* out, int64_t L, int64_t Lpad,
+                            int32_t H, int32_t dh, const int32_t* token_idx, int32_t gT, int32_t gH, int32_t gW,
+                            int32_t rope, void* stream);
+
+/* V [L, D] (row i at in + i*ld) -> Vt [D, Lpad], zero beyond L, with the token order
+ * inside every group of 16 permuted to the attention kernel's operand order:
+ * position 8c + 4u + i of a group holds token 8u + 4c + i (c, u in {0,1}, i < 4).
+ * D % 64 == 0, Lpad % 64 == 0. */
+int32_t chorus_v_transpose(const uint16_t* in, int64_t ld, uint16_t* out, int64_t L, int64_t Lpad, int32_t D,
+                           void* stream);
+
+/* O = softmax(col_scale_j * (Q K^T)/sqrt(dh)) V per head (flash-style, online softmax,
+ * never materialises the logits). Self-attention of the block with col_scale NULL;
+ * cross-attention with TGAA key amplification (Eq. 2) with col_scale = the per-text-
+ * token factor (scaling a key scales its logit column).
+ *   Q   dev bf16 [H, LqPad, dh]     K dev bf16 [H, LkPad, dh]
+ *   Vt  dev bf16 [H*dh, LkPad] in chorus_v_transpose's layout
+ *   O   dev bf16 [Lq, H*dh] token-major
+ *   col_scale dev [Lk] fp32 or NULL
+ * dh in {64,128}; LkPad % 64 == 0, LkPad >= Lk >= 1; rows/cols beyond Lq/Lk are padding
+ * (finite values). */
+int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O,
+                         const float* col_scale, int64_t Lq, int64_t Lk, int64_t LqPad, int64_t LkPad, int32_t H,
+                         int32_t dh, int32_t variant, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Step glue (stand-ins that close the denoising loop around the blocks; the
+ * paper's sampler is DPM++ with default settings, whose coefficients it does not
+ * give, so an Euler update x <- x + dsigma * v is used).
+ * patch_embed: x[i, :] = patch(latent, token_idx[i]) Wp^T + bp for the Ls selected
+ *   tokens; a patch is the (c, dy, dx) values of a 1 x ph x pw cell.
+ * head_update: v = (LN(x)(1 + scale) + shift) Wh^T + bh with (shift, scale) =
+ *   head_table + t_head; latent[patch of token_idx[i]] += dsigma * v[i].
+ * text_project: ctx = gelu_tanh(text W1^T + b1) W2^T + b2 -> bf16 [Lt, D].
+ * ------------------------------------------------------------------------ */
+typedef struct {
+  const uint16_t* w_patch; /* [D, P] bf16, P = C*ph*pw (multiple of 64) */
+  const float* b_patch;    /* [D] */
+  const uint16_t* w_head;  /* [P, D] bf16 */
+  const float* b_head;     /* [P] */
+  const float* head_table; /* [2, D]: shift, scale */
+} chorus_glue_weights;
+
+size_t chorus_glue_workspace_bytes(int32_t D, int32_t P, int64_t Ls);
+int32_t chorus_patch_embed(const float* latent, int32_t C, int32_t T, int32_t Hl, int32_t Wl, int32_t ph, int32_t pw,
+                           const int32_t* token_idx, int64_t Ls, const chorus_glue_weights* gw, int32_t D, float* x,
+                           void* ws, size_t ws_bytes, void* stream);
+int32_t chorus_head_update(float* latent, const float* x, int64_t Ls, const int32_t* token_idx,
+                           const chorus_glue_weights* gw, const float* t_head, float dsigma, int32_t D, int32_t C,
+                           int32_t T, int32_t Hl, int32_t Wl, int32_t ph, int32_t pw, void* ws, size_t ws_bytes,
+                           void* stream);
+size_t chorus_text_project_workspace_bytes(int32_t Lt, int32_t D);
+int32_t chorus_text_project(const uint16_t* text, int32_t Lt, int32_t text_dim, int32_t D, const uint16_t* w1,
+                            const float* b1, const uint16_t* w2, const float* b2, uint16_t* ctx, void* ws,
+                            size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * One computed denoising step (Sec. 3.1: a stage-2 or stage-3 step) in one call:
+ *   x = patch_embed(latent[token_idx]); x = block_b(x) for every block;
+ *   latent[token_idx] += dsigma * head(x); then, when mask_edit is given (stage 2),
+ *   latent = M_edit ? latent : SL (Eq. 6).
+ * Stage 2 passes the compacted list of the visible mask M_see as token_idx (from
+ * chorus_region_compact) and the edit mask M_edit for the fusion; all M_see tokens
+ * go through every layer, only M_edit tokens survive the fusion (Sec. 3.3.2).
+ * Stage 3 passes token_idx = NULL, Ls = all tokens, SL = mask_edit = NULL.
+ *   blocks host array [n_blocks] of structs of device pointers
+ *   latent dev [C, T, Hl, Wl] fp32 in/out;  SL same shape
+ *   t_mod dev [6, D], t_head dev [2, D] fp32: projected timestep embedding of this step
+ * The patch is 1 x ph x pw; the block's token grid must be (T, Hl/ph, Wl/pw).
+ * ------------------------------------------------------------------------ */
+typedef struct {
+  chorus_block_shape block;
+  int32_t C, T, Hl, Wl, ph, pw;
+  int32_t n_blocks;
+} chorus_model_shape;
+
+size_t chorus_denoise_step_workspace_bytes(const chorus_model_shape* model, int64_t Ls);
+int32_t chorus_denoise_step(const chorus_model_shape* model, const chorus_block_weights* blocks,
+                            const chorus_glue_weights* gw, float* latent, const int32_t* token_idx, int64_t Ls,
+                            const uint16_t* text_ctx, const float* t_mod, const float* t_head,
+                            const float* tgaa_key_scale, float gamma_o, float dsigma, const float* SL,
+                            const uint8_t* mask_edit, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Per-kernel timing for benchmarks. When enabled, chorus_dit_block_step brackets
+ * its kernels with HIP events on the caller's stream; chorus_prof_read waits for
+ * them and returns the summed milliseconds and the launch count of one kernel
+ * class since the last reset. Not thread-safe; off by default.
+ * ------------------------------------------------------------------------ */
+#define CHORUS_PROF_SELF_ATTN 0
+#define CHORUS_PROF_CROSS_ATTN 1
+#define CHORUS_PROF_GEMM 2
+#define CHORUS_PROF_NORM 3
+#define CHORUS_PROF_CLASSES 4
+int32_t chorus_prof_enable(int32_t on);
+int32_t chorus_prof_reset(void);
+int32_t chorus_prof_read(int32_t kernel_class, double* total_ms, int32_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHORUS_OPS_H */

@@ -1,0 +1,514 @@
+"""ctypes binding of libchorus.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU (PyTorch is used
+for device memory and streams, nothing else), checks dtype / contiguity, and
+passes raw pointers, sizes and the current HIP stream through the C ABI declared
+in include/chorus.h. Nothing here computes anything, and there is no fallback:
+if the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libchorus.so")
+_lib = None
+
+OK, E_ARG, E_SHAPE, E_WORKSPACE, E_HIP = 0, -1, -2, -3, -4
+_ERR = {E_ARG: "CHORUS_E_ARG", E_SHAPE: "CHORUS_E_SHAPE", E_WORKSPACE: "CHORUS_E_WORKSPACE", E_HIP: "CHORUS_E_HIP"}
+
+
+class ChorusError(RuntimeError):
+    def __init__(self, fn, status, hip=0):
+        self.status = status
+        super().__init__(f"{fn} failed: {_ERR.get(status, status)}" + (f" (hipError {hip})" if status == E_HIP else ""))
+
+
+class LookupResult(C.Structure):
+    _fields_ = [("index", C.c_int32), ("score", C.c_float), ("hit", C.c_int32)]
+
+
+class SchedParams(C.Structure):
+    _fields_ = [("a1", C.c_double), ("b1", C.c_double), ("a2", C.c_double), ("b2", C.c_double), ("r3", C.c_int32),
+                ("Gamma_k", C.c_double), ("Gamma_o", C.c_double), ("lam", C.c_double), ("gamma_override", C.c_double)]
+
+
+class StepPlan(C.Structure):
+    _fields_ = [("stage", C.c_int32), ("gamma_k", C.c_float), ("gamma_o", C.c_float)]
+
+
+class BlockShape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("D", "H", "dh", "F", "Lt", "gT", "gH", "gW")]
+
+
+_W_FIELDS = ["mod_table", "w_qkv", "b_qkv", "g_q", "g_k", "w_o", "b_o", "ln3_w", "ln3_b", "w_cq", "b_cq", "w_ckv",
+             "b_ckv", "g_cq", "g_ck", "w_co", "b_co", "w_1", "b_1", "w_2", "b_2"]
+
+
+class BlockWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _W_FIELDS]
+
+
+class GlueWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("w_patch", "b_patch", "w_head", "b_head", "head_table")]
+
+
+class ModelShape(C.Structure):
+    _fields_ = [("block", BlockShape)] + [(n, C.c_int32) for n in ("C", "T", "Hl", "Wl", "ph", "pw", "n_blocks")]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Loads the shared library (once). Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python -m paper_2604_04451_amd.build` "
+                          "(there is no CPU fallback for the HIP path)")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, i64, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
+    sigs = {
+        "chorus_version": (i32, []),
+        "chorus_last_hip_error": (i32, []),
+        "chorus_cache_lookup_workspace_bytes": (sz, [i64]),
+        "chorus_cache_lookup": (i32, [vp, i64, i32, vp, f32, vp, vp, sz, vp]),
+        "chorus_denoise_schedule": (i32, [f32, f32, i32, C.POINTER(SchedParams), C.POINTER(i32), C.POINTER(i32),
+                                          C.POINTER(StepPlan)]),
+        "chorus_dit_block_workspace_bytes": (sz, [C.POINTER(BlockShape), i64]),
+        "chorus_dit_block_step": (i32, [C.POINTER(BlockShape), C.POINTER(BlockWeights), vp, i64, vp, vp, vp, vp, f32,
+                                        vp, sz, vp]),
+        "chorus_region_blend": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
+        "chorus_region_compact_workspace_bytes": (sz, [i64]),
+        "chorus_region_compact": (i32, [vp, i64, vp, vp, vp, sz, vp]),
+        "chorus_region_gather_rows": (i32, [vp, vp, vp, i64, i64, vp]),
+        "chorus_region_scatter_rows": (i32, [vp, vp, vp, i64, i64, vp]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)  # AttributeError if the header and the library disagree
+        fn.restype = res
+        fn.argtypes = args
+    lib._sigs = sigs
+    _lib = lib
+    _bind_ops(lib)
+    return lib
+
+
+def _bind_ops(lib):
+    """Signatures of include/chorus_ops.h."""
+    vp, i32, i64, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
+    GW, MS = C.POINTER(GlueWeights), C.POINTER(ModelShape)
+    ops = {
+        "chorus_gemm_bf16": (i32, [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, f32, vp]),
+        "chorus_ln_modulate": (i32, [vp, vp, i64, i32, vp, vp, vp, vp, i32, vp]),
+        "chorus_qk_norm_rope": (i32, [vp, i64, vp, vp, i64, i64, i32, i32, vp, i32, i32, i32, i32, vp]),
+        "chorus_v_transpose": (i32, [vp, i64, vp, i64, i64, i32, vp]),
+        "chorus_attention": (i32, [vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, i32, i32, vp]),
+        "chorus_glue_workspace_bytes": (sz, [i32, i32, i64]),
+        "chorus_patch_embed": (i32, [vp, i32, i32, i32, i32, i32, i32, vp, i64, GW, i32, vp, vp, sz, vp]),
+        "chorus_head_update": (i32, [vp, vp, i64, vp, GW, vp, f32, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]),
+        "chorus_text_project_workspace_bytes": (sz, [i32, i32]),
+        "chorus_text_project": (i32, [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]),
+        "chorus_denoise_step_workspace_bytes": (sz, [MS, i64]),
+        "chorus_denoise_step": (i32, [MS, C.POINTER(BlockWeights), GW, vp, vp, i64, vp, vp, vp, vp, f32, f32, vp, vp,
+                                      vp, sz, vp]),
+        "chorus_prof_enable": (i32, [i32]),
+        "chorus_prof_reset": (i32, []),
+        "chorus_prof_read": (i32, [i32, C.POINTER(C.c_double), C.POINTER(i32)]),
+    }
+    for name, (res, args) in ops.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    lib._sigs.update(ops)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _p(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _chk(t, dtype, name, shape=None):
+    if t is None:
+        return
+    if not t.is_cuda:
+        raise TypeError(f"{name}: device tensor required")
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise TypeError(f"{name}: must be contiguous")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise TypeError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+
+
+def _status(fn, st):
+    if st != OK:
+        raise ChorusError(fn, st, load().chorus_last_hip_error())
+
+
+def _ws(nbytes, device):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+# ---------------------------------------------------------------- lookup
+
+def chorus_cache_lookup(cache_emb, query, tau, out=None, ws=None):
+    """Returns a device int32 tensor [3] viewing (index, score bits, hit); use lookup_result() to read it."""
+    lib = load()
+    _chk(cache_emb, torch.float32, "cache_emb")
+    _chk(query, torch.float32, "query")
+    N, d = cache_emb.shape
+    if query.numel() != d:
+        raise TypeError("query: wrong length")
+    if out is None:
+        out = torch.empty(3, dtype=torch.int32, device=query.device)
+    need = lib.chorus_cache_lookup_workspace_bytes(N)
+    if ws is None:
+        ws = _ws(need, query.device)
+    _status("chorus_cache_lookup", lib.chorus_cache_lookup(_p(cache_emb) if N else C.c_void_p(0), N, d, _p(query),
+                                                           float(tau), _p(out), _p(ws), ws.numel(), _stream()))
+    return out
+
+
+def lookup_result(out):
+    """Host read-back of a lookup result tensor: (index, score, hit)."""
+    h = out.cpu()
+    return int(h[0]), float(h[1:2].view(torch.float32)[0]), bool(h[2])
+
+
+# -------------------------------------------------------------- schedule
+
+def chorus_denoise_schedule(m, tau, N, params=None):
+    lib = load()
+    sp = None
+    if params is not None:
+        d = dict(a1=0.25, b1=0.25, a2=0.25, b2=0.25, r3=1, Gamma_k=1.5, Gamma_o=1.5, lam=0.5, gamma_override=0.0)
+        d.update(params)
+        sp = SchedParams(**d)
+    plan = (StepPlan * max(N, 1))()
+    k1, k2 = C.c_int32(0), C.c_int32(0)
+    _status("chorus_denoise_schedule",
+            lib.chorus_denoise_schedule(float(m), float(tau), int(N), C.byref(sp) if sp is not None else None,
+                                        C.byref(k1), C.byref(k2), plan))
+    return k1.value, k2.value, [(plan[i].stage, plan[i].gamma_k, plan[i].gamma_o) for i in range(N)]
+
+
+# ---------------------------------------------------------------- region
+
+def chorus_region_compact(mask, idx_out=None, count_out=None, ws=None):
+    lib = load()
+    _chk(mask, torch.uint8, "mask")
+    L = mask.numel()
+    if idx_out is None:
+        idx_out = torch.empty(max(L, 1), dtype=torch.int32, device=mask.device)
+    if count_out is None:
+        count_out = torch.empty(1, dtype=torch.int32, device=mask.device)
+    if ws is None:
+        ws = _ws(lib.chorus_region_compact_workspace_bytes(L), mask.device)
+    _status("chorus_region_compact",
+            lib.chorus_region_compact(_p(mask), L, _p(idx_out), _p(count_out), _p(ws), ws.numel(), _stream()))
+    return idx_out, count_out
+
+
+def chorus_region_gather_rows(dst, src, idx, Ls=None):
+    lib = load()
+    _chk(idx, torch.int32, "idx")
+    Ls = idx.numel() if Ls is None else Ls
+    row_bytes = src.shape[-1] * src.element_size()
+    assert dst.is_contiguous() and src.is_contiguous() and dst.dtype == src.dtype and dst.shape[-1] == src.shape[-1]
+    assert dst.shape[0] >= Ls
+    _status("chorus_region_gather_rows", lib.chorus_region_gather_rows(_p(dst), _p(src), _p(idx), Ls, row_bytes, _stream()))
+    return dst
+
+
+def chorus_region_scatter_rows(dst, src, idx, Ls=None):
+    lib = load()
+    _chk(idx, torch.int32, "idx")
+    Ls = idx.numel() if Ls is None else Ls
+    row_bytes = src.shape[-1] * src.element_size()
+    assert dst.is_contiguous() and src.is_contiguous() and dst.dtype == src.dtype and dst.shape[-1] == src.shape[-1]
+    assert src.shape[0] >= Ls
+    _status("chorus_region_scatter_rows", lib.chorus_region_scatter_rows(_p(dst), _p(src), _p(idx), Ls, row_bytes, _stream()))
+    return dst
+
+
+def chorus_region_blend(out, L, SL, mask_edit, patch_hw=(2, 2)):
+    lib = load()
+    _chk(L, torch.float32, "L")
+    _chk(SL, torch.float32, "SL", L.shape)
+    _chk(out, torch.float32, "out", L.shape)
+    _chk(mask_edit, torch.uint8, "mask_edit")
+    Cc, T, H, W = L.shape
+    ph, pw = patch_hw
+    if mask_edit.numel() != T * (H // ph) * (W // pw):
+        raise TypeError("mask_edit: wrong size")
+    _status("chorus_region_blend", lib.chorus_region_blend(_p(out), _p(L), _p(SL), _p(mask_edit), Cc, T, H, W, ph, pw, _stream()))
+    return out
+
+
+# ----------------------------------------------------------------- block
+
+@dataclass
+class DeviceBlock:
+    """Device copies of one block's weights plus the C struct that points at them."""
+    tensors: dict
+    cstruct: BlockWeights
+
+
+def make_block_shape(D, H, dh, F, Lt, grid):
+    return BlockShape(D, H, dh, F, Lt, grid[0], grid[1], grid[2])
+
+
+def upload_block_weights(w: dict, device="cuda") -> DeviceBlock:
+    """Copies numpy weights to the device: matrices as bf16 (values must already be
+    bf16-representable), vectors and tables as fp32."""
+    import numpy as np
+    tens = {}
+    for name in _W_FIELDS:
+        a = w[name]
+        t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+        if name.startswith("w_"):
+            tb = t.to(torch.bfloat16)
+            if not torch.equal(tb.to(torch.float32), t):
+                raise ValueError(f"{name}: values are not bf16-representable")
+            t = tb
+        tens[name] = t.to(device).contiguous()
+    cs = BlockWeights(**{n: tens[n].data_ptr() for n in _W_FIELDS})
+    return DeviceBlock(tens, cs)
+
+
+def chorus_dit_block_workspace_bytes(shape: BlockShape, Ls: int) -> int:
+    return load().chorus_dit_block_workspace_bytes(C.byref(shape), int(Ls))
+
+
+def chorus_dit_block_step(shape: BlockShape, weights: DeviceBlock, x, Ls, token_idx, text_ctx, t_mod,
+                          tgaa_key_scale=None, gamma_o=1.0, ws=None):
+    lib = load()
+    _chk(x, torch.float32, "x")
+    _chk(token_idx, torch.int32, "token_idx")
+    _chk(text_ctx, torch.bfloat16, "text_ctx", (shape.Lt, shape.D))
+    _chk(t_mod, torch.float32, "t_mod", (6, shape.D))
+    _chk(tgaa_key_scale, torch.float32, "tgaa_key_scale", (shape.Lt,))
+    if x.shape[-1] != shape.D or x.shape[0] < Ls:
+        raise TypeError("x: wrong shape")
+    if ws is None:
+        ws = _ws(lib.chorus_dit_block_workspace_bytes(C.byref(shape), int(Ls)), x.device)
+    _status("chorus_dit_block_step",
+            lib.chorus_dit_block_step(C.byref(shape), C.byref(weights.cstruct), _p(x), int(Ls), _p(token_idx),
+                                      _p(text_ctx), _p(t_mod), _p(tgaa_key_scale), float(gamma_o), _p(ws), ws.numel(),
+                                      _stream()))
+    return x
+
+
+# ------------------------------------------------------- single operations
+
+EPI_BF16, EPI_GELU_BF16, EPI_F32, EPI_RESID = 0, 1, 2, 3
+PROF_SELF_ATTN, PROF_CROSS_ATTN, PROF_GEMM, PROF_NORM = 0, 1, 2, 3
+
+
+def chorus_gemm_bf16(A, W, epilogue, out, bias=None, gate0=None, gate1=None, scale=1.0, M=None):
+    lib = load()
+    _chk(A, torch.bfloat16, "A")
+    _chk(W, torch.bfloat16, "W")
+    M = A.shape[0] if M is None else M
+    N, K = W.shape
+    if A.shape[1] != K:
+        raise TypeError("A/W inner dimensions differ")
+    want = torch.float32 if epilogue in (EPI_F32, EPI_RESID) else torch.bfloat16
+    _chk(out, want, "out")
+    if out.shape[-1] != N or out.shape[0] < M:
+        raise TypeError("out: wrong shape")
+    for n, t in (("bias", bias), ("gate0", gate0), ("gate1", gate1)):
+        _chk(t, torch.float32, n, (N,))
+    _status("chorus_gemm_bf16", lib.chorus_gemm_bf16(_p(A), _p(W), M, N, K, epilogue, _p(out), _p(bias), _p(gate0),
+                                                     _p(gate1), float(scale), _stream()))
+    return out
+
+
+def chorus_ln_modulate(x, out, mul0, mul1, add0, add1, plus_one):
+    lib = load()
+    _chk(x, torch.float32, "x")
+    _chk(out, torch.bfloat16, "out", x.shape)
+    L, D = x.shape
+    for n, t in (("mul0", mul0), ("mul1", mul1), ("add0", add0), ("add1", add1)):
+        _chk(t, torch.float32, n, (D,))
+    _status("chorus_ln_modulate", lib.chorus_ln_modulate(_p(x), _p(out), L, D, _p(mul0), _p(mul1), _p(add0), _p(add1),
+                                                         int(plus_one), _stream()))
+    return out
+
+
+def chorus_qk_norm_rope(inp, col0, gain, out, L, H, dh, token_idx, grid, rope):
+    """inp: bf16 [L, ld]; the D = H*dh columns starting at col0 are normalised."""
+    lib = load()
+    _chk(inp, torch.bfloat16, "inp")
+    _chk(out, torch.bfloat16, "out")
+    _chk(gain, torch.float32, "gain", (H * dh,))
+    _chk(token_idx, torch.int32, "token_idx")
+    ld = inp.shape[1]
+    Lpad = out.shape[1]
+    if tuple(out.shape) != (H, Lpad, dh) or col0 + H * dh > ld or inp.shape[0] < L:
+        raise TypeError("shape mismatch")
+    ptr = C.c_void_p(inp.data_ptr() + 2 * col0)
+    _status("chorus_qk_norm_rope", lib.chorus_qk_norm_rope(ptr, ld, _p(gain), _p(out), L, Lpad, H, dh, _p(token_idx),
+                                                           grid[0], grid[1], grid[2], int(rope), _stream()))
+    return out
+
+
+def chorus_v_transpose(inp, col0, out, L):
+    lib = load()
+    _chk(inp, torch.bfloat16, "inp")
+    _chk(out, torch.bfloat16, "out")
+    D, Lpad = out.shape
+    ld = inp.shape[1]
+    if col0 + D > ld or inp.shape[0] < L:
+        raise TypeError("shape mismatch")
+    ptr = C.c_void_p(inp.data_ptr() + 2 * col0)
+    _status("chorus_v_transpose", lib.chorus_v_transpose(ptr, ld, _p(out), L, Lpad, D, _stream()))
+    return out
+
+
+def chorus_attention(Q, K, Vt, O, col_scale, Lq, Lk, variant=0):
+    lib = load()
+    for n, t in (("Q", Q), ("K", K), ("Vt", Vt), ("O", O)):
+        _chk(t, torch.bfloat16, n)
+    H, LqPad, dh = Q.shape
+    LkPad = K.shape[1]
+    if K.shape[0] != H or K.shape[2] != dh or tuple(Vt.shape) != (H * dh, LkPad) or O.shape[1] != H * dh or O.shape[0] < Lq:
+        raise TypeError("shape mismatch")
+    _chk(col_scale, torch.float32, "col_scale")
+    if col_scale is not None and col_scale.numel() < Lk:
+        raise TypeError("col_scale too short")
+    _status("chorus_attention", lib.chorus_attention(_p(Q), _p(K), _p(Vt), _p(O), _p(col_scale), Lq, Lk, LqPad, LkPad,
+                                                     H, dh, int(variant), _stream()))
+    return O
+
+
+# ------------------------------------------------------------- step glue
+
+@dataclass
+class DeviceGlue:
+    tensors: dict
+    cstruct: GlueWeights
+
+
+def upload_glue_weights(gw: dict, device="cuda") -> DeviceGlue:
+    import numpy as np
+    tens = {}
+    for name, a in gw.items():
+        t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+        if name.startswith("w_"):
+            tb = t.to(torch.bfloat16)
+            if not torch.equal(tb.to(torch.float32), t):
+                raise ValueError(f"{name}: values are not bf16-representable")
+            t = tb
+        tens[name] = t.to(device).contiguous()
+    cs = GlueWeights(**{n: tens[n].data_ptr() for n in ("w_patch", "b_patch", "w_head", "b_head", "head_table")})
+    return DeviceGlue(tens, cs)
+
+
+def make_model_shape(bshape: BlockShape, latent_shape, patch_hw=(2, 2), n_blocks=1):
+    Cc, T, Hl, Wl = latent_shape
+    return ModelShape(bshape, Cc, T, Hl, Wl, patch_hw[0], patch_hw[1], n_blocks)
+
+
+def chorus_text_project(text, glue: DeviceGlue, ctx=None):
+    lib = load()
+    _chk(text, torch.bfloat16, "text")
+    Lt, td = text.shape
+    D = glue.tensors["w_text1"].shape[0]
+    if ctx is None:
+        ctx = torch.empty(Lt, D, dtype=torch.bfloat16, device=text.device)
+    ws = _ws(lib.chorus_text_project_workspace_bytes(Lt, D), text.device)
+    t = glue.tensors
+    _status("chorus_text_project", lib.chorus_text_project(_p(text), Lt, td, D, _p(t["w_text1"]), _p(t["b_text1"]),
+                                                           _p(t["w_text2"]), _p(t["b_text2"]), _p(ctx), _p(ws),
+                                                           ws.numel(), _stream()))
+    return ctx
+
+
+def chorus_patch_embed(latent, token_idx, Ls, glue: DeviceGlue, D, x, patch_hw=(2, 2), ws=None):
+    lib = load()
+    _chk(latent, torch.float32, "latent")
+    _chk(token_idx, torch.int32, "token_idx")
+    _chk(x, torch.float32, "x")
+    Cc, T, Hl, Wl = latent.shape
+    P = Cc * patch_hw[0] * patch_hw[1]
+    if ws is None:
+        ws = _ws(lib.chorus_glue_workspace_bytes(D, P, Ls), latent.device)
+    _status("chorus_patch_embed", lib.chorus_patch_embed(_p(latent), Cc, T, Hl, Wl, patch_hw[0], patch_hw[1],
+                                                         _p(token_idx), Ls, C.byref(glue.cstruct), D, _p(x), _p(ws),
+                                                         ws.numel(), _stream()))
+    return x
+
+
+def chorus_head_update(latent, x, Ls, token_idx, glue: DeviceGlue, t_head, dsigma, patch_hw=(2, 2), ws=None):
+    lib = load()
+    _chk(latent, torch.float32, "latent")
+    _chk(x, torch.float32, "x")
+    _chk(token_idx, torch.int32, "token_idx")
+    D = x.shape[1]
+    _chk(t_head, torch.float32, "t_head", (2, D))
+    Cc, T, Hl, Wl = latent.shape
+    P = Cc * patch_hw[0] * patch_hw[1]
+    if ws is None:
+        ws = _ws(lib.chorus_glue_workspace_bytes(D, P, Ls), latent.device)
+    _status("chorus_head_update", lib.chorus_head_update(_p(latent), _p(x), Ls, _p(token_idx), C.byref(glue.cstruct),
+                                                         _p(t_head), float(dsigma), D, Cc, T, Hl, Wl, patch_hw[0],
+                                                         patch_hw[1], _p(ws), ws.numel(), _stream()))
+    return latent
+
+
+def block_array(blocks):
+    """Host array of chorus_block_weights structs from a list of DeviceBlock."""
+    arr = (BlockWeights * max(len(blocks), 1))()
+    for i, b in enumerate(blocks):
+        arr[i] = b.cstruct
+    return arr
+
+
+def chorus_denoise_step_workspace_bytes(model: ModelShape, Ls: int) -> int:
+    return load().chorus_denoise_step_workspace_bytes(C.byref(model), int(Ls))
+
+
+def chorus_denoise_step(model: ModelShape, blocks_arr, glue: DeviceGlue, latent, token_idx, Ls, text_ctx, t_mod, t_head,
+                        tgaa_key_scale=None, gamma_o=1.0, dsigma=0.0, SL=None, mask_edit=None, ws=None):
+    lib = load()
+    D = model.block.D
+    _chk(latent, torch.float32, "latent", (model.C, model.T, model.Hl, model.Wl))
+    _chk(SL, torch.float32, "SL", latent.shape)
+    _chk(token_idx, torch.int32, "token_idx")
+    _chk(text_ctx, torch.bfloat16, "text_ctx", (model.block.Lt, D))
+    _chk(t_mod, torch.float32, "t_mod", (6, D))
+    _chk(t_head, torch.float32, "t_head", (2, D))
+    _chk(tgaa_key_scale, torch.float32, "tgaa_key_scale", (model.block.Lt,))
+    _chk(mask_edit, torch.uint8, "mask_edit")
+    if ws is None:
+        ws = _ws(lib.chorus_denoise_step_workspace_bytes(C.byref(model), int(Ls)), latent.device)
+    _status("chorus_denoise_step",
+            lib.chorus_denoise_step(C.byref(model), blocks_arr, C.byref(glue.cstruct), _p(latent), _p(token_idx), int(Ls),
+                                    _p(text_ctx), _p(t_mod), _p(t_head), _p(tgaa_key_scale), float(gamma_o),
+                                    float(dsigma), _p(SL), _p(mask_edit), _p(ws), ws.numel(), _stream()))
+    return latent
+
+
+def prof_enable(on=True):
+    load().chorus_prof_enable(1 if on else 0)
+
+
+def prof_reset():
+    load().chorus_prof_reset()
+
+
+def prof_read(kernel_class):
+    ms, n = C.c_double(0), C.c_int32(0)
+    _status("chorus_prof_read", load().chorus_prof_read(kernel_class, C.byref(ms), C.byref(n)))
+    return ms.value, n.value

@@ -1,0 +1,84 @@
+// Shared host/device helpers of the Chorus HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "chorus.h"
+
+namespace chorus {
+
+// last HIP error seen by this library on this thread
+extern thread_local int32_t g_last_hip_error;
+
+inline int32_t hip_fail(hipError_t e) {
+  g_last_hip_error = (int32_t)e;
+  return CHORUS_E_HIP;
+}
+
+#define CHORUS_HIP(expr)                                   \
+  do {                                                     \
+    hipError_t e__ = (expr);                               \
+    if (e__ != hipSuccess) return ::chorus::hip_fail(e__); \
+  } while (0)
+
+#define CHORUS_LAUNCH_CHECK() CHORUS_HIP(hipGetLastError())
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+typedef __bf16 bf16_t;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+// plain 16-byte register vector (HIP's uint4 is a struct and keeps arrays of it out of registers)
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+
+// streaming (non-temporal) 16-byte accesses for data touched once
+__device__ __forceinline__ float4 ld_stream_f4(const float4* p) {
+  f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void st_stream_f4(float4* p, float4 a) {
+  f32x4 v = {a.x, a.y, a.z, a.w};
+  __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p));
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round to nearest even; the compiler emits the hardware convert on gfx950
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  bf16_t h = (bf16_t)f;
+  return __builtin_bit_cast(uint16_t, h);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Workgroup id -> logical tile id such that the workgroups that land on one XCD
+// (hardware deals consecutive ids round-robin over the 8 XCDs) cover one
+// contiguous range of logical ids and so share operands in that XCD's L2.
+__device__ __forceinline__ int xcd_remap(int bid, int nblocks) {
+  const int NX = 8;
+  int xcd = bid % NX, local = bid / NX;
+  int q = nblocks / NX, r = nblocks % NX;
+  // XCD x owns q+1 ids if x < r else q ids
+  int start = xcd * q + (xcd < r ? xcd : r);
+  return start + local;
+}
+
+}  // namespace chorus

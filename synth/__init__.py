@@ -139,15 +139,16 @@ def block_weights(shape: BlockShape, seed: int = 0, block: int = 0, std: float =
 
 
 def stress_block_weights(shape: BlockShape, seed: int = 0, block: int = 0) -> dict:
-    """Variant that makes every branch matter: non-zero biases, q/k gains of 4
-    (peaked attention logits), gates ~N(1, 0.1), non-trivial norm affine."""
+    """Variant that makes every branch matter: non-zero biases, q/k gains of 2
+    (attention logits with std ~4, i.e. peaked rows), gates ~N(1, 0.1), non-trivial
+    norm affine."""
     w = block_weights(shape, seed, block)
     D, F = shape.D, shape.F
     p = f"stress{block}."
     for b, n in (("b_qkv", 3 * D), ("b_o", D), ("b_cq", D), ("b_ckv", 2 * D), ("b_co", D), ("b_1", F), ("b_2", D)):
         w[b] = normal(seed, p + b, (n,), 0.05)
     for g in ("g_q", "g_k", "g_cq", "g_ck"):
-        w[g] = normal(seed, p + g, (D,), 0.2, 4.0)
+        w[g] = normal(seed, p + g, (D,), 0.1, 2.0)
     w["ln3_w"] = normal(seed, p + "ln3_w", (D,), 0.1, 1.0)
     w["ln3_b"] = normal(seed, p + "ln3_b", (D,), 0.1)
     mt = normal(seed, p + "mod_table", (6, D), 0.1)

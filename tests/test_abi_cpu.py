@@ -1,0 +1,94 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every function the
+headers declare, validates arguments before touching the GPU, and its host-only
+schedule agrees with the oracle. No kernel is launched here."""
+import ctypes as C
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import chorus_oracle as O
+import paper_2604_04451_amd as P
+from paper_2604_04451_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    names = set()
+    for h in ("chorus.h", "chorus_ops.h"):
+        src = open(os.path.join(ROOT, "include", h)).read()
+        src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+        names |= set(re.findall(r"\b(chorus_[a-z0-9_]+)\s*\(", src))
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = P.load()
+    decl = _declared()
+    assert {"chorus_cache_lookup", "chorus_dit_block_step", "chorus_region_blend", "chorus_denoise_schedule"} <= decl
+    for name in sorted(decl):
+        assert hasattr(lib, name), f"{name} declared in include/ but not exported"
+    # and the binding knows a signature for each
+    assert decl <= set(lib._sigs), sorted(decl - set(lib._sigs))
+    assert lib.chorus_version() >= 100
+
+
+@pytest.mark.parametrize("N", [1, 4, 5, 8, 50])
+@pytest.mark.parametrize("tau", [0.65, 0.75])
+def test_schedule_matches_oracle(N, tau):
+    for params in (None, dict(gamma_override=1.5), dict(a1=0.1, b1=0.5, a2=0.2, b2=0.3, r3=2, Gamma_k=2.0, lam=0.9)):
+        for m in list(np.linspace(0.0, 1.0, 101)) + [float("nan"), -math.inf, 1.5]:
+            mf = float(np.float32(m))
+            k1, k2, plan = P.chorus_denoise_schedule(mf, tau, N, params)
+            ok1, ok2, oplan = O.denoise_schedule(mf, float(np.float32(tau)), N, params)
+            assert (k1, k2) == (ok1, ok2), (m, tau, N, params)
+            for (s, gk, go), (os_, ogk, ogo) in zip(plan, oplan):
+                assert s == os_
+                assert gk == np.float32(ogk) and go == np.float32(ogo)
+
+
+def test_argument_validation_returns_codes():
+    lib = P.load()
+    null = C.c_void_p(0)
+    out = (C.c_int32 * 3)()
+    # lookup: d not a multiple of 4; missing workspace; negative N
+    assert lib.chorus_cache_lookup(C.c_void_p(16), 4, 6, C.c_void_p(16), 0.5, out, C.c_void_p(16), 1024, null) == B.E_SHAPE
+    assert lib.chorus_cache_lookup(C.c_void_p(16), 4, 8, C.c_void_p(16), 0.5, out, null, 0, null) == B.E_WORKSPACE
+    assert lib.chorus_cache_lookup(C.c_void_p(16), -1, 8, C.c_void_p(16), 0.5, out, C.c_void_p(16), 1024, null) == B.E_ARG
+    assert lib.chorus_cache_lookup(C.c_void_p(8), 4, 8, C.c_void_p(16), 0.5, out, C.c_void_p(16), 1024, null) == B.E_ARG
+    # schedule
+    assert lib.chorus_denoise_schedule(0.9, 0.75, -1, None, None, None, None) == B.E_ARG
+    assert lib.chorus_denoise_schedule(0.9, 0.75, 0, None, None, None, None) == B.OK
+    # blend: H not divisible by the patch
+    assert lib.chorus_region_blend(C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), 1, 1, 3, 4, 2, 2, null) == B.E_SHAPE
+    assert lib.chorus_region_blend(null, null, null, null, 0, 1, 4, 4, 2, 2, null) == B.OK   # empty tensor
+    # block: unsupported head dim, H*dh != D, missing workspace
+    bad = B.BlockShape(256, 4, 32, 1024, 16, 4, 8, 8)
+    w = B.BlockWeights()
+    assert lib.chorus_dit_block_step(C.byref(bad), C.byref(w), C.c_void_p(16), 4, null, C.c_void_p(16), C.c_void_p(16), null, 1.0, C.c_void_p(16), 1 << 20, null) == B.E_SHAPE
+    bad2 = B.BlockShape(256, 3, 64, 1024, 16, 4, 8, 8)
+    assert lib.chorus_dit_block_workspace_bytes(C.byref(bad2), 10) == 0
+    good = B.BlockShape(256, 4, 64, 1024, 16, 4, 8, 8)
+    need = lib.chorus_dit_block_workspace_bytes(C.byref(good), 256)
+    assert need > 0
+    assert lib.chorus_dit_block_step(C.byref(good), C.byref(w), C.c_void_p(16), 256, null, C.c_void_p(16), C.c_void_p(16), null, 1.0, C.c_void_p(256), need - 1, null) == B.E_WORKSPACE
+    assert lib.chorus_dit_block_step(C.byref(good), C.byref(w), C.c_void_p(16), 0, null, C.c_void_p(16), C.c_void_p(16), null, 1.0, null, 0, null) == B.OK  # Ls == 0
+    # gemm: K not a multiple of 64
+    assert lib.chorus_gemm_bf16(C.c_void_p(16), C.c_void_p(16), 8, 64, 100, 0, C.c_void_p(16), null, null, null, 1.0, null) == B.E_SHAPE
+    # attention: head dim, pad
+    assert lib.chorus_attention(C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), null, 8, 8, 64, 64, 2, 96, 0, null) == B.E_SHAPE
+    assert lib.chorus_attention(C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), null, 8, 8, 64, 60, 2, 64, 0, null) == B.E_SHAPE
+    assert lib.chorus_attention(C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), null, 8, 0, 64, 64, 2, 64, 0, null) == B.E_SHAPE
+
+
+def test_workspace_sizes_scale_with_rows():
+    lib = P.load()
+    sh = B.BlockShape(1536, 12, 128, 8960, 512, 21, 30, 52)
+    a = lib.chorus_dit_block_workspace_bytes(C.byref(sh), 13104)
+    b = lib.chorus_dit_block_workspace_bytes(C.byref(sh), 32760)
+    assert 0 < a < b < 3 * (1 << 30)
+    assert lib.chorus_cache_lookup_workspace_bytes(4096) >= 4096 * 4
+    assert lib.chorus_region_compact_workspace_bytes(75600) >= 4 * ((75600 + 4095) // 4096)

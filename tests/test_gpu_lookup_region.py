@@ -1,0 +1,187 @@
+"""GPU parity: cache lookup, compaction, gather/scatter and latent fusion against the
+CPU oracle, through the C ABI. Integer / bit-copy results must match exactly."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import chorus_oracle as O
+import paper_2604_04451_amd as P
+from gpu_util import DEV, dev_f32, host
+
+pytestmark = pytest.mark.gpu
+
+
+def _lookup(cache, q, tau=0.75):
+    out = P.chorus_cache_lookup(dev_f32(cache).reshape(cache.shape), dev_f32(q), tau)
+    return P.lookup_result(out)
+
+
+def _check_lookup(cache, q, tau=0.75):
+    j, m, hit = _lookup(cache, q, tau)
+    s = O.cosine_scores(cache, q)
+    oj, om, ohit = O.cache_lookup(cache, q, tau)
+    d = cache.shape[1]
+    tol = 4e-7 * max(8.0, math.sqrt(d))  # fp32 dot of d unit-scale products against fp64
+    if s.size and np.isfinite(om):
+        order = np.sort(s)[::-1]
+        gap = order[0] - order[1] if s.size > 1 else np.inf
+        if gap > 2 * tol:
+            assert j == oj, (j, oj, gap)       # the index is decided: must match bit-exactly
+        else:
+            assert s[j] >= om - 2 * tol        # a numerical tie: any of the tied rows is valid
+        assert abs(m - s[j]) <= tol
+        if abs(om - tau) > tol:
+            assert hit == ohit
+    else:
+        assert (j, hit) == (oj, ohit) and m == om
+    return j, m, hit
+
+
+def test_lookup_c1_and_edges():
+    print("[case] lookup c1", flush=True)
+    cache = synth.cache_embeddings(8, 256, seed=0)
+    q = synth.cache_query(cache, seed=0, near=5)
+    j, m, hit = _check_lookup(cache, q)
+    assert j == 5 and hit
+    # miss
+    j, m, hit = _check_lookup(cache, synth.cache_query(cache, seed=0))
+    assert not hit
+    # empty cache (cold start)
+    assert _lookup(np.zeros((0, 256), np.float32), q) == (-1, -math.inf, False)
+    # single entry, zero-norm row, zero-norm query
+    _check_lookup(cache[:1], q)
+    z = cache.copy()
+    z[5] = 0
+    _check_lookup(z, q)
+    j, m, hit = _check_lookup(cache, np.zeros(256, np.float32))
+    assert m == -math.inf and not hit
+    # duplicates: lowest index, and bit-identical scores for identical rows
+    dup = synth.cache_embeddings(64, 512, seed=3)
+    dup[40] = dup[7]
+    dup[63] = dup[7]
+    j, m, hit = _check_lookup(dup, dup[7])
+    assert j == 7
+    # threshold is inclusive
+    e = np.zeros((2, 4), np.float32)
+    e[0, 0] = 1
+    e[1, 1] = 1
+    assert _lookup(e, e[0], 1.0) == (0, 1.0, True)
+
+
+@pytest.mark.parametrize("N,d", [(1000, 768), (257, 4), (33, 2052), (4096, 4096)])
+def test_lookup_shapes(N, d):
+    print(f"[case] lookup N={N} d={d}", flush=True)
+    cache = synth.cache_embeddings(N, d, seed=1)
+    for trial, near in enumerate((N // 3, None, N - 1)):
+        q = synth.cache_query(cache, seed=1, near=near, trial=trial)
+        j, m, hit = _check_lookup(cache, q)
+        if near is not None and d >= 768:
+            assert j == near
+    # non-unit rows: cosine, not dot
+    scaled = cache * synth.stream(1, "rowscale").uniform(0.1, 10.0, size=(N, 1)).astype(np.float32)
+    _check_lookup(scaled, synth.cache_query(cache, seed=1, near=N // 2, trial=9))
+
+
+def test_lookup_deterministic():
+    cache = dev_f32(synth.cache_embeddings(4096, 1024, seed=2))
+    q = dev_f32(synth.cache_query(host(cache), seed=2, near=99))
+    a = P.chorus_cache_lookup(cache, q, 0.75).cpu()
+    b = P.chorus_cache_lookup(cache, q, 0.75).cpu()
+    assert torch.equal(a, b)
+
+
+# ---------------------------------------------------------------- compaction
+
+@pytest.mark.parametrize("L", [1, 15, 16, 17, 4095, 4096, 4097, 32760, 75600, 1 << 20])
+def test_compact_sizes(L):
+    print(f"[case] compact L={L}", flush=True)
+    for kind in ("bern0.4", "ones", "zeros", "bern0.01"):
+        if kind == "ones":
+            m = np.ones(L, np.uint8)
+        elif kind == "zeros":
+            m = np.zeros(L, np.uint8)
+        else:
+            m = synth.bernoulli_mask(L, float(kind[4:]), seed=L)
+            m[m != 0] = synth.stream(L, "vals").integers(1, 256, size=int(m.sum())).astype(np.uint8)  # any non-zero byte
+        ref = O.region_compact(m)
+        idx, cnt = P.chorus_region_compact(torch.from_numpy(m).to(DEV))
+        n = int(cnt.cpu()[0])
+        assert n == ref.size
+        np.testing.assert_array_equal(host(idx[:n]).astype(np.int64), ref)
+
+
+def test_compact_box_and_empty():
+    bs = synth.SHAPES["wan1p3b_480p"]
+    m = synth.box_mask(bs.grid, 21, 24, 26, 0, 3, 13)
+    assert int(m.sum()) == 13104
+    idx, cnt = P.chorus_region_compact(torch.from_numpy(m).to(DEV))
+    assert int(cnt.cpu()[0]) == 13104
+    np.testing.assert_array_equal(host(idx[:13104]).astype(np.int64), O.region_compact(m))
+    # unaligned mask pointer (a view at an odd offset)
+    big = torch.from_numpy(np.concatenate([[9], m]).astype(np.uint8)).to(DEV)
+    idx2, cnt2 = P.chorus_region_compact(big[1:])
+    assert int(cnt2.cpu()[0]) == 13104 and torch.equal(idx2[:13104], idx[:13104])
+    # L == 0
+    idx0, cnt0 = P.chorus_region_compact(torch.empty(0, dtype=torch.uint8, device=DEV))
+    assert int(cnt0.cpu()[0]) == 0
+
+
+# ------------------------------------------------------------ gather / scatter
+
+@pytest.mark.parametrize("W,dtype", [(64, torch.float32), (1536, torch.float32), (1536, torch.bfloat16), (3, torch.float32), (6, torch.bfloat16)])
+def test_gather_scatter_bit_exact(W, dtype):
+    print(f"[case] gather/scatter W={W} {dtype}", flush=True)
+    L = 5000
+    m = synth.bernoulli_mask(L, 0.37, seed=W)
+    ref_idx = O.region_compact(m)
+    Ls = ref_idx.size
+    src_np = synth.normal(W, "gs", (L, W))
+    src = torch.from_numpy(src_np).to(DEV).to(dtype)
+    idx = torch.from_numpy(ref_idx.astype(np.int32)).to(DEV)
+    dst = torch.zeros(Ls, W, dtype=dtype, device=DEV)
+    P.chorus_region_gather_rows(dst, src, idx)
+    ref = O.gather_rows(src.cpu().view(torch.int16 if dtype == torch.bfloat16 else torch.int32).numpy(), ref_idx)
+    got = dst.cpu().view(torch.int16 if dtype == torch.bfloat16 else torch.int32).numpy()
+    np.testing.assert_array_equal(got, ref)
+    back = torch.full((L, W), 7.0, dtype=dtype, device=DEV)
+    P.chorus_region_scatter_rows(back, dst, idx)
+    sref = O.scatter_rows(np.full((L, W), 7.0, np.float32), src.float().cpu().numpy()[ref_idx], ref_idx)
+    np.testing.assert_array_equal(back.float().cpu().numpy(), sref)
+    # Ls == 0 is a no-op
+    P.chorus_region_gather_rows(dst, src, idx[:0], Ls=0)
+
+
+# -------------------------------------------------------------------- blend
+
+def _blend_case(shape, grid, mask, inplace=False):
+    L = synth.normal(5, "bl.L", shape)
+    SL = synth.normal(5, "bl.SL", shape)
+    ref = O.region_blend(L, SL, mask, grid, (1, 2, 2))
+    dL, dSL = torch.from_numpy(L).to(DEV), torch.from_numpy(SL).to(DEV)
+    out = dL if inplace else torch.empty_like(dL)
+    P.chorus_region_blend(out, dL, dSL, torch.from_numpy(mask).to(DEV))
+    assert out.cpu().numpy().tobytes() == ref.astype(np.float32).tobytes()
+
+
+def test_blend_bit_exact():
+    print("[case] blend", flush=True)
+    bs = synth.SHAPES["c1"]
+    shp, grid = bs.latent_shape, bs.grid
+    _blend_case(shp, grid, np.zeros(bs.L, np.uint8))                 # all reuse: the cached latent bit for bit
+    _blend_case(shp, grid, np.ones(bs.L, np.uint8))                  # all compute
+    _blend_case(shp, grid, synth.exact_count_mask(bs.L, 128, 0))     # config-1 mask
+    _blend_case(shp, grid, synth.exact_count_mask(bs.L, 128, 0), inplace=True)
+    # width not a multiple of 4 -> scalar path
+    _blend_case((3, 2, 6, 10), (2, 3, 5), synth.exact_count_mask(30, 11, 1))
+
+
+def test_blend_full_shape():
+    bs = synth.SHAPES["wan1p3b_480p"]
+    print("[case] blend 1.3B latent box 40%", flush=True)
+    _blend_case(bs.latent_shape, bs.grid, synth.box_mask(bs.grid, 21, 24, 26, 0, 3, 13))
+    print("[case] blend 1.3B latent bernoulli", flush=True)
+    _blend_case(bs.latent_shape, bs.grid, synth.bernoulli_mask(bs.L, 0.4, 0))
+    _blend_case(bs.latent_shape, bs.grid, np.zeros(bs.L, np.uint8), inplace=True)

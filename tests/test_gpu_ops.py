@@ -1,0 +1,162 @@
+"""GPU parity of the single operations the block is made of (GEMM + epilogues,
+LayerNorm/modulate, RMSNorm + RoPE, V transpose, attention) against the oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import chorus_oracle as O
+import paper_2604_04451_amd as P
+from paper_2604_04451_amd import binding as B
+from gpu_util import DEV, check, dev_bf16, dev_f32, host, host_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+# --------------------------------------------------------------------- GEMM
+
+@pytest.mark.parametrize("M,N,K", [(1, 64, 64), (100, 768, 256), (257, 1536, 1536), (1000, 64, 1536),
+                                   (4099, 4608, 1536), (3000, 1536, 8960), (513, 1024, 64), (70, 8, 128)])
+def test_gemm_epilogues(M, N, K):
+    print(f"[case] gemm M={M} N={N} K={K}", flush=True)
+    A = synth.round_bf16(synth.normal(M, "g.A", (M, K)))
+    W = synth.round_bf16(synth.normal(M, "g.W", (N, K), 0.05))
+    bias = synth.normal(M, "g.b", (N,), 0.5)
+    g0 = synth.normal(M, "g.g0", (N,), 0.5)
+    g1 = synth.normal(M, "g.g1", (N,), 0.5)
+    resid = synth.normal(M, "g.r", (M, N))
+    ref = O.linear(A, W, bias)
+    dA, dW, db = dev_bf16(A), dev_bf16(W), dev_f32(bias)
+    out = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+    B.chorus_gemm_bf16(dA, dW, B.EPI_BF16, out, db)
+    check(host_bf16(out), ref, "gemm bf16", max_abs=np.abs(ref).max() * 2 ** -8, rel_l2=3e-3)
+    B.chorus_gemm_bf16(dA, dW, B.EPI_GELU_BF16, out, db)
+    gref = O.gelu_tanh(ref)
+    check(host_bf16(out), gref, "gemm gelu", max_abs=max(np.abs(gref).max() * 2 ** -8, 1e-3), rel_l2=3e-3)
+    o32 = torch.empty(M, N, dtype=torch.float32, device=DEV)
+    B.chorus_gemm_bf16(dA, dW, B.EPI_F32, o32, None)
+    check(host(o32), O.linear(A, W, np.zeros(N)), "gemm f32", max_abs=1e-3, rel_l2=1e-5)
+    r = dev_f32(resid)
+    B.chorus_gemm_bf16(dA, dW, B.EPI_RESID, r, db, dev_f32(g0), dev_f32(g1), 1.0)
+    check(host(r), resid + (g0.astype(np.float64) + g1) * ref, "gemm resid gated", max_abs=1e-3, rel_l2=1e-5)
+    r = dev_f32(resid)
+    B.chorus_gemm_bf16(dA, dW, B.EPI_RESID, r, db, None, None, 1.5)
+    check(host(r), resid + 1.5 * ref, "gemm resid scale", max_abs=1e-3, rel_l2=1e-5)
+
+
+# ------------------------------------------------------------- LN + modulate
+
+@pytest.mark.parametrize("L,D", [(1, 256), (301, 256), (130, 1536), (37, 5120), (50, 320)])
+def test_ln_modulate(L, D):
+    print(f"[case] ln_modulate L={L} D={D}", flush=True)
+    x = synth.normal(D, "ln.x", (L, D), 1.3, 0.4)
+    tab = synth.normal(D, "ln.tab", (4, D), 0.3)
+    out = torch.empty(L, D, dtype=torch.bfloat16, device=DEV)
+    d = [dev_f32(tab[i]) for i in range(4)]
+    B.chorus_ln_modulate(dev_f32(x), out, d[0], d[1], d[2], d[3], True)
+    ref = O.layernorm(x) * (1.0 + tab[0].astype(np.float64) + tab[1]) + (tab[2].astype(np.float64) + tab[3])
+    check(host_bf16(out), ref, "adaln", max_abs=np.abs(ref).max() * 2 ** -8, rel_l2=2.5e-3)
+    B.chorus_ln_modulate(dev_f32(x), out, d[0], None, d[2], None, False)
+    ref = O.layernorm(x) * tab[0].astype(np.float64) + tab[2]
+    check(host_bf16(out), ref, "ln affine", max_abs=np.abs(ref).max() * 2 ** -8, rel_l2=2.5e-3)
+
+
+# ------------------------------------------------------------ RMSNorm + RoPE
+
+@pytest.mark.parametrize("H,dh,grid", [(4, 64, (4, 8, 8)), (12, 128, (5, 12, 20)), (2, 128, (21, 30, 52))])
+def test_qk_norm_rope(H, dh, grid):
+    print(f"[case] qk_norm_rope H={H} dh={dh} grid={grid}", flush=True)
+    D = H * dh
+    Ltok = grid[0] * grid[1] * grid[2]
+    m = synth.bernoulli_mask(Ltok, 0.3, seed=dh) if Ltok > 2000 else np.ones(Ltok, np.uint8)
+    idx = O.region_compact(m)
+    L = idx.size
+    Lpad = (L + 255) // 256 * 256
+    z = synth.round_bf16(synth.normal(dh, "qk.z", (L, 3 * D), 1.5))
+    gain = synth.normal(dh, "qk.g", (D,), 0.2, 1.5)
+    out = torch.full((H, Lpad, dh), 3.0, dtype=torch.bfloat16, device=DEV)
+    B.chorus_qk_norm_rope(dev_bf16(z), D, dev_f32(gain), out, L, H, dh,
+                          torch.from_numpy(idx.astype(np.int32)).to(DEV), grid, True)
+    ref = O.rope3d(O.rmsnorm(z[:, D:2 * D], gain), idx, grid, H, dh).reshape(L, H, dh).transpose(1, 0, 2)
+    got = host_bf16(out)
+    check(got[:, :L], ref, "rms+rope", max_abs=np.abs(ref).max() * 2 ** -8, rel_l2=2.5e-3)
+    assert (got[:, L:] == 0).all()
+    # no RoPE, identity positions
+    B.chorus_qk_norm_rope(dev_bf16(z), 0, dev_f32(gain), out, L, H, dh, None, grid, False)
+    ref = O.rmsnorm(z[:, :D], gain).reshape(L, H, dh).transpose(1, 0, 2)
+    check(host_bf16(out)[:, :L], ref, "rms only", max_abs=np.abs(ref).max() * 2 ** -8, rel_l2=2.5e-3)
+
+
+def _vt_reference(v, Lpad):
+    """[L, D] -> [D, Lpad] with the 16-group token permutation position 8c+4u+i <- token 8u+4c+i."""
+    L, D = v.shape
+    vp = np.zeros((Lpad, D), v.dtype)
+    vp[:L] = v
+    pos = np.arange(Lpad)
+    G, r = pos // 16, pos % 16
+    c, u, i = r // 8, (r // 4) % 2, r % 4
+    tok = 16 * G + 8 * u + 4 * c + i
+    return vp[tok].T.copy()
+
+
+@pytest.mark.parametrize("L,D", [(1, 64), (100, 256), (1200, 1536)])
+def test_v_transpose_bit_exact(L, D):
+    print(f"[case] v_transpose L={L} D={D}", flush=True)
+    Lpad = (L + 255) // 256 * 256
+    z = synth.round_bf16(synth.normal(L, "vt.z", (L, 3 * D)))
+    out = torch.full((D, Lpad), 5.0, dtype=torch.bfloat16, device=DEV)
+    B.chorus_v_transpose(dev_bf16(z), 2 * D, out, L)
+    np.testing.assert_array_equal(host_bf16(out), _vt_reference(z[:, 2 * D:].astype(np.float64), Lpad))
+
+
+# ---------------------------------------------------------------- attention
+
+def _attn_case(H, dh, Lq, Lk, variant, col_scale=None, q_std=1.0, seed=0, name=""):
+    D = H * dh
+    q = synth.round_bf16(synth.normal(seed, "at.q", (Lq, D), q_std))
+    k = synth.round_bf16(synth.normal(seed, "at.k", (Lk, D), q_std))
+    v = synth.round_bf16(synth.normal(seed, "at.v", (Lk, D)))
+    LqPad = (Lq + 255) // 256 * 256
+    LkPad = (Lk + 63) // 64 * 64
+    Q = torch.zeros(H, LqPad, dh, dtype=torch.bfloat16, device=DEV)
+    K = torch.zeros(H, LkPad, dh, dtype=torch.bfloat16, device=DEV)
+    Q[:, :Lq] = dev_bf16(q).reshape(Lq, H, dh).transpose(0, 1)
+    K[:, :Lk] = dev_bf16(k).reshape(Lk, H, dh).transpose(0, 1)
+    Vt = torch.from_numpy(synth.to_bf16_bits(_vt_reference(v, LkPad).astype(np.float32)).reshape(D, LkPad).view(np.int16)).to(DEV).view(torch.bfloat16)
+    Oo = torch.full((Lq, D), 9.0, dtype=torch.bfloat16, device=DEV)
+    cs = None if col_scale is None else dev_f32(col_scale)
+    B.chorus_attention(Q, K, Vt, Oo, cs, Lq, Lk, variant)
+    ref = O.attention(q.astype(np.float64), O.tgaa_amplify_keys(k.astype(np.float64), col_scale), v.astype(np.float64), H, dh)
+    return check(host_bf16(Oo), ref, f"attention {name} H={H} dh={dh} Lq={Lq} Lk={Lk} v{variant}",
+                 max_abs=max(np.abs(ref).max() * 2 ** -7, 2e-3), rel_l2=5e-3)
+
+
+@pytest.mark.parametrize("variant", [1, 2])
+@pytest.mark.parametrize("H,dh,Lq,Lk", [(2, 64, 300, 300), (3, 128, 500, 333), (1, 128, 1, 1), (2, 128, 64, 64),
+                                        (2, 64, 257, 65), (12, 128, 1200, 1200), (4, 64, 256, 16)])
+def test_attention_plain(H, dh, Lq, Lk, variant):
+    print(f"[case] attention H={H} dh={dh} Lq={Lq} Lk={Lk} variant={variant}", flush=True)
+    _attn_case(H, dh, Lq, Lk, variant, name="plain")
+
+
+@pytest.mark.parametrize("variant", [1, 2])
+def test_attention_peaked(variant):
+    """Logits with std ~4: rows dominated by few keys; catches masking / rescale mistakes that
+    near-uniform rows (output ~ mean V) would hide."""
+    print(f"[case] attention peaked variant={variant}", flush=True)
+    _attn_case(4, 128, 700, 900, variant, q_std=2.0, seed=3, name="peaked")
+    _attn_case(2, 64, 333, 2000, variant, q_std=2.0, seed=4, name="peaked64")
+
+
+@pytest.mark.parametrize("variant", [1, 2])
+@pytest.mark.parametrize("H,dh,Lq,Lt", [(4, 64, 256, 16), (12, 128, 700, 512), (2, 128, 100, 77)])
+def test_attention_tgaa_column_scale(H, dh, Lq, Lt, variant):
+    print(f"[case] cross-attention TGAA H={H} dh={dh} Lq={Lq} Lt={Lt} variant={variant}", flush=True)
+    _attn_case(H, dh, Lq, Lt, variant, col_scale=synth.tdiff_scale(Lt, 1.5), q_std=1.5, name="tgaa-all")
+    _attn_case(H, dh, Lq, Lt, variant, col_scale=synth.tdiff_scale(Lt, 1.5, n_diff=max(1, Lt // 64)), q_std=1.5, name="tgaa-subset")
+    # neutral scale equals the plain kernel's result
+    a = _attn_case(H, dh, Lq, Lt, variant, col_scale=np.ones(Lt, np.float32), q_std=1.5, name="tgaa-neutral")
+    b = _attn_case(H, dh, Lq, Lt, variant, col_scale=None, q_std=1.5, name="plain")
+    assert abs(a[1] - b[1]) < 1e-3
