@@ -133,6 +133,60 @@ int32_t chorus_denoise_step(const chorus_model_shape* model, const chorus_block_
                             const uint8_t* mask_edit, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * The whole three-stage request (Sec. 3.1) on one stream:
+ *   1. top-1 cosine lookup of `query` in the cache; the score m is read back
+ *   2. (K1, K2) and the per-step TGAA factors from chorus_denoise_schedule
+ *   3. steps [0, K1): full reuse -- the matched entry's cached latent replaces `latent`
+ *      steps [K1, K2): compact M_see once, then chorus_denoise_step on those tokens with
+ *        key scale g_j = gamma_k on the differential tokens (tdiff[j] != 0; tdiff NULL
+ *        = every token), output amplification gamma_o, and fusion with the cached
+ *        latent under M_edit (Eq. 6)
+ *      steps [K2, N): chorus_denoise_step on all tokens
+ * A miss (m < tau, or an empty cache) runs N plain steps from the caller's latent.
+ * One cached latent per entry serves both the stage-1 copy and the stage-2 fusion.
+ * Two host synchronisations: after the lookup and after the compaction count.
+ *   cache_emb dev [N, d]; cache_latents dev [N, C, T, Hl, Wl] fp32; query dev [d]
+ *   sigmas host [n_steps + 1]; t_mods dev [n_steps, 6, D]; t_heads dev [n_steps, 2, D]
+ *   text_ctx dev [Lt, D] bf16; tdiff dev [Lt] uint8 or NULL
+ *   mask_see, mask_edit dev [T*Hg*Wg] uint8 (needed only if a stage-2 step is planned)
+ *   sched: NULL = default schedule parameters;  n_steps <= 64
+ *   latent dev [C, T, Hl, Wl] fp32: initial noise in, final latent out
+ *   result host
+ * chorus_stage1_copy is the full-reuse copy on its own (n fp32 elements).
+ * ------------------------------------------------------------------------ */
+typedef struct {
+  const float* cache_emb;
+  const float* cache_latents;
+  int64_t cache_N;
+  int32_t cache_d;
+  const float* query;
+  float tau;
+  const chorus_sched_params* sched;
+  int32_t n_steps;
+  const float* sigmas;
+  const float* t_mods;
+  const float* t_heads;
+  const uint16_t* text_ctx;
+  const uint8_t* tdiff;
+  const uint8_t* mask_see;
+  const uint8_t* mask_edit;
+} chorus_request;
+
+typedef struct {
+  int32_t index;
+  float score;
+  int32_t hit;
+  int32_t K1, K2;
+  int32_t Ls; /* tokens computed in a stage-2 step (0 if none was planned) */
+} chorus_run_result;
+
+size_t chorus_denoise_run_workspace_bytes(const chorus_model_shape* model, int64_t N);
+int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_weights* blocks,
+                           const chorus_glue_weights* gw, const chorus_request* rq, float* latent,
+                           chorus_run_result* result, void* ws, size_t ws_bytes, void* stream);
+int32_t chorus_stage1_copy(float* latent, const float* SL, int64_t n, void* stream);
+
+/* ------------------------------------------------------------------------
  * Per-kernel timing for benchmarks. When enabled, chorus_dit_block_step brackets
  * its kernels with HIP events on the caller's stream; chorus_prof_read waits for
  * them and returns the summed milliseconds and the launch count of one kernel

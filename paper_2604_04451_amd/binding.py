@@ -60,6 +60,19 @@ class ModelShape(C.Structure):
     _fields_ = [("block", BlockShape)] + [(n, C.c_int32) for n in ("C", "T", "Hl", "Wl", "ph", "pw", "n_blocks")]
 
 
+class Request(C.Structure):
+    _fields_ = [("cache_emb", C.c_void_p), ("cache_latents", C.c_void_p), ("cache_N", C.c_int64),
+                ("cache_d", C.c_int32), ("query", C.c_void_p), ("tau", C.c_float),
+                ("sched", C.POINTER(SchedParams)), ("n_steps", C.c_int32), ("sigmas", C.POINTER(C.c_float)),
+                ("t_mods", C.c_void_p), ("t_heads", C.c_void_p), ("text_ctx", C.c_void_p), ("tdiff", C.c_void_p),
+                ("mask_see", C.c_void_p), ("mask_edit", C.c_void_p)]
+
+
+class RunResult(C.Structure):
+    _fields_ = [("index", C.c_int32), ("score", C.c_float), ("hit", C.c_int32), ("K1", C.c_int32),
+                ("K2", C.c_int32), ("Ls", C.c_int32)]
+
+
 def lib_path() -> str:
     return _LIB_PATH
 
@@ -118,6 +131,10 @@ def _bind_ops(lib):
         "chorus_denoise_step_workspace_bytes": (sz, [MS, i64]),
         "chorus_denoise_step": (i32, [MS, C.POINTER(BlockWeights), GW, vp, vp, i64, vp, vp, vp, vp, f32, f32, vp, vp,
                                       vp, sz, vp]),
+        "chorus_denoise_run_workspace_bytes": (sz, [MS, i64]),
+        "chorus_denoise_run": (i32, [MS, C.POINTER(BlockWeights), GW, C.POINTER(Request), vp, C.POINTER(RunResult), vp,
+                                     sz, vp]),
+        "chorus_stage1_copy": (i32, [vp, vp, i64, vp]),
         "chorus_prof_enable": (i32, [i32]),
         "chorus_prof_reset": (i32, []),
         "chorus_prof_read": (i32, [i32, C.POINTER(C.c_double), C.POINTER(i32)]),
@@ -498,6 +515,54 @@ def chorus_denoise_step(model: ModelShape, blocks_arr, glue: DeviceGlue, latent,
                                     _p(text_ctx), _p(t_mod), _p(t_head), _p(tgaa_key_scale), float(gamma_o),
                                     float(dsigma), _p(SL), _p(mask_edit), _p(ws), ws.numel(), _stream()))
     return latent
+
+
+def chorus_stage1_copy(latent, SL):
+    _chk(latent, torch.float32, "latent")
+    _chk(SL, torch.float32, "SL", latent.shape)
+    _status("chorus_stage1_copy", load().chorus_stage1_copy(_p(latent), _p(SL), latent.numel(), _stream()))
+    return latent
+
+
+def chorus_denoise_run_workspace_bytes(model: ModelShape, N: int) -> int:
+    return load().chorus_denoise_run_workspace_bytes(C.byref(model), int(N))
+
+
+def chorus_denoise_run(model: ModelShape, blocks_arr, glue: DeviceGlue, latent, cache_emb, cache_latents, query, tau,
+                       sigmas, t_mods, t_heads, text_ctx, tdiff=None, mask_see=None, mask_edit=None, sched=None,
+                       ws=None):
+    """Runs one request; returns a dict with the lookup result, K1, K2 and the stage-2 token count."""
+    lib = load()
+    D = model.block.D
+    n_steps = len(sigmas) - 1
+    N, d = cache_emb.shape
+    _chk(latent, torch.float32, "latent", (model.C, model.T, model.Hl, model.Wl))
+    _chk(cache_emb, torch.float32, "cache_emb")
+    _chk(cache_latents, torch.float32, "cache_latents", (N,) + tuple(latent.shape))
+    _chk(query, torch.float32, "query", (d,))
+    _chk(t_mods, torch.float32, "t_mods", (n_steps, 6, D))
+    _chk(t_heads, torch.float32, "t_heads", (n_steps, 2, D))
+    _chk(text_ctx, torch.bfloat16, "text_ctx", (model.block.Lt, D))
+    _chk(tdiff, torch.uint8, "tdiff", (model.block.Lt,))
+    Ltok = model.T * (model.Hl // model.ph) * (model.Wl // model.pw)
+    _chk(mask_see, torch.uint8, "mask_see", (Ltok,))
+    _chk(mask_edit, torch.uint8, "mask_edit", (Ltok,))
+    sp = None
+    if sched is not None:
+        dflt = dict(a1=0.25, b1=0.25, a2=0.25, b2=0.25, r3=1, Gamma_k=1.5, Gamma_o=1.5, lam=0.5, gamma_override=0.0)
+        dflt.update(sched)
+        sp = SchedParams(**dflt)
+    sig = (C.c_float * (n_steps + 1))(*[float(v) for v in sigmas])
+    rq = Request(cache_emb.data_ptr() if N else 0, cache_latents.data_ptr() if N else 0, N, d, query.data_ptr(),
+                 float(tau), C.pointer(sp) if sp is not None else None, n_steps, sig, t_mods.data_ptr(),
+                 t_heads.data_ptr(), text_ctx.data_ptr(), 0 if tdiff is None else tdiff.data_ptr(),
+                 0 if mask_see is None else mask_see.data_ptr(), 0 if mask_edit is None else mask_edit.data_ptr())
+    if ws is None:
+        ws = _ws(lib.chorus_denoise_run_workspace_bytes(C.byref(model), N), latent.device)
+    res = RunResult()
+    _status("chorus_denoise_run", lib.chorus_denoise_run(C.byref(model), blocks_arr, C.byref(glue.cstruct), C.byref(rq),
+                                                         _p(latent), C.byref(res), _p(ws), ws.numel(), _stream()))
+    return dict(index=res.index, score=res.score, hit=bool(res.hit), K1=res.K1, K2=res.K2, Ls=res.Ls)
 
 
 def prof_enable(on=True):

@@ -88,3 +88,178 @@ int32_t chorus_denoise_step(const chorus_model_shape* model, const chorus_block_
 }
 
 }  // extern "C"
+
+// ---------------------------------------------------------------------------
+// chorus_denoise_run: the whole three-stage request on one stream.
+// ---------------------------------------------------------------------------
+namespace {
+
+__global__ __launch_bounds__(256) void stream_copy_kernel(float4* __restrict__ dst, const float4* __restrict__ src,
+                                                          long n4) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n4) st_stream_f4(&dst[i], ld_stream_f4(&src[i]));
+}
+
+__global__ void copy_tail_kernel(float* __restrict__ dst, const float* __restrict__ src, long from, long n) {
+  long i = from + (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
+// g_j = gamma_k where tdiff[j] != 0, else 1  (the per-token key factor of Eq. 2)
+__global__ void key_scale_kernel(float* __restrict__ g, const uint8_t* __restrict__ tdiff, int Lt, float gamma_k) {
+  int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < Lt) g[j] = (tdiff == nullptr || tdiff[j]) ? gamma_k : 1.0f;
+}
+
+int32_t device_copy(float* dst, const float* src, long n, hipStream_t s) {
+  if (n <= 0 || dst == src) return CHORUS_OK;
+  long n4 = (aligned16(dst) && aligned16(src)) ? n / 4 : 0;
+  if (n4 > 0) {
+    hipLaunchKernelGGL(stream_copy_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, (float4*)dst,
+                       (const float4*)src, n4);
+    CHORUS_LAUNCH_CHECK();
+  }
+  if (n4 * 4 < n) {
+    hipLaunchKernelGGL(copy_tail_kernel, dim3((unsigned)((n - n4 * 4 + 255) / 256)), dim3(256), 0, s, dst, src, n4 * 4,
+                       n);
+    CHORUS_LAUNCH_CHECK();
+  }
+  return CHORUS_OK;
+}
+
+struct RunWs {
+  chorus_lookup_result* lookup;  // device
+  int32_t* count;
+  int32_t* idx;
+  float* key_scale;
+  void* lookup_ws;
+  size_t lookup_ws_bytes;
+  void* compact_ws;
+  size_t compact_ws_bytes;
+  void* step;
+  size_t step_bytes;
+  size_t bytes;
+};
+
+RunWs carve_run(const chorus_model_shape& m, int64_t N, void* base) {
+  RunWs w;
+  uint8_t* p = (uint8_t*)base;
+  size_t off = 0;
+  const int64_t Ltok = (int64_t)m.T * (m.Hl / m.ph) * (m.Wl / m.pw);
+  auto take = [&](size_t bytes) {
+    void* r = p + off;
+    off += align_up(bytes, 256);
+    return r;
+  };
+  w.lookup = (chorus_lookup_result*)take(sizeof(chorus_lookup_result));
+  w.count = (int32_t*)take(sizeof(int32_t));
+  w.idx = (int32_t*)take((size_t)Ltok * 4);
+  w.key_scale = (float*)take((size_t)m.block.Lt * 4);
+  w.lookup_ws_bytes = chorus_cache_lookup_workspace_bytes(N);
+  w.lookup_ws = take(w.lookup_ws_bytes);
+  w.compact_ws_bytes = chorus_region_compact_workspace_bytes(Ltok);
+  w.compact_ws = take(w.compact_ws_bytes);
+  w.step_bytes = chorus_denoise_step_workspace_bytes(&m, Ltok);
+  w.step = take(w.step_bytes);
+  w.bytes = off;
+  return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t chorus_denoise_run_workspace_bytes(const chorus_model_shape* model, int64_t N) {
+  if (check_model(model) != CHORUS_OK || N < 0) return 0;
+  return carve_run(*model, N, nullptr).bytes;
+}
+
+int32_t chorus_stage1_copy(float* latent, const float* SL, int64_t n, void* stream) {
+  if (n < 0 || (n > 0 && (!latent || !SL))) return CHORUS_E_ARG;
+  return device_copy(latent, SL, (long)n, (hipStream_t)stream);
+}
+
+int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_weights* blocks,
+                           const chorus_glue_weights* gw, const chorus_request* rq, float* latent,
+                           chorus_run_result* result, void* ws, size_t ws_bytes, void* stream) {
+  int32_t st = check_model(model);
+  if (st != CHORUS_OK) return st;
+  if (!rq || !latent || !result || !gw) return CHORUS_E_ARG;
+  if (rq->n_steps < 0 || rq->cache_N < 0 || rq->cache_d <= 0) return CHORUS_E_ARG;
+  if (rq->n_steps > 0 && (!rq->sigmas || !rq->t_mods || !rq->t_heads || !rq->text_ctx)) return CHORUS_E_ARG;
+  if (!rq->query || (rq->cache_N > 0 && (!rq->cache_emb || !rq->cache_latents))) return CHORUS_E_ARG;
+  if (!ws) return CHORUS_E_WORKSPACE;
+  const chorus_model_shape& m = *model;
+  RunWs w = carve_run(m, rq->cache_N, ws);
+  if (ws_bytes < w.bytes) return CHORUS_E_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const int64_t Ltok = (int64_t)m.T * (m.Hl / m.ph) * (m.Wl / m.pw);
+  const int64_t lat_elems = (int64_t)m.C * m.T * m.Hl * m.Wl;
+  const int D = m.block.D;
+
+  // stage-1 retrieval, then the scheduler needs the score on the host
+  st = chorus_cache_lookup(rq->cache_emb, rq->cache_N, rq->cache_d, rq->query, rq->tau, w.lookup, w.lookup_ws,
+                           w.lookup_ws_bytes, stream);
+  if (st != CHORUS_OK) return st;
+  chorus_lookup_result lr;
+  CHORUS_HIP(hipMemcpyAsync(&lr, w.lookup, sizeof(lr), hipMemcpyDeviceToHost, s));
+  CHORUS_HIP(hipStreamSynchronize(s));
+  result->index = lr.index;
+  result->score = lr.score;
+  result->hit = lr.hit;
+
+  chorus_step_plan plan_buf[64];
+  if (rq->n_steps > 64) return CHORUS_E_SHAPE;
+  int32_t K1 = 0, K2 = 0;
+  st = chorus_denoise_schedule(lr.score, rq->tau, rq->n_steps, rq->sched, &K1, &K2, plan_buf);
+  if (st != CHORUS_OK) return st;
+  result->K1 = K1;
+  result->K2 = K2;
+  result->Ls = 0;
+
+  const float* SL = lr.hit ? rq->cache_latents + (int64_t)lr.index * lat_elems : nullptr;
+  int64_t Ls = 0;
+  if (K2 > K1) {
+    if (!rq->mask_see || !rq->mask_edit) return CHORUS_E_ARG;
+    st = chorus_region_compact(rq->mask_see, Ltok, w.idx, w.count, w.compact_ws, w.compact_ws_bytes, stream);
+    if (st != CHORUS_OK) return st;
+    int32_t cnt = 0;
+    CHORUS_HIP(hipMemcpyAsync(&cnt, w.count, sizeof(cnt), hipMemcpyDeviceToHost, s));
+    CHORUS_HIP(hipStreamSynchronize(s));
+    Ls = cnt;
+    result->Ls = cnt;
+  }
+
+  for (int i = 0; i < rq->n_steps; ++i) {
+    const chorus_step_plan& p = plan_buf[i];
+    if (p.stage == 1) {
+      // full reuse: only the last reused step's latent survives
+      if (i == K1 - 1) {
+        st = device_copy(latent, SL, (long)lat_elems, s);
+        if (st != CHORUS_OK) return st;
+      }
+      continue;
+    }
+    const float* ks = nullptr;
+    if (p.gamma_k != 1.0f) {
+      hipLaunchKernelGGL(key_scale_kernel, dim3((unsigned)((m.block.Lt + 255) / 256)), dim3(256), 0, s, w.key_scale,
+                         rq->tdiff, m.block.Lt, p.gamma_k);
+      CHORUS_LAUNCH_CHECK();
+      ks = w.key_scale;
+    }
+    const float dsigma = rq->sigmas[i + 1] - rq->sigmas[i];
+    const float* t_mod = rq->t_mods + (size_t)i * 6 * D;
+    const float* t_head = rq->t_heads + (size_t)i * 2 * D;
+    if (p.stage == 2) {
+      st = chorus_denoise_step(model, blocks, gw, latent, w.idx, Ls, rq->text_ctx, t_mod, t_head, ks, p.gamma_o, dsigma,
+                               SL, rq->mask_edit, w.step, w.step_bytes, stream);
+    } else {
+      st = chorus_denoise_step(model, blocks, gw, latent, nullptr, Ltok, rq->text_ctx, t_mod, t_head, ks, p.gamma_o,
+                               dsigma, nullptr, nullptr, w.step, w.step_bytes, stream);
+    }
+    if (st != CHORUS_OK) return st;
+  }
+  return CHORUS_OK;
+}
+
+}  // extern "C"

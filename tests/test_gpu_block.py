@@ -33,8 +33,16 @@ def _run_block(bs, w, inp, token_idx=None, key_scale=None, gamma_o=1.0, Ls=None)
     return host(x)
 
 
-def _compare(got, x_in, ref, name):
-    check(got, ref, name + " x")
+def _compare(got, x_in, ref, name, stress=False):
+    if stress:
+        # not a spec configuration: gates ~1 and biased branches make |x_out| several
+        # units, and q/k gains of 2 with key amplification 1.5 give cross-attention logits of
+        # std ~6, where the two bf16 roundings of q and of k (2^-9 each) move a logit by ~1e-2
+        # and a probability by ~1%. The bound therefore scales with the output: 8 bf16 ulps
+        # of the largest value, rel-L2 1e-2.
+        check(got, ref, name + " x", max_abs=max(MAX_ABS, np.abs(ref).max() * 2 ** -6), rel_l2=1e-2)
+    else:
+        check(got, ref, name + " x")
     a, r = errs(got - x_in, ref - x_in)
     print(f"[parity] {name} delta: max_abs={a:.3e} rel_l2={r:.3e} |delta|max={np.abs(ref - x_in).max():.3e}", flush=True)
     assert r <= DELTA_REL, f"{name}: delta rel-L2 {r:.3e}"
@@ -130,14 +138,14 @@ def test_block_1p3b_widths_small_grid(stress):
     g = synth.tdiff_scale(bs.Lt, 1.5, n_diff=8)
     got = _run_block(bs, w, inp, key_scale=g, gamma_o=1.5)
     ref = O.dit_block(inp["x"], w, bs, inp["text_ctx"], inp["t_mod"], key_scale=g, gamma_o=1.5)
-    _compare(got, inp["x"], ref, f"1.3B-small full stress={stress}")
+    _compare(got, inp["x"], ref, f"1.3B-small full stress={stress}", stress)
     mask = synth.box_mask(bs.grid, 5, 8, 12, 0, 2, 3)
     idx = O.region_compact(mask)
     xc = dict(inp)
     xc["x"] = inp["x"][idx]
     got = _run_block(bs, w, xc, token_idx=idx, key_scale=g, gamma_o=1.5)
     ref = O.dit_block(inp["x"][idx], w, bs, inp["text_ctx"], inp["t_mod"], token_idx=idx, key_scale=g, gamma_o=1.5)
-    _compare(got, inp["x"][idx], ref, f"1.3B-small box stress={stress}")
+    _compare(got, inp["x"][idx], ref, f"1.3B-small box stress={stress}", stress)
 
 
 def test_block_deterministic():

@@ -1,0 +1,154 @@
+"""GPU parity of the step glue, one denoising step (stage 2 / stage 3) and the whole
+three-stage request against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import chorus_oracle as O
+import paper_2604_04451_amd as P
+from paper_2604_04451_amd import binding as B
+from gpu_util import DEV, check, dev_bf16, dev_f32, errs, host, host_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+class Model:
+    """Device + host copies of a small synthetic model."""
+
+    def __init__(self, bs, n_blocks, seed=0, stress=False, n_steps=4):
+        self.bs = bs
+        mk = synth.stress_block_weights if stress else synth.block_weights
+        self.blocks = [mk(bs, seed, b) for b in range(n_blocks)]
+        self.gw = synth.glue_weights(bs, seed)
+        self.text_raw = synth.round_bf16(synth.normal(seed, "text_raw", (bs.Lt, bs.text_dim), bs.text_std))
+        self.t_mods = synth.normal(seed, "t_mods", (n_steps, 6, bs.D), 0.02)
+        self.t_heads = synth.normal(seed, "t_heads", (n_steps, 2, bs.D), 0.02)
+        self.sigmas = [1.0 - i / n_steps for i in range(n_steps + 1)]
+        self.dblocks = [P.upload_block_weights(w) for w in self.blocks]
+        self.arr = B.block_array(self.dblocks)
+        self.dglue = B.upload_glue_weights(self.gw)
+        self.shape = P.make_block_shape(bs.D, bs.H, bs.dh, bs.F, bs.Lt, bs.grid)
+        self.model = B.make_model_shape(self.shape, bs.latent_shape, (2, 2), n_blocks)
+        self.d_tmods, self.d_theads = dev_f32(self.t_mods), dev_f32(self.t_heads)
+        # text context: the device projection, rounded to bf16, is what both sides use downstream
+        self.d_ctx = B.chorus_text_project(dev_bf16(self.text_raw), self.dglue)
+        self.ctx = host_bf16(self.d_ctx)
+
+
+def test_text_project_and_glue_ops():
+    print("[case] text_project / patch_embed / head_update", flush=True)
+    bs = synth.SHAPES["c1"]
+    md = Model(bs, 1)
+    ref_ctx = O.text_project(md.text_raw, md.gw)
+    check(md.ctx, ref_ctx, "text_project", max_abs=np.abs(ref_ctx).max() * 2 ** -7, rel_l2=5e-3)
+    lat = synth.latent(bs, 0, std=1.0)
+    mask = synth.exact_count_mask(bs.L, 100, seed=3)
+    idx = O.region_compact(mask)
+    didx = torch.from_numpy(idx.astype(np.int32)).to(DEV)
+    x = torch.empty(idx.size, bs.D, dtype=torch.float32, device=DEV)
+    B.chorus_patch_embed(dev_f32(lat), didx, idx.size, md.dglue, bs.D, x)
+    ref_x = O.patch_embed(O.gather_rows(O.patchify(lat, bs.patch), idx), md.gw)
+    check(host(x), ref_x, "patch_embed", max_abs=1e-4, rel_l2=1e-4)
+    dl = dev_f32(lat)
+    xin = synth.normal(1, "hx", (idx.size, bs.D))
+    B.chorus_head_update(dl, dev_f32(xin), idx.size, didx, md.dglue, md.d_theads[0], -0.25)
+    toks = O.patchify(lat.astype(np.float64), bs.patch)
+    toks[idx] += -0.25 * O.head(xin, md.gw, md.t_heads[0])
+    ref_l = O.unpatchify(toks, lat.shape, bs.patch)
+    check(host(dl), ref_l, "head_update", max_abs=2e-3, rel_l2=1e-3)
+    untouched = ~O.expand_token_mask(mask, bs.grid, bs.patch, bs.C).astype(bool)
+    np.testing.assert_array_equal(host(dl)[untouched], lat[untouched])
+
+
+@pytest.mark.parametrize("name,n_blocks,stress", [("c1", 2, True), ("wan1p3b_small", 2, False)])
+def test_denoise_step_stage2_and_stage3(name, n_blocks, stress):
+    print(f"[case] denoise_step {name} blocks={n_blocks} stress={stress}", flush=True)
+    bs = synth.SHAPES[name]
+    md = Model(bs, n_blocks, stress=stress)
+    lat = synth.latent(bs, 0, std=1.0)
+    SL = synth.latent(bs, 0, "SL", std=1.0)
+    g = synth.tdiff_scale(bs.Lt, 1.5)
+    # stage 3
+    dl = dev_f32(lat)
+    B.chorus_denoise_step(md.model, md.arr, md.dglue, dl, None, bs.L, md.d_ctx, md.d_tmods[2], md.d_theads[2], dsigma=-0.25)
+    ref = O.denoise_step(lat, md.blocks, md.gw, bs, md.ctx, md.t_mods[2], md.t_heads[2], -0.25)
+    check(host(dl), ref, "stage-3 step latent")
+    a, r = errs(host(dl) - lat, ref - lat)
+    print(f"[parity] stage-3 step update: rel_l2={r:.3e}", flush=True)
+    assert r <= 2e-2
+    # stage 2: M_edit strictly inside M_see
+    T, Hg, Wg = bs.grid
+    see = synth.box_mask(bs.grid, T, max(2, Hg * 2 // 3), max(2, Wg * 2 // 3), 0, 1, 1)
+    edit = synth.box_mask(bs.grid, T, max(1, Hg * 2 // 3 - 2), max(1, Wg * 2 // 3 - 2), 0, 2, 2)
+    assert ((edit == 0) | (see == 1)).all() and edit.sum() < see.sum()
+    idx_d, cnt = P.chorus_region_compact(torch.from_numpy(see).to(DEV))
+    Ls = int(cnt.cpu()[0])
+    dl = dev_f32(lat)
+    B.chorus_denoise_step(md.model, md.arr, md.dglue, dl, idx_d, Ls, md.d_ctx, md.d_tmods[1], md.d_theads[1],
+                          tgaa_key_scale=dev_f32(g), gamma_o=1.5, dsigma=-0.25, SL=dev_f32(SL),
+                          mask_edit=torch.from_numpy(edit).to(DEV))
+    ref = O.denoise_step(lat, md.blocks, md.gw, bs, md.ctx, md.t_mods[1], md.t_heads[1], -0.25, mask_see=see,
+                         mask_edit=edit, SL=SL, key_scale=g, gamma_o=1.5)
+    check(host(dl), ref, "stage-2 step latent")
+    Me = O.expand_token_mask(edit, bs.grid, bs.patch, bs.C).astype(bool)
+    np.testing.assert_array_equal(host(dl)[~Me], SL[~Me])     # reused region: the cached latent bit for bit
+    a, r = errs(host(dl)[Me] - lat[Me], ref[Me] - lat[Me])
+    print(f"[parity] stage-2 step update on M_edit: rel_l2={r:.3e}", flush=True)
+    assert r <= 2e-2
+    # all-reuse edit mask: cached latent bit for bit; all-compute masks: the unmasked step bit for bit
+    dl = dev_f32(lat)
+    B.chorus_denoise_step(md.model, md.arr, md.dglue, dl, idx_d, Ls, md.d_ctx, md.d_tmods[1], md.d_theads[1],
+                          dsigma=-0.25, SL=dev_f32(SL), mask_edit=torch.zeros(bs.L, dtype=torch.uint8, device=DEV))
+    assert host(dl).tobytes() == SL.tobytes()
+    ones = torch.ones(bs.L, dtype=torch.uint8, device=DEV)
+    idx1, cnt1 = P.chorus_region_compact(ones)
+    da, db = dev_f32(lat), dev_f32(lat)
+    B.chorus_denoise_step(md.model, md.arr, md.dglue, da, idx1, bs.L, md.d_ctx, md.d_tmods[1], md.d_theads[1],
+                          dsigma=-0.25, SL=dev_f32(SL), mask_edit=ones)
+    B.chorus_denoise_step(md.model, md.arr, md.dglue, db, None, bs.L, md.d_ctx, md.d_tmods[1], md.d_theads[1], dsigma=-0.25)
+    assert torch.equal(da, db)
+
+
+@pytest.mark.parametrize("name,n_blocks", [("c1", 2), ("wan1p3b_small", 2)])
+def test_denoise_run_four_step_schedule(name, n_blocks):
+    """Hit: stage-1 reuse, one stage-2 step with a 40% box and TGAA 1.5, two full steps.
+    Miss: four plain steps. Both against the oracle's loop."""
+    print(f"[case] denoise_run {name}", flush=True)
+    bs = synth.SHAPES[name]
+    md = Model(bs, n_blocks)
+    N = 16
+    cache = synth.cache_embeddings(N, bs.cache_d, seed=0)
+    cache_lat = synth.normal(0, "cache_lat", (N,) + bs.latent_shape)
+    noise = synth.latent(bs, 0, "noise", std=1.0)
+    T, Hg, Wg = bs.grid
+    see = synth.box_mask(bs.grid, T, Hg * 4 // 5, Wg // 2, 0, 1, 2)
+    tdiff = np.zeros(bs.Lt, np.uint8)
+    tdiff[synth.stream(0, "tdiff").permutation(bs.Lt)[:max(1, bs.Lt // 64)]] = 1
+    sched = dict(gamma_override=1.5)
+    for near in (5, None):
+        q = synth.cache_query(cache, seed=0, near=near)
+        dl = dev_f32(noise)
+        res = B.chorus_denoise_run(md.model, md.arr, md.dglue, dl, dev_f32(cache), dev_f32(cache_lat), dev_f32(q), 0.75,
+                                   md.sigmas, md.d_tmods, md.d_theads, md.d_ctx, tdiff=torch.from_numpy(tdiff).to(DEV),
+                                   mask_see=torch.from_numpy(see).to(DEV), mask_edit=torch.from_numpy(see).to(DEV),
+                                   sched=sched)
+        oj, om, ohit = O.cache_lookup(cache, q, 0.75)
+        K1, K2, plan = O.denoise_schedule(float(np.float32(res["score"])), float(np.float32(0.75)), 4, sched)
+        assert (res["index"], res["hit"]) == (oj, ohit) and abs(res["score"] - om) < 1e-5
+        assert (res["K1"], res["K2"]) == (K1, K2)
+        if near is not None:
+            assert ohit and [p[0] for p in plan] == [1, 2, 3, 3] and res["Ls"] == int(see.sum())
+        else:
+            assert not ohit and (K1, K2) == (0, 0)
+        ks_of = lambda gk: np.where(tdiff != 0, gk, 1.0)
+        ref = O.run_schedule(plan, md.sigmas, noise, cache_lat[oj], md.blocks, md.gw, bs, md.ctx, md.t_mods, md.t_heads,
+                             mask_see=see, mask_edit=see, key_scale_of=ks_of)
+        check(host(dl), ref, f"run near={near} latent")
+    # empty cache: a miss, plain generation
+    dl = dev_f32(noise)
+    res = B.chorus_denoise_run(md.model, md.arr, md.dglue, dl, torch.empty(0, bs.cache_d, device=DEV),
+                               torch.empty((0,) + bs.latent_shape, device=DEV), dev_f32(q), 0.75, md.sigmas, md.d_tmods,
+                               md.d_theads, md.d_ctx)
+    assert (res["index"], res["hit"], res["K1"], res["K2"]) == (-1, False, 0, 0)
+    check(host(dl), ref, "run empty cache latent")
