@@ -187,17 +187,18 @@ int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_w
 int32_t chorus_stage1_copy(float* latent, const float* SL, int64_t n, void* stream);
 
 /* ------------------------------------------------------------------------
- * Per-kernel timing for benchmarks. When enabled, chorus_dit_block_step brackets
- * its kernels with HIP events on the caller's stream; chorus_prof_read waits for
- * them and returns the summed milliseconds and the launch count of one kernel
- * class since the last reset. Not thread-safe; off by default.
+ * Per-kernel timing for benchmarks. chorus_prof_enable takes a bit mask of kernel
+ * classes (bit c = class c; 0 = off, the default). For the enabled classes
+ * chorus_dit_block_step brackets the launches with HIP events on the caller's
+ * stream; chorus_prof_read waits for them and returns the summed milliseconds and
+ * the launch count of one class since the last reset. Not thread-safe.
  * ------------------------------------------------------------------------ */
 #define CHORUS_PROF_SELF_ATTN 0
 #define CHORUS_PROF_CROSS_ATTN 1
 #define CHORUS_PROF_GEMM 2
 #define CHORUS_PROF_NORM 3
 #define CHORUS_PROF_CLASSES 4
-int32_t chorus_prof_enable(int32_t on);
+int32_t chorus_prof_enable(int32_t class_mask);
 int32_t chorus_prof_reset(void);
 int32_t chorus_prof_read(int32_t kernel_class, double* total_ms, int32_t* launches);
 

@@ -565,8 +565,12 @@ def chorus_denoise_run(model: ModelShape, blocks_arr, glue: DeviceGlue, latent, 
     return dict(index=res.index, score=res.score, hit=bool(res.hit), K1=res.K1, K2=res.K2, Ls=res.Ls)
 
 
-def prof_enable(on=True):
-    load().chorus_prof_enable(1 if on else 0)
+def prof_enable(classes=()):
+    """classes: iterable of PROF_* ids to time (empty = off)."""
+    mask = 0
+    for c in classes:
+        mask |= 1 << c
+    load().chorus_prof_enable(mask)
 
 
 def prof_reset():

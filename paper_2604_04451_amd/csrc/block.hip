@@ -13,7 +13,7 @@ struct ProfRec {
   int cls;
   hipEvent_t a, b;
 };
-bool g_prof_on = false;
+unsigned g_prof_mask = 0;  // bit c set: kernel class c is timed
 std::vector<ProfRec> g_prof;
 
 struct ProfScope {
@@ -21,7 +21,7 @@ struct ProfScope {
   ProfRec rec;
   bool live;
   ProfScope(int cls, hipStream_t st) : s(st), live(false) {
-    if (!g_prof_on) return;
+    if (!(g_prof_mask & (1u << cls))) return;
     rec.cls = cls;
     if (hipEventCreate(&rec.a) != hipSuccess) return;
     if (hipEventCreate(&rec.b) != hipSuccess) {
@@ -106,8 +106,8 @@ using namespace chorus;
 
 extern "C" {
 
-int32_t chorus_prof_enable(int32_t on) {
-  g_prof_on = on != 0;
+int32_t chorus_prof_enable(int32_t class_mask) {
+  g_prof_mask = (unsigned)class_mask & ((1u << CHORUS_PROF_CLASSES) - 1u);
   return CHORUS_OK;
 }
 
