@@ -118,6 +118,13 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void attention_kernel(
 
   load_tile(0);
   store_tile(0);
+  // Pin the Q fragments in registers here. Without this the compiler sinks their loads
+  // into the loop, and the waits it then needs inside the loop also wait for the prefetch
+  // of tile kt+1, exposing the global latency every iteration.
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+    for (int s = 0; s < SK; ++s) asm volatile("" : "+v"(qf[qb][s]));
   __syncthreads();
 
   for (int kt = 0; kt < ntiles; ++kt) {
@@ -250,6 +257,269 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void attention_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------
+// Ping-pong variant: 8 waves, one block of 32 query rows each, two groups of four
+// waves (one wave of each group per SIMD). A wave alternates between a VALU phase
+// (softmax of tile j) and an MFMA phase (O += V(j) P(j), then S(j+1) = K(j+1) Q^T),
+// separated by workgroup barriers; group 1 runs one phase behind group 0, so on
+// every SIMD one wave feeds the matrix pipe while the other runs the softmax.
+//
+// LDS holds two K and two V^T tiles. In its MFMA phase of tile j a wave first
+// stores the registers it prefetched one iteration earlier (K(j+2) into the
+// buffer S(j) was read from, V(j+1) into the buffer of V(j-1)), then issues the
+// global loads for K(j+3) and V(j+2). Both groups have finished reading a buffer
+// at least one barrier before either group overwrites it.
+// ---------------------------------------------------------------------------
+template <int DH, bool COLSCALE>
+__global__ __launch_bounds__(512, 2) void attention_pp_kernel(
+    const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vt,
+    uint16_t* __restrict__ O, const float* __restrict__ col_scale, long Lq, long Lk, long LqPad, long LkPad, int H,
+    int n_qtiles, float scale_log2) {
+  constexpr int NT = 512;
+  constexpr int KS = AttnSmem<DH>::KS, VS = AttnSmem<DH>::VS;
+  constexpr int K_LD = KT * (DH / 8) / NT;
+  constexpr int V_LD = DH * (KT / 8) / NT;
+  constexpr int SK = DH / 16;
+  constexpr int TD = DH / 32;
+  constexpr int QROWS = 8 * 32;
+
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+  AttnSmem<DH>& sm = *reinterpret_cast<AttnSmem<DH>*>(smem_raw);
+
+  const int tile_id = xcd_remap(blockIdx.x, H * n_qtiles);
+  const int head = tile_id / n_qtiles;
+  const int qt = tile_id - head * n_qtiles;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int group = wave >> 2;
+  const int lrow = lane & 31, c = lane >> 5, lk = c * 8;
+  const long q_wave0 = (long)qt * QROWS + wave * 32;
+
+  const uint16_t* Kh = K + (long)head * LkPad * DH;
+  const uint16_t* Vh = Vt + (long)head * DH * LkPad;
+
+  bf16x8 qf[SK];
+  {
+    long q = q_wave0 + lrow;
+    if (q > Lq - 1) q = Lq - 1;
+    const uint16_t* qp = Q + ((long)head * LqPad + q) * DH + lk;
+#pragma unroll
+    for (int s = 0; s < SK; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
+  }
+
+  f32x16 o[TD];
+#pragma unroll
+  for (int t = 0; t < TD; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  const int ntiles = (int)((Lk + KT - 1) / KT);
+  u32x4 rk[K_LD], rv[V_LD];
+
+  auto load_k = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < K_LD; ++i)
+      rk[i] = *reinterpret_cast<const u32x4*>(Kh + (long)kt * KT * DH + (tid + NT * i) * 8);
+  };
+  auto load_v = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < V_LD; ++i) {
+      int id = tid + NT * i, row = id >> 3, ch = id & 7;
+      rv[i] = *reinterpret_cast<const u32x4*>(Vh + (long)row * LkPad + (long)kt * KT + ch * 8);
+    }
+  };
+  auto store_k = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < K_LD; ++i) {
+      int id = tid + NT * i, row = id / (DH / 8), ch = id % (DH / 8);
+      *reinterpret_cast<u32x4*>(&sm.k[buf][row * KS + ch * 8]) = rk[i];
+    }
+  };
+  auto store_v = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < V_LD; ++i) {
+      int id = tid + NT * i, row = id >> 3, ch = id & 7;
+      *reinterpret_cast<u32x4*>(&sm.v[buf][row * VS + ch * 8]) = rv[i];
+    }
+  };
+  f32x16 s[2];
+  auto compute_s = [&](int buf) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < SK; ++ks) {
+      bf16x8 kf[2];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+        kf[kb] = *reinterpret_cast<const bf16x8*>(&sm.k[buf][(32 * kb + lrow) * KS + 16 * ks + lk]);
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], qf[ks], s[kb], 0, 0, 0);
+    }
+  };
+
+  // prologue: K(0), V(0), K(1) into LDS; K(2), V(1) into the prefetch registers
+  load_k(0);
+  load_v(0);
+  store_k(0);
+  store_v(0);
+  if (ntiles > 1) {
+    load_k(1);
+    store_k(1);
+    load_v(1);
+  }
+  if (ntiles > 2) load_k(2);
+#pragma unroll
+  for (int sI = 0; sI < SK; ++sI) asm volatile("" : "+v"(qf[sI]));  // Q fragments resident before the loop
+  __syncthreads();
+  compute_s(0);
+  __syncthreads();
+  if (group == 1) __builtin_amdgcn_s_barrier();  // run one phase behind group 0
+
+  for (int j = 0; j < ntiles; ++j) {
+    // ================= VALU phase: softmax of tile j =================
+    __builtin_amdgcn_sched_barrier(0);
+    const long key0 = (long)j * KT + 4 * c;
+    if (COLSCALE) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          long key = key0 + 32 * kb + 8 * (r >> 2) + (r & 3);
+          s[kb][r] *= col_scale[key < Lk ? key : Lk - 1] * scale_log2;
+        }
+    }
+    if (j == ntiles - 1 && (Lk % KT) != 0) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          long key = key0 + 32 * kb + 8 * (r >> 2) + (r & 3);
+          if (key >= Lk) s[kb][r] = -INFINITY;
+        }
+    }
+    float mx = s[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mxs = COLSCALE ? mx : mx * scale_log2;
+    if (__any(mxs > m_run + 8.0f)) {
+      const float m_new = fmaxf(m_run, mxs);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int t = 0; t < TD; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[t][r] *= alpha;
+    }
+    bf16x8 pf[4];
+    {
+      const float mref = m_run;
+      float lsum = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        float p[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float a = COLSCALE ? (s[kb][r] - mref) : __builtin_fmaf(s[kb][r], scale_log2, -mref);
+          p[r] = __builtin_amdgcn_exp2f(a);
+          lsum += p[r];
+        }
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) pf[2 * kb + h2][e] = (bf16_t)p[8 * h2 + e];
+      }
+      l_run += lsum;
+    }
+    // the probabilities must exist before the barrier (otherwise the compiler sinks the
+    // exponentials into the MFMA phase, which defeats the phase split)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) asm volatile("" : "+v"(pf[i]));
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ================= MFMA phase: O += V(j) P(j); S(j+1) = K(j+1) Q^T =================
+    // Branch-free on purpose (one basic block the scheduler can pipeline): past the last
+    // tiles the prefetch re-reads the final tile and the extra stores / S tile are never used.
+    __builtin_amdgcn_s_setprio(1);
+    store_k(j & 1);
+    store_v((j + 1) & 1);
+    load_k(j + 3 < ntiles ? j + 3 : ntiles - 1);
+    load_v(j + 2 < ntiles ? j + 2 : ntiles - 1);
+    {
+      const int vb = j & 1;
+#pragma unroll
+      for (int t = 0; t < TD; ++t) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(&sm.v[vb][(32 * t + lrow) * VS + 16 * ks + lk]);
+          o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks], o[t], 0, 0, 0);
+        }
+      }
+    }
+    compute_s((j + 1) & 1);
+    // issue order: LDS stores, global prefetch, then LDS operand reads kept 6 ahead of the MFMAs
+    __builtin_amdgcn_sched_group_barrier(0x200, K_LD + V_LD, 0);
+    __builtin_amdgcn_sched_group_barrier(0x020, K_LD + V_LD, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+    for (int i = 0; i < 4 * TD + 2 * SK - 6; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
+    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wave's LDS stores are done; global prefetch stays in flight
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  if (group == 0) __builtin_amdgcn_s_barrier();  // every wave executes the same number of barriers
+
+  const int D = H * DH;
+  const float l = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.0f / l;
+  const long q = q_wave0 + lrow;
+  if (q < Lq) {
+    uint16_t* op = O + q * (long)D + head * DH + 4 * c;
+#pragma unroll
+    for (int t = 0; t < TD; ++t)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        uint2 w;
+        w.x = pack_bf16x2(o[t][4 * jj + 0] * inv, o[t][4 * jj + 1] * inv);
+        w.y = pack_bf16x2(o[t][4 * jj + 2] * inv, o[t][4 * jj + 3] * inv);
+        *reinterpret_cast<uint2*>(op + 32 * t + 8 * jj) = w;
+      }
+  }
+}
+
+template <int DH, bool CS>
+int32_t launch_attn_pp(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, const float* cs, long Lq,
+                       long Lk, long LqPad, long LkPad, int H, hipStream_t s) {
+  long nqt = (Lq + 255) / 256;
+  if (nqt * H > 0x7fffffffL) return CHORUS_E_SHAPE;
+  size_t smem = sizeof(AttnSmem<DH>);
+  auto kern = attention_pp_kernel<DH, CS>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    CHORUS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)smem));
+    attr_done = true;
+  }
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(nqt * H)), dim3(512), smem, s, Q, K, Vt, O, cs, Lq, Lk, LqPad, LkPad, H,
+                     (int)nqt, scale_log2);
+  CHORUS_LAUNCH_CHECK();
+  return CHORUS_OK;
+}
+
 template <int DH, int QB, int NW, bool CS>
 int32_t launch_attn(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, const float* cs, long Lq,
                     long Lk, long LqPad, long LkPad, int H, hipStream_t s) {
@@ -276,7 +546,7 @@ int32_t launch_attn(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, ui
 
 using namespace chorus;
 
-// variant: 0 = default for the shape; 1 = 8 waves x 32 rows; 2 = 4 waves x 64 rows
+// variant: 0 = default; 1 = 8 waves x 32 rows; 2 = 4 waves x 64 rows; 3 = 8 waves, ping-pong phases
 extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O,
                                     const float* col_scale, int64_t Lq, int64_t Lk, int64_t LqPad, int64_t LkPad,
                                     int32_t H, int32_t dh, int32_t variant, void* stream) {
@@ -288,10 +558,17 @@ extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const 
   if (!aligned16(Q) || !aligned16(K) || !aligned16(Vt) || !aligned16(O)) return CHORUS_E_ARG;
   hipStream_t s = (hipStream_t)stream;
   const bool cs = col_scale != nullptr;
-  if (variant == 0) variant = cs ? 1 : 2;  // the column-scale kernel needs the leaner 8-wave shape
+  if (variant == 0) variant = 3;  // ping-pong phases: one wave per SIMD on the matrix pipe, one on the softmax
 #define ATTN(DHV, QBV, NWV)                                                                               \
   (cs ? launch_attn<DHV, QBV, NWV, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)              \
       : launch_attn<DHV, QBV, NWV, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s))
+  if (variant == 3) {
+    if (dh == 128)
+      return cs ? launch_attn_pp<128, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
+                : launch_attn_pp<128, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
+    return cs ? launch_attn_pp<64, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
+              : launch_attn_pp<64, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
+  }
   if (dh == 128) {
     if (variant == 1) return ATTN(128, 1, 8);
     return ATTN(128, 2, 4);

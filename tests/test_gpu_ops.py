@@ -133,7 +133,7 @@ def _attn_case(H, dh, Lq, Lk, variant, col_scale=None, q_std=1.0, seed=0, name="
                  max_abs=max(np.abs(ref).max() * 2 ** -7, 2e-3), rel_l2=5e-3)
 
 
-@pytest.mark.parametrize("variant", [1, 2])
+@pytest.mark.parametrize("variant", [1, 2, 3])
 @pytest.mark.parametrize("H,dh,Lq,Lk", [(2, 64, 300, 300), (3, 128, 500, 333), (1, 128, 1, 1), (2, 128, 64, 64),
                                         (2, 64, 257, 65), (12, 128, 1200, 1200), (4, 64, 256, 16)])
 def test_attention_plain(H, dh, Lq, Lk, variant):
@@ -141,7 +141,7 @@ def test_attention_plain(H, dh, Lq, Lk, variant):
     _attn_case(H, dh, Lq, Lk, variant, name="plain")
 
 
-@pytest.mark.parametrize("variant", [1, 2])
+@pytest.mark.parametrize("variant", [1, 2, 3])
 def test_attention_peaked(variant):
     """Logits with std ~4: rows dominated by few keys; catches masking / rescale mistakes that
     near-uniform rows (output ~ mean V) would hide."""
@@ -150,7 +150,7 @@ def test_attention_peaked(variant):
     _attn_case(2, 64, 333, 2000, variant, q_std=2.0, seed=4, name="peaked64")
 
 
-@pytest.mark.parametrize("variant", [1, 2])
+@pytest.mark.parametrize("variant", [1, 2, 3])
 @pytest.mark.parametrize("H,dh,Lq,Lt", [(4, 64, 256, 16), (12, 128, 700, 512), (2, 128, 100, 77)])
 def test_attention_tgaa_column_scale(H, dh, Lq, Lt, variant):
     print(f"[case] cross-attention TGAA H={H} dh={dh} Lq={Lq} Lt={Lt} variant={variant}", flush=True)
