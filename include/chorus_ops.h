@@ -37,6 +37,9 @@ int32_t chorus_gemm_bf16(const uint16_t* A, const uint16_t* W, int64_t M, int32_
                          void* out, const float* bias, const float* gate0, const float* gate1, float scale,
                          void* stream);
 
+/* Benchmark hook: 0 = default kernel choice, 1 = never use the direct-to-LDS 256x256 kernel. Host only. */
+int32_t chorus_gemm_set_variant(int32_t v);
+
 /* out bf16 [L, D] = LN(x) * (mul_base + mul0 + mul1) + (add0 + add1), LN over D without
  * affine, eps 1e-6; mul_base = 1 if plus_one else 0; mul1/add1 may be NULL.
  * AdaLN modulation: mul = scale rows of (table, t_mod), add = shift rows, plus_one = 1.

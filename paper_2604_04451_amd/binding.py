@@ -119,6 +119,7 @@ def _bind_ops(lib):
     GW, MS = C.POINTER(GlueWeights), C.POINTER(ModelShape)
     ops = {
         "chorus_gemm_bf16": (i32, [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, f32, vp]),
+        "chorus_gemm_set_variant": (i32, [i32]),
         "chorus_ln_modulate": (i32, [vp, vp, i64, i32, vp, vp, vp, vp, i32, vp]),
         "chorus_qk_norm_rope": (i32, [vp, i64, vp, vp, i64, i64, i32, i32, vp, i32, i32, i32, i32, vp]),
         "chorus_v_transpose": (i32, [vp, i64, vp, i64, i64, i32, vp]),

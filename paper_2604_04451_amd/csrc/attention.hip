@@ -270,21 +270,24 @@ __global__ __launch_bounds__(NW * 64, NW / 4) void attention_kernel(
 // global loads for K(j+3) and V(j+2). Both groups have finished reading a buffer
 // at least one barrier before either group overwrites it.
 // ---------------------------------------------------------------------------
-template <int DH, bool COLSCALE>
+template <int DH, int KTL, bool COLSCALE>
 __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vt,
     uint16_t* __restrict__ O, const float* __restrict__ col_scale, long Lq, long Lk, long LqPad, long LkPad, int H,
     int n_qtiles, float scale_log2) {
   constexpr int NT = 512;
-  constexpr int KS = AttnSmem<DH>::KS, VS = AttnSmem<DH>::VS;
-  constexpr int K_LD = KT * (DH / 8) / NT;
-  constexpr int V_LD = DH * (KT / 8) / NT;
+  constexpr int KS = DH + 8, VS = KTL + 8;  // padded LDS row strides (elements)
+  constexpr int KB = KTL / 32;                // 32-key blocks of S^T per tile
+  constexpr int NKS = KTL / 16;               // 16-key MFMA steps of P V per tile
+  constexpr int K_LD = KTL * (DH / 8) / NT;
+  constexpr int V_LD = DH * (KTL / 8) / NT;
   constexpr int SK = DH / 16;
   constexpr int TD = DH / 32;
   constexpr int QROWS = 8 * 32;
 
   extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
-  AttnSmem<DH>& sm = *reinterpret_cast<AttnSmem<DH>*>(smem_raw);
+  uint16_t* smk = reinterpret_cast<uint16_t*>(smem_raw);   // [2][KTL][KS]
+  uint16_t* smv = smk + 2 * KTL * KS;                      // [2][DH][VS]
 
   const int tile_id = xcd_remap(blockIdx.x, H * n_qtiles);
   const int head = tile_id / n_qtiles;
@@ -313,49 +316,49 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
     for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  const int ntiles = (int)((Lk + KT - 1) / KT);
+  const int ntiles = (int)((Lk + KTL - 1) / KTL);
   u32x4 rk[K_LD], rv[V_LD];
 
   auto load_k = [&](int kt) {
 #pragma unroll
     for (int i = 0; i < K_LD; ++i)
-      rk[i] = *reinterpret_cast<const u32x4*>(Kh + (long)kt * KT * DH + (tid + NT * i) * 8);
+      rk[i] = *reinterpret_cast<const u32x4*>(Kh + (long)kt * KTL * DH + (tid + NT * i) * 8);
   };
   auto load_v = [&](int kt) {
 #pragma unroll
     for (int i = 0; i < V_LD; ++i) {
-      int id = tid + NT * i, row = id >> 3, ch = id & 7;
-      rv[i] = *reinterpret_cast<const u32x4*>(Vh + (long)row * LkPad + (long)kt * KT + ch * 8);
+      int id = tid + NT * i, row = id / (KTL / 8), ch = id % (KTL / 8);
+      rv[i] = *reinterpret_cast<const u32x4*>(Vh + (long)row * LkPad + (long)kt * KTL + ch * 8);
     }
   };
   auto store_k = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < K_LD; ++i) {
       int id = tid + NT * i, row = id / (DH / 8), ch = id % (DH / 8);
-      *reinterpret_cast<u32x4*>(&sm.k[buf][row * KS + ch * 8]) = rk[i];
+      *reinterpret_cast<u32x4*>(&smk[(buf * KTL + row) * KS + ch * 8]) = rk[i];
     }
   };
   auto store_v = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < V_LD; ++i) {
-      int id = tid + NT * i, row = id >> 3, ch = id & 7;
-      *reinterpret_cast<u32x4*>(&sm.v[buf][row * VS + ch * 8]) = rv[i];
+      int id = tid + NT * i, row = id / (KTL / 8), ch = id % (KTL / 8);
+      *reinterpret_cast<u32x4*>(&smv[(buf * DH + row) * VS + ch * 8]) = rv[i];
     }
   };
-  f32x16 s[2];
+  f32x16 s[KB];
   auto compute_s = [&](int buf) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < SK; ++ks) {
-      bf16x8 kf[2];
+      bf16x8 kf[KB];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-        kf[kb] = *reinterpret_cast<const bf16x8*>(&sm.k[buf][(32 * kb + lrow) * KS + 16 * ks + lk]);
+      for (int kb = 0; kb < KB; ++kb)
+        kf[kb] = *reinterpret_cast<const bf16x8*>(&smk[(buf * KTL + 32 * kb + lrow) * KS + 16 * ks + lk]);
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], qf[ks], s[kb], 0, 0, 0);
+      for (int kb = 0; kb < KB; ++kb) s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], qf[ks], s[kb], 0, 0, 0);
     }
   };
 
@@ -375,24 +378,24 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
   __syncthreads();
   compute_s(0);
   __syncthreads();
-  if (group == 1) __builtin_amdgcn_s_barrier();  // run one phase behind group 0
+  if (group == 1) lds_barrier();  // run one phase behind group 0
 
   for (int j = 0; j < ntiles; ++j) {
     // ================= VALU phase: softmax of tile j =================
     __builtin_amdgcn_sched_barrier(0);
-    const long key0 = (long)j * KT + 4 * c;
+    const long key0 = (long)j * KTL + 4 * c;
     if (COLSCALE) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           long key = key0 + 32 * kb + 8 * (r >> 2) + (r & 3);
           s[kb][r] *= col_scale[key < Lk ? key : Lk - 1] * scale_log2;
         }
     }
-    if (j == ntiles - 1 && (Lk % KT) != 0) {
+    if (j == ntiles - 1 && (Lk % KTL) != 0) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           long key = key0 + 32 * kb + 8 * (r >> 2) + (r & 3);
@@ -401,7 +404,7 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
     }
     float mx = s[0][0];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
@@ -416,12 +419,12 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[t][r] *= alpha;
     }
-    bf16x8 pf[4];
+    bf16x8 pf[NKS];
     {
       const float mref = m_run;
       float lsum = 0.f;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+      for (int kb = 0; kb < KB; ++kb) {
         float p[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -439,9 +442,9 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
     // the probabilities must exist before the barrier (otherwise the compiler sinks the
     // exponentials into the MFMA phase, which defeats the phase split)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) asm volatile("" : "+v"(pf[i]));
+    for (int i = 0; i < NKS; ++i) asm volatile("" : "+v"(pf[i]));
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_barrier();
+    lds_barrier();
     __builtin_amdgcn_sched_barrier(0);
 
     // ================= MFMA phase: O += V(j) P(j); S(j+1) = K(j+1) Q^T =================
@@ -457,8 +460,8 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
 #pragma unroll
       for (int t = 0; t < TD; ++t) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(&sm.v[vb][(32 * t + lrow) * VS + 16 * ks + lk]);
+        for (int ks = 0; ks < NKS; ++ks) {
+          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(&smv[(vb * DH + 32 * t + lrow) * VS + 16 * ks + lk]);
           o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks], o[t], 0, 0, 0);
         }
       }
@@ -469,18 +472,17 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
     __builtin_amdgcn_sched_group_barrier(0x020, K_LD + V_LD, 0);
     __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
 #pragma unroll
-    for (int i = 0; i < 4 * TD + 2 * SK - 6; ++i) {
+    for (int i = 0; i < NKS * TD + KB * SK - 6; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
     __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
     __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wave's LDS stores are done; global prefetch stays in flight
-    __builtin_amdgcn_s_barrier();
+    lds_barrier();  // this wave's LDS stores are done; the global prefetch stays in flight
     __builtin_amdgcn_sched_barrier(0);
   }
-  if (group == 0) __builtin_amdgcn_s_barrier();  // every wave executes the same number of barriers
+  if (group == 0) lds_barrier();  // every wave executes the same number of barriers
 
   const int D = H * DH;
   const float l = l_run + __shfl_xor(l_run, 32, 64);
@@ -500,13 +502,13 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
   }
 }
 
-template <int DH, bool CS>
+template <int DH, int KTL, bool CS>
 int32_t launch_attn_pp(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, const float* cs, long Lq,
                        long Lk, long LqPad, long LkPad, int H, hipStream_t s) {
   long nqt = (Lq + 255) / 256;
   if (nqt * H > 0x7fffffffL) return CHORUS_E_SHAPE;
-  size_t smem = sizeof(AttnSmem<DH>);
-  auto kern = attention_pp_kernel<DH, CS>;
+  size_t smem = 2 * ((size_t)KTL * (DH + 8) + (size_t)DH * (KTL + 8)) * sizeof(uint16_t);
+  auto kern = attention_pp_kernel<DH, KTL, CS>;
   static bool attr_done = false;
   if (!attr_done) {
     CHORUS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -564,10 +566,18 @@ extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const 
       : launch_attn<DHV, QBV, NWV, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s))
   if (variant == 3) {
     if (dh == 128)
-      return cs ? launch_attn_pp<128, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
-                : launch_attn_pp<128, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
-    return cs ? launch_attn_pp<64, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
-              : launch_attn_pp<64, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
+      return cs ? launch_attn_pp<128, 64, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
+                : launch_attn_pp<128, 64, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
+    return cs ? launch_attn_pp<64, 64, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
+              : launch_attn_pp<64, 64, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
+  }
+  if (variant == 4) {  // 128-key tiles (needs LkPad % 128 == 0)
+    if (LkPad % 128) return CHORUS_E_SHAPE;
+    if (dh == 128)
+      return cs ? launch_attn_pp<128, 128, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
+                : launch_attn_pp<128, 128, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
+    return cs ? launch_attn_pp<64, 128, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
+              : launch_attn_pp<64, 128, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
   }
   if (dh == 128) {
     if (variant == 1) return ATTN(128, 1, 8);

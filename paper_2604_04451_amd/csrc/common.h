@@ -69,6 +69,16 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Workgroup barrier that orders LDS traffic only: waits for this wave's LDS operations
+// (lgkmcnt) but leaves global loads in flight, unlike __syncthreads(), whose fences also
+// drain vmcnt and would expose the latency of every prefetch. The fences keep the compiler
+// from moving LDS accesses across the barrier.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // Workgroup id -> logical tile id such that the workgroups that land on one XCD
 // (hardware deals consecutive ids round-robin over the 8 XCDs) cover one
 // contiguous range of logical ids and so share operands in that XCD's L2.
