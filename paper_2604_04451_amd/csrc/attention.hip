@@ -560,7 +560,9 @@ extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const 
   if (!aligned16(Q) || !aligned16(K) || !aligned16(Vt) || !aligned16(O)) return CHORUS_E_ARG;
   hipStream_t s = (hipStream_t)stream;
   const bool cs = col_scale != nullptr;
-  if (variant == 0) variant = 3;  // ping-pong phases: one wave per SIMD on the matrix pipe, one on the softmax
+  // ping-pong phases (one wave per SIMD on the matrix pipe, one on the softmax); 128-key tiles
+  // when the padding allows and no column scale is needed (that kernel would spill registers)
+  if (variant == 0) variant = (!cs && LkPad % 128 == 0 && Lk > 128) ? 4 : 3;
 #define ATTN(DHV, QBV, NWV)                                                                               \
   (cs ? launch_attn<DHV, QBV, NWV, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)              \
       : launch_attn<DHV, QBV, NWV, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s))

@@ -12,7 +12,10 @@ constexpr int kRowsPerBlock = 4;  // one wave per cache row
 
 // One wave per row: lanes stride over the row in float4, then a butterfly
 // reduction. The order of additions depends only on d, never on the row index,
-// so identical rows produce identical scores.
+// so identical rows produce identical values. The kernel stores r_j = <q, c_j> / |c_j|;
+// the query norm is a positive constant for the whole scan and is applied once, in the
+// argmax kernel (score_j = r_j / |q|), which keeps this HBM-bound loop at 8 FMAs per
+// 16 bytes read.
 __global__ __launch_bounds__(256) void lookup_scores_kernel(const float* __restrict__ cache,
                                                             const float* __restrict__ query, float* __restrict__ scores,
                                                             long N, int d) {
@@ -22,7 +25,7 @@ __global__ __launch_bounds__(256) void lookup_scores_kernel(const float* __restr
   const float4* c4 = reinterpret_cast<const float4*>(cache + row * (long)d);
   const float4* q4 = reinterpret_cast<const float4*>(query);
   const int n4 = d >> 2;
-  float dot = 0.f, cc = 0.f, qq = 0.f;
+  float dot = 0.f, cc = 0.f;
   int i = lane;
   // 8 independent 16-byte loads in flight per lane
   for (; i + 7 * 64 < n4; i += 8 * 64) {
@@ -35,7 +38,6 @@ __global__ __launch_bounds__(256) void lookup_scores_kernel(const float* __restr
     for (int u = 0; u < 8; ++u) {
       dot += c[u].x * q[u].x + c[u].y * q[u].y + c[u].z * q[u].z + c[u].w * q[u].w;
       cc += c[u].x * c[u].x + c[u].y * c[u].y + c[u].z * c[u].z + c[u].w * c[u].w;
-      qq += q[u].x * q[u].x + q[u].y * q[u].y + q[u].z * q[u].z + q[u].w * q[u].w;
     }
   }
   for (; i < n4; i += 64) {
@@ -43,24 +45,29 @@ __global__ __launch_bounds__(256) void lookup_scores_kernel(const float* __restr
     float4 q = q4[i];
     dot += c.x * q.x + c.y * q.y + c.z * q.z + c.w * q.w;
     cc += c.x * c.x + c.y * c.y + c.z * c.z + c.w * c.w;
-    qq += q.x * q.x + q.y * q.y + q.z * q.z + q.w * q.w;
   }
   dot = wave_sum(dot);
   cc = wave_sum(cc);
-  qq = wave_sum(qq);
   if (lane == 0) {
-    float denom = sqrtf(qq) * sqrtf(cc);
-    float s = denom > 0.f ? dot / denom : -INFINITY;
+    float nc = sqrtf(cc);
+    float s = nc > 0.f ? dot / nc : -INFINITY;
     if (!(s == s)) s = -INFINITY;
     scores[row] = s;
   }
 }
 
-// Single workgroup: max score, lowest index among equal maxima.
-__global__ __launch_bounds__(1024) void lookup_argmax_kernel(const float* __restrict__ scores, long N, float tau,
+// Single workgroup: |q|, then max score with the lowest index among equal maxima.
+__global__ __launch_bounds__(1024) void lookup_argmax_kernel(const float* __restrict__ scores, long N,
+                                                             const float* __restrict__ query, int d, float tau,
                                                              chorus_lookup_result* __restrict__ out) {
   __shared__ float sv[16];
   __shared__ long si[16];
+  __shared__ float sq[16];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int nw = blockDim.x >> 6;
+  float qq = 0.f;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) qq += query[i] * query[i];
+  qq = wave_sum(qq);
   float best = -INFINITY;
   long bi = N > 0 ? N : -1;  // sentinel larger than any index
   for (long j = threadIdx.x; j < N; j += blockDim.x) {
@@ -79,14 +86,15 @@ __global__ __launch_bounds__(1024) void lookup_argmax_kernel(const float* __rest
       bi = oi;
     }
   }
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   if (lane == 0) {
     sv[wave] = best;
     si[wave] = bi;
+    sq[wave] = qq;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    const int nw = blockDim.x >> 6;
+    float qsum = 0.f;
+    for (int w = 0; w < nw; ++w) qsum += sq[w];
     for (int w = 1; w < nw; ++w) {
       if (sv[w] > best || (sv[w] == best && si[w] < bi)) {
         best = sv[w];
@@ -99,9 +107,13 @@ __global__ __launch_bounds__(1024) void lookup_argmax_kernel(const float* __rest
       r.score = -INFINITY;
       r.hit = 0;
     } else {
-      r.index = (int32_t)(bi >= N ? 0 : bi);  // all scores -inf: index 0, like a first-maximum scan
-      r.score = best;
-      r.hit = best >= tau ? 1 : 0;
+      const float nq = sqrtf(qsum);
+      float m = (nq > 0.f && best > -INFINITY) ? best / nq : -INFINITY;
+      if (!(m == m)) m = -INFINITY;
+      // every score -inf (zero-norm query or rows): index 0, like a first-maximum scan
+      r.index = (int32_t)((bi >= N || m == -INFINITY) ? 0 : bi);
+      r.score = m;
+      r.hit = m >= tau ? 1 : 0;
     }
     *out = r;
   }
@@ -134,7 +146,7 @@ int32_t chorus_cache_lookup(const float* cache_emb, int64_t N, int32_t d, const 
     hipLaunchKernelGGL(lookup_scores_kernel, dim3(grid), dim3(256), 0, s, cache_emb, query, scores, (long)N, d);
     CHORUS_LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL(lookup_argmax_kernel, dim3(1), dim3(1024), 0, s, scores, (long)N, tau, out);
+  hipLaunchKernelGGL(lookup_argmax_kernel, dim3(1), dim3(1024), 0, s, scores, (long)N, query, d, tau, out);
   CHORUS_LAUNCH_CHECK();
   return CHORUS_OK;
 }

@@ -107,35 +107,65 @@ __global__ __launch_bounds__(256) void move_rows_kernel(V* __restrict__ dst, con
   }
 }
 
-// Eq. 6 as a select. One thread per float4 along W; the source that is not
-// selected is not read unless the four elements straddle tokens that disagree.
+// Eq. 6 as a select. A thread owns kBlendU float4 (along W) spaced a grid apart and issues
+// all their loads before any store; the source that is not selected is not read unless the
+// four elements straddle tokens that disagree.
+constexpr int kBlendU = 4;
+
+template <int PW>  // PW > 0: patch width known at compile time (1, 2 or 4); 0: runtime pw
 __global__ __launch_bounds__(256) void blend_vec4_kernel(float4* out, const float4* Lc, const float4* SL,  // out may alias a source
-                                                        
-                                                         const uint8_t* __restrict__ mask, long nvec, int T, int H,
-                                                         int W4, int ph, int pw, int Hm, int Wm) {
-  long v = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (v >= nvec) return;
-  int x4 = (int)(v % W4);
-  long row = v / W4;
-  int y = (int)(row % H);
-  int t = (int)((row / H) % T);
-  const uint8_t* mrow = mask + ((long)t * Hm + y / ph) * Wm;
-  int x = x4 * 4;
-  bool m0 = mrow[(x + 0) / pw] != 0, m1 = mrow[(x + 1) / pw] != 0, m2 = mrow[(x + 2) / pw] != 0,
-       m3 = mrow[(x + 3) / pw] != 0;
-  float4 r;
-  if (m0 && m1 && m2 && m3) {
-    r = ld_stream_f4(&Lc[v]);
-  } else if (!(m0 || m1 || m2 || m3)) {
-    r = ld_stream_f4(&SL[v]);
-  } else {
-    float4 a = Lc[v], b = SL[v];
-    r.x = m0 ? a.x : b.x;
-    r.y = m1 ? a.y : b.y;
-    r.z = m2 ? a.z : b.z;
-    r.w = m3 ? a.w : b.w;
+                                                         const uint8_t* __restrict__ mask, unsigned nvec, unsigned T,
+                                                         unsigned H, unsigned W4, unsigned ph, unsigned pw,
+                                                         unsigned Hm, unsigned Wm) {
+  // 32-bit index arithmetic on purpose: 64-bit divisions cost more than the memory traffic here
+  const unsigned stride = gridDim.x * blockDim.x;
+  const unsigned v0 = blockIdx.x * blockDim.x + threadIdx.x;
+  f32x4 a[kBlendU], b[kBlendU];  // native vectors: arrays of HIP's float4 struct would live in scratch memory
+  int sel[kBlendU];  // bit e set: element e keeps L; -1: out of range
+#pragma unroll
+  for (int u = 0; u < kBlendU; ++u) {
+    const unsigned v = v0 + u * stride;
+    sel[u] = -1;
+    if (v >= nvec) continue;
+    const unsigned row = v / W4;
+    const unsigned x4 = v - row * W4;
+    const unsigned rt = row / H;
+    const unsigned y = row - rt * H;
+    const unsigned t = rt % T;
+    const uint8_t* mrow = mask + (t * Hm + y / ph) * Wm;
+    const unsigned x = x4 * 4;
+    int m = 0;
+    if (PW == 2) {
+      m = (mrow[x >> 1] != 0 ? 3 : 0) | (mrow[(x >> 1) + 1] != 0 ? 12 : 0);
+    } else if (PW == 4) {
+      m = mrow[x >> 2] != 0 ? 15 : 0;
+    } else if (PW == 1) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) m |= (mrow[x + e] != 0) << e;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) m |= (mrow[(x + e) / pw] != 0) << e;
+    }
+    sel[u] = m;
+    if (m != 0) a[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(&Lc[v]));
+    if (m != 15) b[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(&SL[v]));
   }
-  st_stream_f4(&out[v], r);
+#pragma unroll
+  for (int u = 0; u < kBlendU; ++u) {
+    if (sel[u] < 0) continue;
+    const unsigned v = v0 + u * stride;
+    const int m = sel[u];
+    f32x4 r;
+    if (m == 15) {
+      r = a[u];
+    } else if (m == 0) {
+      r = b[u];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) r[e] = ((m >> e) & 1) ? a[u][e] : b[u][e];
+    }
+    __builtin_nontemporal_store(r, reinterpret_cast<f32x4*>(&out[v]));
+  }
 }
 
 __global__ __launch_bounds__(256) void blend_scalar_kernel(float* out, const float* Lc, const float* SL,
@@ -238,9 +268,18 @@ int32_t chorus_region_blend(float* out, const float* L, const float* SL, const u
   int Hm = H / ph, Wm = W / pw;
   if (W % 4 == 0 && aligned16(out) && aligned16(L) && aligned16(SL)) {
     int64_t nvec = n / 4;
-    if ((nvec + 255) / 256 > 0x7fffffffLL) return CHORUS_E_SHAPE;
-    hipLaunchKernelGGL(blend_vec4_kernel, dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, s, (float4*)out,
-                       (const float4*)L, (const float4*)SL, mask_edit, (long)nvec, T, H, W / 4, ph, pw, Hm, Wm);
+    const int64_t per_block = 256 * kBlendU;
+    if (nvec + per_block * 2 > 0x7fffffffLL) return CHORUS_E_SHAPE;  // the kernel indexes in 32 bits
+    const dim3 grid((unsigned)((nvec + per_block - 1) / per_block)), block(256);
+#define BLEND_LAUNCH(PWV)                                                                                        \
+  hipLaunchKernelGGL(blend_vec4_kernel<PWV>, grid, block, 0, s, (float4*)out, (const float4*)L, (const float4*)SL, \
+                     mask_edit, (unsigned)nvec, (unsigned)T, (unsigned)H, (unsigned)(W / 4), (unsigned)ph,        \
+                     (unsigned)pw, (unsigned)Hm, (unsigned)Wm)
+    if (pw == 2) BLEND_LAUNCH(2);
+    else if (pw == 4) BLEND_LAUNCH(4);
+    else if (pw == 1) BLEND_LAUNCH(1);
+    else BLEND_LAUNCH(0);
+#undef BLEND_LAUNCH
   } else {
     if ((n + 255) / 256 > 0x7fffffffLL) return CHORUS_E_SHAPE;
     hipLaunchKernelGGL(blend_scalar_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, out, L, SL, mask_edit,

@@ -94,10 +94,19 @@ int32_t chorus_denoise_step(const chorus_model_shape* model, const chorus_block_
 // ---------------------------------------------------------------------------
 namespace {
 
+constexpr int kCopyU = 4;  // float4 per thread, all loads issued before the stores
+
 __global__ __launch_bounds__(256) void stream_copy_kernel(float4* __restrict__ dst, const float4* __restrict__ src,
                                                           long n4) {
-  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n4) st_stream_f4(&dst[i], ld_stream_f4(&src[i]));
+  const long stride = (long)gridDim.x * blockDim.x;
+  const long i0 = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  f32x4 v[kCopyU];
+#pragma unroll
+  for (int u = 0; u < kCopyU; ++u)
+    if (i0 + u * stride < n4) v[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(&src[i0 + u * stride]));
+#pragma unroll
+  for (int u = 0; u < kCopyU; ++u)
+    if (i0 + u * stride < n4) __builtin_nontemporal_store(v[u], reinterpret_cast<f32x4*>(&dst[i0 + u * stride]));
 }
 
 __global__ void copy_tail_kernel(float* __restrict__ dst, const float* __restrict__ src, long from, long n) {
@@ -115,7 +124,7 @@ int32_t device_copy(float* dst, const float* src, long n, hipStream_t s) {
   if (n <= 0 || dst == src) return CHORUS_OK;
   long n4 = (aligned16(dst) && aligned16(src)) ? n / 4 : 0;
   if (n4 > 0) {
-    hipLaunchKernelGGL(stream_copy_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, (float4*)dst,
+    hipLaunchKernelGGL(stream_copy_kernel, dim3((unsigned)((n4 + 256 * kCopyU - 1) / (256 * kCopyU))), dim3(256), 0, s, (float4*)dst,
                        (const float4*)src, n4);
     CHORUS_LAUNCH_CHECK();
   }
