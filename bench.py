@@ -28,6 +28,13 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
+# Bytes that leave / enter L2 per self-attention launch of the default workload (stage-2
+# launches at 13104 tokens and stage-3 launches at 32760 tokens, weighted 30:60), from the
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/bench_wan1p3b_480p_pmc_traffic.txt (FETCH_SIZE scaled by 1.992, the factor a plain
+# 8.39 MB copy kernel of the same run shows; WRITE_SIZE by 1.000). Counters cannot be read
+# inside this process, so the figure is only reported for that exact workload.
+SELF_ATTN_TRAFFIC_BYTES_DEFAULT = 7.69e8
 
 
 def block_flops(Ls, D, F, Lt):
@@ -180,7 +187,10 @@ def main():
         "self_attn_tflops": round(attn_tflops, 2),
         "self_attn_ms_per_launch": round(attn_ms / max(attn_n, 1), 4),
         "roofline": {"bound": "mfma", "achieved": round(attn_tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(attn_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(attn_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": (SELF_ATTN_TRAFFIC_BYTES_DEFAULT if (args.workload == "wan1p3b_480p" and args.blocks is None
+                                                                      and args.region == 0.4 and not args.bernoulli) else None),
+                     "algorithmic_bytes": (30 * 4 * 2.0 * Ls * D + 60 * 4 * 2.0 * L * D) / 90.0,
                      "kernel": "attention_kernel (self-attention)", "launches": attn_n},
     }
     if args.plain:

@@ -562,7 +562,7 @@ extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const 
   const bool cs = col_scale != nullptr;
   // ping-pong phases (one wave per SIMD on the matrix pipe, one on the softmax); 128-key tiles
   // when the padding allows and no column scale is needed (that kernel would spill registers)
-  if (variant == 0) variant = (!cs && LkPad % 128 == 0 && Lk > 128) ? 4 : 3;
+  if (variant == 0) variant = (!cs && LkPad % 128 == 0 && Lk >= 2048) ? 4 : 3;
 #define ATTN(DHV, QBV, NWV)                                                                               \
   (cs ? launch_attn<DHV, QBV, NWV, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)              \
       : launch_attn<DHV, QBV, NWV, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s))
