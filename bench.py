@@ -47,7 +47,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="wan1p3b_480p", choices=["wan1p3b_480p", "wan1p3b_small", "c1"])
+    ap.add_argument("--workload", default="wan1p3b_480p", choices=["wan1p3b_480p", "wan1p3b_small", "c1", "wan14b_720p"])
     ap.add_argument("--blocks", type=int, default=None, help="override the block count (default: the model's)")
     ap.add_argument("--cache-entries", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -148,6 +148,24 @@ def test_block_1p3b_widths_small_grid(stress):
     _compare(got, inp["x"][idx], ref, f"1.3B-small box stress={stress}", stress)
 
 
+def test_block_14b_widths_small_grid():
+    """Config-5 widths (D 5120, 40 x 128 heads, F 13824, 512 text tokens) on a 3x8x10 grid with a
+    50% box mask and TGAA 1.5: the widest GEMM / norm paths (register-resident LayerNorm at D=5120)."""
+    import dataclasses
+    print("[case] block 14B widths small grid", flush=True)
+    bs = dataclasses.replace(synth.SHAPES["wan14b_720p"], grid=(3, 8, 10))
+    w = synth.block_weights(bs, 0)
+    inp = synth.block_inputs(bs, 0)
+    g = synth.tdiff_scale(bs.Lt, 1.5)
+    mask = synth.box_mask(bs.grid, 3, 8, 5, 0, 0, 3)
+    idx = O.region_compact(mask)
+    xc = dict(inp)
+    xc["x"] = inp["x"][idx]
+    got = _run_block(bs, w, xc, token_idx=idx, key_scale=g, gamma_o=1.5)
+    ref = O.dit_block(inp["x"][idx], w, bs, inp["text_ctx"], inp["t_mod"], token_idx=idx, key_scale=g, gamma_o=1.5)
+    _compare(got, inp["x"][idx], ref, "14B widths box 50%")
+
+
 def test_block_deterministic():
     bs = synth.SHAPES["c1"]
     w = synth.stress_block_weights(bs, 5)

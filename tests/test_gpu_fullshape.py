@@ -47,7 +47,7 @@ def test_self_attention_full_length_peaked():
         check(got[rows], ref, f"attention full length v{variant}", max_abs=max(np.abs(ref).max() * 2 ** -7, 2e-3), rel_l2=5e-3)
 
 
-@pytest.mark.parametrize("masked", [False, True])
+@pytest.mark.parametrize("masked", [False, True, "bernoulli"])
 def test_block_full_shape_row_sampled(masked):
     bs = synth.SHAPES["wan1p3b_480p"]
     print(f"[case] block 1.3B 480p full shape masked={masked}", flush=True)
@@ -55,7 +55,10 @@ def test_block_full_shape_row_sampled(masked):
     inp = synth.block_inputs(bs, 0)
     g = synth.tdiff_scale(bs.Lt, 1.5, n_diff=8) if masked else None
     go = 1.5 if masked else 1.0
-    if masked:
+    if masked == "bernoulli":
+        mask = synth.bernoulli_mask(bs.L, 0.5, seed=0)           # region sweep: i.i.d. per-token mask
+        idx = O.region_compact(mask)
+    elif masked:
         mask = synth.box_mask(bs.grid, 21, 24, 26, 0, 3, 13)     # exactly 40% of the tokens
         idx = O.region_compact(mask)
         assert idx.size == 13104
