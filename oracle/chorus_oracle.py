@@ -285,6 +285,80 @@ def dit_block(x, w, shape, text_ctx, t_mod, token_idx=None, key_scale=None, gamm
 
 
 # --------------------------------------------------------------------------
+# Region masks (Sec. 3.3.1 "Region Mask Generation", stages 2-3; Sec. 3.3.2, Eq. 5)
+# --------------------------------------------------------------------------
+
+def mask_propagate_keyframes(key_masks, frame_key):
+    """Key-frame strategy of the pixel-space segmentation stage: masks exist only for
+    the key frames; frame f takes the mask of the key frame of its temporal group,
+    frame_key[f]. key_masks [Kf, Hp, Wp] -> [Tp, Hp, Wp]. How frames are grouped is
+    not fixed by the paper, so the assignment is an input."""
+    km = np.asarray(key_masks) != 0
+    fk = np.asarray(frame_key, np.int64)
+    assert fk.ndim == 1 and (fk >= 0).all() and (fk < km.shape[0]).all()
+    return km[fk].astype(np.uint8)
+
+
+def pooled_extent(n, k, lead=0):
+    """Number of windows along one axis: `lead` leading sites are windows of their own
+    (a causal video VAE encodes the first frame alone), the rest is cut into windows of
+    k, the last one possibly short."""
+    assert k >= 1 and 0 <= lead <= n
+    return lead + -(-(n - lead) // k)
+
+
+def mask_maxpool(mask, window, t_lead=0):
+    """Latent-space projection: the binary mask is downsampled with a max pool
+    (stride = window, windows that run over the edge are cut at the edge).
+    mask [Tp, Hp, Wp], window (kt, kh, kw). Along time the first t_lead frames map
+    to one output frame each. A window is set iff any site in it is set."""
+    m = np.asarray(mask) != 0
+    Tp, Hp, Wp = m.shape
+    kt, kh, kw = window
+    To, Ho, Wo = pooled_extent(Tp, kt, t_lead), pooled_extent(Hp, kh), pooled_extent(Wp, kw)
+    out = np.zeros((To, Ho, Wo), np.uint8)
+    for t in range(To):
+        if t < t_lead:
+            t0, t1 = t, t + 1
+        else:
+            t0 = t_lead + (t - t_lead) * kt
+            t1 = min(t0 + kt, Tp)
+        for y in range(Ho):
+            rows = m[t0:t1, y * kh:min((y + 1) * kh, Hp), :]
+            col_any = rows.any(axis=(0, 1))                       # [Wp]
+            for x in range(Wo):
+                out[t, y, x] = col_any[x * kw:min((x + 1) * kw, Wp)].any()
+    return out
+
+
+def mask_dilate(mask_base, radius):
+    """Eq. 5: I(M_base * K_r > 0) with K_r the all-ones kernel of (2 r_a + 1) sites
+    along each axis a. The convolution is written out as a sum of shifted copies of
+    the zero-padded mask (sites beyond the grid count as 0). The paper gives one
+    radius r; a radius per axis (rt, rh, rw) covers both a purely spatial kernel
+    (rt = 0) and a spatio-temporal one."""
+    m = (np.asarray(mask_base) != 0).astype(np.int64)
+    assert m.ndim == 3
+    rt, rh, rw = radius
+    assert rt >= 0 and rh >= 0 and rw >= 0
+    T, H, W = m.shape
+    padded = np.pad(m, ((rt, rt), (rh, rh), (rw, rw)))
+    conv = np.zeros_like(m)
+    for dt in range(2 * rt + 1):
+        for dy in range(2 * rh + 1):
+            for dx in range(2 * rw + 1):
+                conv += padded[dt:dt + T, dy:dy + H, dx:dx + W]
+    return (conv > 0).astype(np.uint8)
+
+
+def mask_hierarchy(mask_base, r_edit, r_see):
+    """Eq. 5: (M_edit, M_see) from M_base with r_see >= r_edit on every axis, which
+    gives M_see >= M_edit >= M_base site by site."""
+    assert all(a >= b for a, b in zip(r_see, r_edit))
+    return mask_dilate(mask_base, r_edit), mask_dilate(mask_base, r_see)
+
+
+# --------------------------------------------------------------------------
 # Selective region path (Sec. 3.3; Eq. 6)
 # --------------------------------------------------------------------------
 

@@ -245,3 +245,39 @@ def tdiff_scale(Lt: int, gamma_k: float, seed: int = 0, n_diff: int | None = Non
     else:
         g[stream(seed, "tdiff").permutation(Lt)[:n_diff]] = gamma_k
     return g
+
+
+def pixel_key_masks(Kf: int, Hp: int, Wp: int, seed: int = 0, n_obj: int = 2, fill: float = 0.12) -> np.ndarray:
+    """Stand-in for a segmentation model's output on the key frames: uint8 [Kf, Hp, Wp]
+    with n_obj filled ellipses that drift and breathe from key frame to key frame, plus a
+    few isolated pixels (segmentation speckle). `fill` is roughly the covered fraction."""
+    g = stream(seed, f"mask.pixel.{Kf}x{Hp}x{Wp}")
+    yy, xx = np.mgrid[0:Hp, 0:Wp]
+    out = np.zeros((Kf, Hp, Wp), np.uint8)
+    area = fill * Hp * Wp / max(1, n_obj)
+    for _ in range(n_obj):
+        cy, cx = g.uniform(0.2, 0.8) * Hp, g.uniform(0.2, 0.8) * Wp
+        vy, vx = g.uniform(-0.02, 0.02) * Hp, g.uniform(-0.02, 0.02) * Wp
+        aspect = g.uniform(0.6, 1.6)
+        ry, rx = np.sqrt(area / np.pi * aspect), np.sqrt(area / np.pi / aspect)
+        for k in range(Kf):
+            s = 1.0 + 0.1 * np.sin(0.7 * k)
+            e = ((yy - (cy + vy * k)) / (ry * s)) ** 2 + ((xx - (cx + vx * k)) / (rx * s)) ** 2 <= 1.0
+            out[k] |= e.astype(np.uint8)
+    n_speck = max(1, Hp * Wp // 50000)
+    for k in range(Kf):
+        out[k, g.integers(0, Hp, n_speck), g.integers(0, Wp, n_speck)] = 1
+    return out
+
+
+def frame_key_groups(Tp: int, Kf: int) -> np.ndarray:
+    """Frame -> key-frame index for Kf contiguous temporal groups of (nearly) equal length."""
+    return np.minimum(np.arange(Tp, dtype=np.int64) * Kf // max(1, Tp), Kf - 1).astype(np.int32)
+
+
+def sparse_site_mask(shape3, count: int, seed: int = 0) -> np.ndarray:
+    """uint8 [T, H, W] with exactly `count` isolated set sites (dilation / pooling edge cases)."""
+    n = int(np.prod(shape3))
+    m = np.zeros(n, np.uint8)
+    m[stream(seed, f"mask.sparse.{shape3}").permutation(n)[:count]] = 1
+    return m.reshape(shape3)

@@ -495,3 +495,101 @@ def test_schedule_run_stage1_and_miss():
     for i in range(2):
         b = O.denoise_step(b, blocks, gw, bs, ctx, t_mods[i], t_heads[i], sig[i + 1] - sig[i])
     np.testing.assert_array_equal(a, b)
+
+
+# ------------------------------------------------------------------ region masks (Eq. 5, max-pool projection)
+
+def _brute_dilate(m, r):
+    T, H, W = m.shape
+    out = np.zeros_like(m)
+    for t in range(T):
+        for y in range(H):
+            for x in range(W):
+                hit = 0
+                for tt in range(max(0, t - r[0]), min(T, t + r[0] + 1)):
+                    for yy in range(max(0, y - r[1]), min(H, y + r[1] + 1)):
+                        for xx in range(max(0, x - r[2]), min(W, x + r[2] + 1)):
+                            hit |= int(m[tt, yy, xx] != 0)
+                out[t, y, x] = hit
+    return out
+
+
+def test_dilate_brute_force_and_scipy():
+    from scipy import ndimage
+    m = (synth.stream(0, "pin.dil").random((4, 9, 11)) < 0.08).astype(np.uint8)
+    for r in [(0, 0, 0), (0, 1, 1), (1, 2, 3), (2, 0, 1), (0, 3, 0), (5, 12, 12)]:
+        got = O.mask_dilate(m, r)
+        np.testing.assert_array_equal(got, _brute_dilate(m, r))
+        lib = ndimage.binary_dilation(m, structure=np.ones((2 * r[0] + 1, 2 * r[1] + 1, 2 * r[2] + 1), bool))
+        np.testing.assert_array_equal(got, lib.astype(np.uint8))
+    np.testing.assert_array_equal(O.mask_dilate(m, (0, 0, 0)), m)                 # K_0 = [1]: identity
+
+
+def test_dilate_closed_forms():
+    # one site -> the (2r+1) box around it, cut at the border; asymmetric radii hit the right axes
+    m = np.zeros((5, 8, 10), np.uint8)
+    m[2, 3, 4] = 1
+    d = O.mask_dilate(m, (1, 2, 3))
+    exp = np.zeros_like(m)
+    exp[1:4, 1:6, 1:8] = 1
+    np.testing.assert_array_equal(d, exp)
+    assert d.sum() == 3 * 5 * 7
+    m[:] = 0
+    m[0, 0, 9] = 1                                                                  # corner: zero padding outside
+    d = O.mask_dilate(m, (1, 1, 2))
+    assert d.sum() == 2 * 2 * 3 and d[0:2, 0:2, 7:10].all()
+    # box kernels compose: dilation by r1 then r2 is dilation by r1 + r2
+    mm = synth.sparse_site_mask((4, 12, 12), 5, seed=3)
+    np.testing.assert_array_equal(O.mask_dilate(O.mask_dilate(mm, (1, 1, 2)), (0, 2, 1)), O.mask_dilate(mm, (1, 3, 3)))
+    # empty stays empty, full stays full
+    assert O.mask_dilate(np.zeros((2, 3, 4), np.uint8), (1, 1, 1)).sum() == 0
+    assert O.mask_dilate(np.ones((2, 3, 4), np.uint8), (1, 1, 1)).all()
+    # any non-zero byte counts as set, the output is 0/1
+    m3 = np.zeros((1, 3, 3), np.uint8)
+    m3[0, 1, 1] = 200
+    assert set(np.unique(O.mask_dilate(m3, (0, 1, 1)))) == {1}
+
+
+def test_mask_hierarchy_containment():
+    base = synth.pixel_key_masks(3, 24, 40, seed=1, n_obj=2)
+    edit, see = O.mask_hierarchy(base, (0, 1, 1), (1, 3, 3))
+    assert ((base != 0) <= (edit != 0)).all() and (edit <= see).all()              # M_see >= M_edit >= M_base
+    assert edit.sum() > (base != 0).sum() and see.sum() > edit.sum()
+    with pytest.raises(AssertionError):
+        O.mask_hierarchy(base, (0, 2, 2), (0, 1, 3))                                # r' must dominate r
+
+
+def test_maxpool_vs_torch_and_brute_force():
+    m = (synth.stream(0, "pin.pool").random((9, 20, 28)) < 0.03).astype(np.uint8)
+    # divisible and ragged windows against torch's max_pool3d (ceil_mode cuts windows at the edge)
+    for win in [(1, 2, 2), (4, 8, 8), (2, 3, 5), (9, 20, 28), (1, 1, 1), (4, 16, 16)]:
+        got = O.mask_maxpool(m, win)
+        lib = TF.max_pool3d(torch.from_numpy(m)[None, None].float(), win, stride=win, ceil_mode=True)[0, 0]
+        np.testing.assert_array_equal(got, lib.numpy().astype(np.uint8))
+    # leading frame on its own (causal video VAE: 1 + 4k frames -> 1 + k latent frames)
+    got = O.mask_maxpool(m, (4, 8, 8), t_lead=1)
+    assert got.shape == (3, 3, 4)
+    for t, (t0, t1) in enumerate([(0, 1), (1, 5), (5, 9)]):
+        for y in range(3):
+            for x in range(4):
+                assert got[t, y, x] == int(m[t0:t1, 8 * y:8 * y + 8, 8 * x:8 * x + 8].any())
+    assert O.pooled_extent(81, 4, 1) == 21 and O.pooled_extent(480, 16) == 30 and O.pooled_extent(17, 4) == 5
+    # pooling keeps "any": set sites never vanish, empty windows stay empty
+    assert got.any() == m.any()
+    assert O.mask_maxpool(np.zeros((5, 8, 8), np.uint8), (4, 8, 8), 1).sum() == 0
+    # two-step projection pixel -> latent -> token equals one pool with the product window
+    a = O.mask_maxpool(O.mask_maxpool(m, (4, 8, 8), 1), (1, 2, 2))
+    b = O.mask_maxpool(m, (4, 16, 16), 1)
+    np.testing.assert_array_equal(a, b)
+
+
+def test_keyframe_propagation():
+    km = synth.pixel_key_masks(3, 12, 16, seed=2)
+    fk = synth.frame_key_groups(9, 3)
+    np.testing.assert_array_equal(fk, [0, 0, 0, 1, 1, 1, 2, 2, 2])
+    fr = O.mask_propagate_keyframes(km, fk)
+    assert fr.shape == (9, 12, 16)
+    for f in range(9):
+        np.testing.assert_array_equal(fr[f], (km[fk[f]] != 0).astype(np.uint8))
+    with pytest.raises(AssertionError):
+        O.mask_propagate_keyframes(km, np.array([0, 3]))
