@@ -190,6 +190,44 @@ int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_w
 int32_t chorus_stage1_copy(float* latent, const float* SL, int64_t n, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Region masks (Sec. 3.3.1 "Region Mask Generation" stages 2-3; Sec. 3.3.2, Eq. 5).
+ * Byte masks on the device, any non-zero byte is "set"; outputs hold 0 / 1. Exact.
+ *
+ * chorus_mask_pooled_extent (host-only): number of windows along an axis of n sites cut
+ * into windows of k after `lead` leading sites that are windows of their own
+ * (lead + ceil((n - lead) / k)); CHORUS_E_ARG (negative) for k < 1, lead < 0 or lead > n.
+ *
+ * chorus_mask_project: key-frame propagation fused with the max-pool projection from
+ * pixel space to the latent / token grid.
+ *   key_masks  dev [Kf, Hp, Wp] uint8, the segmentation masks of the key frames
+ *   frame_key  dev [Tp] int32, key frame of every frame's temporal group; NULL = every
+ *              frame is its own key frame (then Kf must equal Tp). An entry outside
+ *              [0, Kf) makes that frame contribute nothing.
+ *   window     (kt, kh, kw), stride = window, windows are cut at the far edge; along time
+ *              the first t_lead frames map to one output frame each (a causal video VAE
+ *              encodes the first frame alone: 81 frames, kt = 4, t_lead = 1 -> 21)
+ *   out        dev [To, Ho, Wo] uint8 with the extents chorus_mask_pooled_extent gives;
+ *              out[t,y,x] = 1 iff any site of the window is set. Must not overlap key_masks.
+ * Wp up to 65536. Errors: CHORUS_E_ARG (null pointer, window < 1, t_lead outside [0, Tp],
+ * frame_key NULL with Kf != Tp), CHORUS_E_SHAPE (extent limits), CHORUS_E_HIP.
+ *
+ * chorus_mask_hierarchy: Eq. 5, M_edit = I(M_base * K_r > 0), M_see = I(M_base * K_r' > 0)
+ * with all-ones box kernels of 2 r + 1 sites per axis; sites beyond the grid count as 0.
+ *   mask_base  dev [T, H, W] uint8
+ *   r_edit, r_see  host int32[3] = radii along (t, h, w); r_see[a] >= r_edit[a] >= 0,
+ *              which gives M_see >= M_edit >= M_base. r_edit may be NULL iff mask_edit is.
+ *   mask_edit, mask_see  dev [T, H, W] uint8; either may be NULL (not both); neither may
+ *              overlap mask_base.
+ * Errors: CHORUS_E_ARG, CHORUS_E_SHAPE (more than 2^31 - 257 sites), CHORUS_E_HIP.
+ * Both calls are asynchronous on `stream` and allocate nothing.
+ * ---------------------------------------------------------------------- */
+int32_t chorus_mask_pooled_extent(int32_t n, int32_t k, int32_t lead);
+int32_t chorus_mask_project(const uint8_t* key_masks, int32_t Kf, const int32_t* frame_key, int32_t Tp, int32_t Hp,
+                            int32_t Wp, int32_t kt, int32_t kh, int32_t kw, int32_t t_lead, uint8_t* out, void* stream);
+int32_t chorus_mask_hierarchy(const uint8_t* mask_base, int32_t T, int32_t H, int32_t W, const int32_t r_edit[3],
+                              const int32_t r_see[3], uint8_t* mask_edit, uint8_t* mask_see, void* stream);
+
+/* ------------------------------------------------------------------------
  * Per-kernel timing for benchmarks. chorus_prof_enable takes a bit mask of kernel
  * classes (bit c = class c; 0 = off, the default). For the enabled classes
  * chorus_dit_block_step brackets the launches with HIP events on the caller's

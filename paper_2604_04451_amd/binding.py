@@ -136,6 +136,9 @@ def _bind_ops(lib):
         "chorus_denoise_run": (i32, [MS, C.POINTER(BlockWeights), GW, C.POINTER(Request), vp, C.POINTER(RunResult), vp,
                                      sz, vp]),
         "chorus_stage1_copy": (i32, [vp, vp, i64, vp]),
+        "chorus_mask_pooled_extent": (i32, [i32, i32, i32]),
+        "chorus_mask_project": (i32, [vp, i32, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]),
+        "chorus_mask_hierarchy": (i32, [vp, i32, i32, i32, C.POINTER(i32), C.POINTER(i32), vp, vp, vp]),
         "chorus_prof_enable": (i32, [i32]),
         "chorus_prof_reset": (i32, []),
         "chorus_prof_read": (i32, [i32, C.POINTER(C.c_double), C.POINTER(i32)]),
@@ -523,6 +526,44 @@ def chorus_stage1_copy(latent, SL):
     _chk(SL, torch.float32, "SL", latent.shape)
     _status("chorus_stage1_copy", load().chorus_stage1_copy(_p(latent), _p(SL), latent.numel(), _stream()))
     return latent
+
+
+# ---------------------------------------------------------------- region masks
+
+def chorus_mask_pooled_extent(n: int, k: int, lead: int = 0) -> int:
+    r = load().chorus_mask_pooled_extent(int(n), int(k), int(lead))
+    if r < 0:
+        _status("chorus_mask_pooled_extent", r)
+    return r
+
+
+def chorus_mask_project(key_masks, frame_key, Tp, window, t_lead=0, out=None):
+    """key_masks uint8 [Kf, Hp, Wp], frame_key int32 [Tp] or None -> uint8 [To, Ho, Wo]."""
+    lib = load()
+    _chk(key_masks, torch.uint8, "key_masks")
+    _chk(frame_key, torch.int32, "frame_key", (Tp,))
+    Kf, Hp, Wp = key_masks.shape
+    kt, kh, kw = (int(v) for v in window)
+    shape = (chorus_mask_pooled_extent(Tp, kt, t_lead), chorus_mask_pooled_extent(Hp, kh), chorus_mask_pooled_extent(Wp, kw))
+    if out is None:
+        out = torch.empty(shape, dtype=torch.uint8, device=key_masks.device)
+    _chk(out, torch.uint8, "out", shape)
+    _status("chorus_mask_project", lib.chorus_mask_project(_p(key_masks), Kf, _p(frame_key), int(Tp), Hp, Wp, kt, kh, kw,
+                                                           int(t_lead), _p(out), _stream()))
+    return out
+
+
+def chorus_mask_hierarchy(mask_base, r_edit, r_see, want_edit=True, want_see=True):
+    """Eq. 5 on a uint8 [T, H, W] mask; returns (mask_edit, mask_see) (None where not wanted)."""
+    lib = load()
+    _chk(mask_base, torch.uint8, "mask_base")
+    T, H, W = mask_base.shape
+    edit = torch.empty_like(mask_base) if want_edit else None
+    see = torch.empty_like(mask_base) if want_see else None
+    re = (C.c_int32 * 3)(*[int(v) for v in r_edit]) if r_edit is not None else None
+    rs = (C.c_int32 * 3)(*[int(v) for v in r_see])
+    _status("chorus_mask_hierarchy", lib.chorus_mask_hierarchy(_p(mask_base), T, H, W, re, rs, _p(edit), _p(see), _stream()))
+    return edit, see
 
 
 def chorus_denoise_run_workspace_bytes(model: ModelShape, N: int) -> int:

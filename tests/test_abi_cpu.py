@@ -92,3 +92,28 @@ def test_workspace_sizes_scale_with_rows():
     assert 0 < a < b < 3 * (1 << 30)
     assert lib.chorus_cache_lookup_workspace_bytes(4096) >= 4096 * 4
     assert lib.chorus_region_compact_workspace_bytes(75600) >= 4 * ((75600 + 4095) // 4096)
+
+
+def test_mask_entry_points_validate_and_pooled_extent_matches_oracle():
+    from oracle import chorus_oracle as O
+    lib = P.load()
+    null, p16 = C.c_void_p(0), C.c_void_p(16)
+    for n, k, lead in [(81, 4, 1), (480, 16, 0), (17, 4, 0), (5, 7, 0), (1, 1, 1), (0, 3, 0), (9, 2, 9)]:
+        assert lib.chorus_mask_pooled_extent(n, k, lead) == O.pooled_extent(n, k, lead)
+    assert lib.chorus_mask_pooled_extent(8, 0, 0) == B.E_ARG
+    assert lib.chorus_mask_pooled_extent(8, 2, 9) == B.E_ARG
+    # project: window < 1, t_lead > Tp, identity frame map with Kf != Tp, null pointers; empty input is OK
+    assert lib.chorus_mask_project(p16, 2, p16, 4, 8, 8, 0, 2, 2, 0, p16, null) == B.E_ARG
+    assert lib.chorus_mask_project(p16, 2, p16, 4, 8, 8, 2, 2, 2, 5, p16, null) == B.E_ARG
+    assert lib.chorus_mask_project(p16, 2, null, 4, 8, 8, 2, 2, 2, 0, p16, null) == B.E_ARG
+    assert lib.chorus_mask_project(null, 2, p16, 4, 8, 8, 2, 2, 2, 0, p16, null) == B.E_ARG
+    assert lib.chorus_mask_project(p16, 2, p16, 4, 8, 1 << 20, 2, 2, 2, 0, p16, null) == B.E_SHAPE
+    assert lib.chorus_mask_project(null, 0, null, 0, 8, 8, 2, 2, 2, 0, null, null) == B.OK
+    # hierarchy: r' < r, negative radius, aliasing, no output; empty grid is OK
+    r = lambda *v: (C.c_int32 * 3)(*v)
+    assert lib.chorus_mask_hierarchy(p16, 2, 4, 4, r(0, 2, 2), r(0, 1, 3), C.c_void_p(32), C.c_void_p(64), null) == B.E_ARG
+    assert lib.chorus_mask_hierarchy(p16, 2, 4, 4, r(0, -1, 0), r(0, 1, 1), C.c_void_p(32), C.c_void_p(64), null) == B.E_ARG
+    assert lib.chorus_mask_hierarchy(p16, 2, 4, 4, r(0, 1, 1), r(0, 1, 1), p16, C.c_void_p(64), null) == B.E_ARG
+    assert lib.chorus_mask_hierarchy(p16, 2, 4, 4, r(0, 1, 1), r(0, 1, 1), null, null, null) == B.E_ARG
+    assert lib.chorus_mask_hierarchy(p16, 2, 4, 4, None, r(0, 1, 1), C.c_void_p(32), C.c_void_p(64), null) == B.E_ARG
+    assert lib.chorus_mask_hierarchy(null, 0, 4, 4, r(0, 1, 1), r(0, 1, 1), null, null, null) == B.OK
