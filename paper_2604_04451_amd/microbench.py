@@ -1,0 +1,126 @@
+"""Per-entry-point timing of the memory-bound steps of the Chorus hot path on one MI355X:
+cache lookup, stage-1 copy, latent fusion, compaction, row gather / scatter, the
+region-mask pipeline and the per-token normalisation kernels, at the Wan2.1-1.3B 480p
+shapes. Each call is timed with HIP events on the launch stream over a rotation of
+buffers larger than the last-level cache, so every launch reads cold data.
+
+    python -m paper_2604_04451_amd.microbench [--iters 48]
+
+Prints one line per entry point: algorithmic bytes, median and best microseconds, and
+the rate on algorithmic bytes. Run it under `rocprofv3 --kernel-trace --stats` for the
+per-kernel durations without launch overhead.
+"""
+from __future__ import annotations
+
+import argparse
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+DEV = "cuda"
+
+
+def timeit(fn, n):
+    for i in range(3):
+        fn(i)
+    torch.cuda.synchronize()
+    ts = []
+    for i in range(n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) * 1e3)
+    return float(np.median(ts)), float(min(ts))
+
+
+def report(name, nbytes, med, best):
+    print(f"{name:<44s} {nbytes / 1e6:9.3f} MB  median {med:7.1f} us  best {best:7.1f} us  "
+          f"{nbytes / med / 1e3:7.0f} GB/s median  {nbytes / best / 1e3:7.0f} GB/s best", flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--iters", type=int, default=48)
+    args = ap.parse_args()
+    n = args.iters
+    if not torch.cuda.is_available():
+        raise SystemExit("microbench: needs a GPU")
+    B.load()
+    g = torch.Generator(device=DEV)
+    g.manual_seed(0)
+
+    # ---- lookup: 10 caches of 67 MB, more than the 256 MB last-level cache
+    N = d = 4096
+    caches = [torch.randn(N, d, device=DEV, generator=g) for _ in range(10)]
+    q = torch.randn(d, device=DEV, generator=g)
+    out = torch.empty(3, dtype=torch.int32, device=DEV)
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device=DEV)
+    med, best = timeit(lambda i: B.chorus_cache_lookup(caches[i % 10], q, 0.75, out, ws), n)
+    report("cache_lookup 4096x4096 fp32 (2 launches)", N * d * 4 + d * 4, med, best)
+    del caches
+
+    # ---- latent-sized kernels: 24 triples of 8.4 MB
+    C_, T, Hl, Wl = 16, 21, 60, 104
+    Hg, Wg = Hl // 2, Wl // 2
+    L = T * Hg * Wg
+    bufs = [torch.randn(3, C_, T, Hl, Wl, device=DEV, generator=g) for _ in range(24)]
+    lat_bytes = bufs[0][0].numel() * 4
+    box = torch.zeros(T, Hg, Wg, dtype=torch.uint8, device=DEV)
+    box[:, 3:27, 13:39] = 1                                                 # 21 x 24 x 26 = 40 %
+    bern = (torch.rand(L, device=DEV, generator=g) < 0.5).to(torch.uint8)
+    for name, m in (("box 40 %", box.reshape(-1)), ("Bernoulli 50 %", bern)):
+        med, best = timeit(lambda i: B.chorus_region_blend(bufs[i % 24][2], bufs[i % 24][0], bufs[i % 24][1], m), n)
+        report(f"region_blend {name}", 2 * lat_bytes + L, med, best)
+    med, best = timeit(lambda i: B.chorus_stage1_copy(bufs[i % 24][2], bufs[i % 24][0]), n)
+    report("stage1_copy", 2 * lat_bytes, med, best)
+
+    # ---- compaction and row moves
+    idx = torch.empty(L, dtype=torch.int32, device=DEV)
+    cnt = torch.empty(1, dtype=torch.int32, device=DEV)
+    med, best = timeit(lambda i: B.chorus_region_compact(box.reshape(-1), idx, cnt, ws), n)
+    Ls = int(cnt.cpu()[0])
+    report("region_compact box 40 % (3 launches)", L + 4 * Ls, med, best)
+    W = 64
+    rows = [torch.randn(2, L, W, device=DEV, generator=g) for _ in range(24)]
+    med, best = timeit(lambda i: B.chorus_region_gather_rows(rows[i % 24][1], rows[i % 24][0], idx, Ls), n)
+    report("region_gather_rows W=64 fp32, 40 %", 2 * Ls * W * 4 + 4 * Ls, med, best)
+    med, best = timeit(lambda i: B.chorus_region_scatter_rows(rows[i % 24][1], rows[i % 24][0], idx, Ls), n)
+    report("region_scatter_rows W=64 fp32, 40 %", 2 * Ls * W * 4 + 4 * Ls, med, best)
+    del rows, bufs
+
+    # ---- region masks: 21 key frames of 480 x 832, 81 frames, window 4 x 16 x 16 -> 21 x 30 x 52
+    Tp, Kf, Hp, Wp = 81, 21, 480, 832
+    kms = [(torch.rand(Kf, Hp, Wp, device=DEV, generator=g) < 0.001).to(torch.uint8) for _ in range(40)]
+    fk = torch.minimum(torch.arange(Tp, device=DEV) * Kf // Tp, torch.tensor(Kf - 1, device=DEV)).to(torch.int32)
+    base = torch.empty(T, Hg, Wg, dtype=torch.uint8, device=DEV)
+    med, best = timeit(lambda i: B.chorus_mask_project(kms[i % 40], fk, Tp, (4, 16, 16), 1, base), n)
+    report("mask_project 21x480x832 -> 21x30x52", Kf * Hp * Wp + L + 4 * Tp, med, best)
+    del kms
+    med, best = timeit(lambda i: B.chorus_mask_hierarchy(box, (0, 1, 1), (1, 3, 3)), n)
+    report("mask_hierarchy 21x30x52 r=(0,1,1) r'=(1,3,3)", 3 * L, med, best)
+
+    # ---- per-token normalisation kernels at L = 32760, D = 1536 (rotation of 4: 0.2-0.6 GB each)
+    D, H, dh = 1536, 12, 128
+    Lpad = (L + 255) // 256 * 256
+    xs = [torch.randn(L, D, device=DEV, generator=g) for _ in range(4)]
+    hs = [torch.empty(L, D, dtype=torch.bfloat16, device=DEV) for _ in range(4)]
+    vec = [torch.randn(D, device=DEV, generator=g) * 0.02 for _ in range(4)]
+    med, best = timeit(lambda i: B.chorus_ln_modulate(xs[i % 4], hs[i % 4], vec[0], vec[1], vec[2], vec[3], True), n)
+    report("ln_modulate 32760x1536", L * D * 6, med, best)
+    qkv = [torch.randn(L, 3 * D, device=DEV, generator=g).to(torch.bfloat16) for _ in range(4)]
+    qo = [torch.empty(H, Lpad, dh, dtype=torch.bfloat16, device=DEV) for _ in range(4)]
+    vt = [torch.empty(D, Lpad, dtype=torch.bfloat16, device=DEV) for _ in range(4)]
+    tok = torch.arange(L, dtype=torch.int32, device=DEV)
+    gain = torch.ones(D, device=DEV)
+    med, best = timeit(lambda i: B.chorus_qk_norm_rope(qkv[i % 4], 0, gain, qo[i % 4], L, H, dh, tok, (T, Hg, Wg), True), n)
+    report("qk_norm_rope 32760x1536 (one of q, k)", L * D * 4, med, best)
+    med, best = timeit(lambda i: B.chorus_v_transpose(qkv[i % 4], 2 * D, vt[i % 4], L), n)
+    report("v_transpose 32760x1536", L * D * 4, med, best)
+
+
+if __name__ == "__main__":
+    main()
