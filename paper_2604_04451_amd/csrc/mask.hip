@@ -74,8 +74,62 @@ __global__ __launch_bounds__(kProjThreads) void mask_project_kernel(const uint8_
   }
 }
 
-// One thread per site: scans the (2 r_see + 1)^3 box once; the inner (2 r_edit + 1)^3 box
-// feeds M_edit. Sites beyond the grid count as 0 (the box is cut at the border).
+// Eq. 5 with box kernels is separable. One workgroup per (frame t, strip of rows): the OR over the time window
+// goes into LDS while the rows of the strip (plus r_see rows of halo) are loaded, then a pass along x and a pass
+// along y, each for both radii. Sites beyond the grid count as 0.
+constexpr int kHierThreads = 256;
+constexpr int kHierLdsBytes = 48 * 1024;
+
+__global__ __launch_bounds__(kHierThreads) void mask_hierarchy_lds_kernel(const uint8_t* __restrict__ base, int T, int H, int W,
+                                                                          int et, int eh, int ew, int st, int sh, int sw,
+                                                                          int strip, int nstrips, uint8_t* __restrict__ edit,
+                                                                          uint8_t* __restrict__ see) {
+  extern __shared__ uint8_t hier_lds[];
+  const int t = blockIdx.x / nstrips, y0 = (blockIdx.x % nstrips) * strip, y1 = min(H, y0 + strip);
+  const int ya = max(0, y0 - sh), yb = min(H, y1 + sh);  // rows held in LDS
+  const int n_in = (yb - ya) * W;
+  uint8_t* S0 = hier_lds;       // OR over the see time window
+  uint8_t* E0 = S0 + n_in;      // OR over the edit time window
+  uint8_t* S1 = E0 + n_in;      // ... then along x
+  uint8_t* E1 = S1 + n_in;
+  const int t0 = max(0, t - st), t1 = min(T - 1, t + st);
+  const size_t plane = (size_t)H * W;
+  for (int i = threadIdx.x; i < n_in; i += kHierThreads) {
+    uint32_t s = 0, e = 0;
+    const uint8_t* p = base + (size_t)ya * W + i;
+    for (int tt = t0; tt <= t1; ++tt) {
+      const uint32_t v = p[tt * plane];
+      s |= v;
+      e |= (abs(tt - t) <= et) ? v : 0u;
+    }
+    S0[i] = s ? 1 : 0;
+    E0[i] = e ? 1 : 0;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < n_in; i += kHierThreads) {
+    const int x = i % W, row = i - x;
+    const int xa = max(0, x - sw), xb = min(W - 1, x + sw);
+    uint32_t s = 0, e = 0;
+    for (int xx = xa; xx <= xb; ++xx) s |= S0[row + xx];
+    for (int xx = max(0, x - ew); xx <= min(W - 1, x + ew); ++xx) e |= E0[row + xx];
+    S1[i] = s;
+    E1[i] = e;
+  }
+  __syncthreads();
+  const int n_out = (y1 - y0) * W;
+  for (int i = threadIdx.x; i < n_out; i += kHierThreads) {
+    const int x = i % W, y = y0 + i / W;
+    uint32_t s = 0, e = 0;
+    for (int yy = max(ya, y - sh); yy <= min(yb - 1, y + sh); ++yy) s |= S1[(yy - ya) * W + x];
+    for (int yy = max(ya, y - eh); yy <= min(yb - 1, y + eh); ++yy) e |= E1[(yy - ya) * W + x];
+    const size_t o = (size_t)t * plane + (size_t)y * W + x;
+    if (edit) edit[o] = e;
+    if (see) see[o] = s;
+  }
+}
+
+// Fallback for planes too wide for the LDS kernel. One thread per site: scans the (2 r_see + 1)^3 box once;
+// the inner (2 r_edit + 1)^3 box feeds M_edit. Sites beyond the grid count as 0 (the box is cut at the border).
 __global__ __launch_bounds__(256) void mask_hierarchy_kernel(const uint8_t* __restrict__ base, int T, int H, int W, int et,
                                                              int eh, int ew, int st, int sh, int sw,
                                                              uint8_t* __restrict__ edit, uint8_t* __restrict__ see) {
@@ -155,8 +209,23 @@ int32_t chorus_mask_hierarchy(const uint8_t* mask_base, int32_t T, int32_t H, in
   if (mask_base == mask_edit || mask_base == mask_see) return CHORUS_E_ARG;  // every site reads its neighbours
   if (n > 0x7fffffffLL - 256) return CHORUS_E_SHAPE;
   hipStream_t s = (hipStream_t)stream;
-  hipLaunchKernelGGL(mask_hierarchy_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, mask_base, T, H, W, re[0],
-                     re[1], re[2], r_see[0], r_see[1], r_see[2], mask_edit, mask_see);
+  // strips of rows: enough workgroups to spread over the chip, each strip with its r_see halo within the LDS budget
+  const int halo = 2 * (r_see[1] < H ? r_see[1] : H);
+  const long rows_fit = kHierLdsBytes / (4L * W) - halo;
+  if (rows_fit >= 1) {
+    int nstrips = (128 + T - 1) / T;
+    if (nstrips > H) nstrips = H;
+    if (nstrips < 1) nstrips = 1;
+    int strip = (H + nstrips - 1) / nstrips;
+    if (strip > rows_fit) strip = (int)rows_fit;
+    nstrips = (H + strip - 1) / strip;
+    const size_t lds = 4 * (size_t)(strip + halo) * W;
+    hipLaunchKernelGGL(mask_hierarchy_lds_kernel, dim3((unsigned)((long)T * nstrips)), dim3(kHierThreads), lds, s, mask_base,
+                       T, H, W, re[0], re[1], re[2], r_see[0], r_see[1], r_see[2], strip, nstrips, mask_edit, mask_see);
+  } else {
+    hipLaunchKernelGGL(mask_hierarchy_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, mask_base, T, H, W, re[0],
+                       re[1], re[2], r_see[0], r_see[1], r_see[2], mask_edit, mask_see);
+  }
   CHORUS_LAUNCH_CHECK();
   return CHORUS_OK;
 }

@@ -26,6 +26,8 @@ def _project(km, fk, Tp, win, t_lead):
     ((1, 1, 1), [((0, 0, 0), (1, 1, 1))]),
     ((3, 1, 300), [((0, 0, 2), (1, 0, 7))]),                       # one-row planes, several workgroups, ragged tail
     ((21, 30, 52), [((0, 1, 1), (1, 3, 3)), ((0, 2, 2), (0, 4, 4))]),  # the 480p token grid
+    ((2, 3, 13000), [((0, 0, 1), (1, 1, 3))]),                     # rows too wide for the LDS kernel: per-site fallback
+    ((3, 200, 96), [((1, 2, 2), (1, 9, 5))]),                      # several row strips per frame with halos
 ])
 def test_mask_hierarchy(shape, radii):
     n = int(np.prod(shape))
