@@ -161,6 +161,28 @@ int32_t chorus_dit_block_step(const chorus_block_shape* shape, const chorus_bloc
                               const int32_t* token_idx, const uint16_t* text_ctx, const float* t_mod,
                               const float* tgaa_key_scale, float gamma_o, void* ws, size_t ws_bytes, void* stream);
 
+/* -----------------------------------------------------------------------------
+ * Text keys / values of one block, projected once per request (Sec. 2.1: cross-attention
+ * conditions on the prompt only, so its keys and values are the same at every denoising
+ * step; Eq. 2 scales logits, not the stored keys, so TGAA leaves them valid).
+ *   chorus_text_kv_bytes            device bytes of one block's entry: the normalised keys
+ *                                   head-major [H, LtPad, dh] bf16, then the values
+ *                                   key-contiguous [D, LtPad] bf16 (LtPad = Lt rounded up to 64)
+ *   chorus_text_kv_workspace_bytes  scratch of chorus_text_kv_project ([Lt, 2D] bf16)
+ *   chorus_text_kv_project          text_ctx dev [Lt, D] bf16 -> text_kv dev (caller-owned)
+ *   chorus_dit_block_step_kv        chorus_dit_block_step with text_kv in place of text_ctx:
+ *                                   the same kernels on the same values, so the result is
+ *                                   bit-identical to the call that projects inside the block
+ * Errors as chorus_dit_block_step. Asynchronous on `stream`, no allocation.
+ * --------------------------------------------------------------------------- */
+size_t chorus_text_kv_bytes(const chorus_block_shape* shape);
+size_t chorus_text_kv_workspace_bytes(const chorus_block_shape* shape);
+int32_t chorus_text_kv_project(const chorus_block_shape* shape, const chorus_block_weights* w, const uint16_t* text_ctx,
+                               uint16_t* text_kv, void* ws, size_t ws_bytes, void* stream);
+int32_t chorus_dit_block_step_kv(const chorus_block_shape* shape, const chorus_block_weights* w, float* x, int64_t Ls,
+                                 const int32_t* token_idx, const uint16_t* text_kv, const float* t_mod,
+                                 const float* tgaa_key_scale, float gamma_o, void* ws, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------------------------
  * Latent fusion (Eq. 6): out = M_edit * L + (1 - M_edit) * SL with a binary mask
  * given per token and expanded over channels and the ph x pw patch. Done as a

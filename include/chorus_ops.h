@@ -134,6 +134,19 @@ int32_t chorus_denoise_step(const chorus_model_shape* model, const chorus_block_
                             const uint16_t* text_ctx, const float* t_mod, const float* t_head,
                             const float* tgaa_key_scale, float gamma_o, float dsigma, const float* SL,
                             const uint8_t* mask_edit, void* ws, size_t ws_bytes, void* stream);
+/* The same step with the prompt given as the per-block text keys / values that
+ * chorus_model_text_kv_project makes once per request (block b's entry at
+ * text_kv + b * chorus_text_kv_bytes(&model->block)); results are bit-identical to
+ * chorus_denoise_step. chorus_model_text_kv_project needs a workspace of
+ * chorus_text_kv_workspace_bytes(&model->block). */
+size_t chorus_model_text_kv_bytes(const chorus_model_shape* model);
+int32_t chorus_model_text_kv_project(const chorus_model_shape* model, const chorus_block_weights* blocks,
+                                     const uint16_t* text_ctx, void* text_kv, void* ws, size_t ws_bytes, void* stream);
+int32_t chorus_denoise_step_kv(const chorus_model_shape* model, const chorus_block_weights* blocks,
+                               const chorus_glue_weights* gw, float* latent, const int32_t* token_idx, int64_t Ls,
+                               const void* text_kv, const float* t_mod, const float* t_head,
+                               const float* tgaa_key_scale, float gamma_o, float dsigma, const float* SL,
+                               const uint8_t* mask_edit, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
  * The whole three-stage request (Sec. 3.1) on one stream:
@@ -145,6 +158,7 @@ int32_t chorus_denoise_step(const chorus_model_shape* model, const chorus_block_
  *        = every token), output amplification gamma_o, and fusion with the cached
  *        latent under M_edit (Eq. 6)
  *      steps [K2, N): chorus_denoise_step on all tokens
+ *      (the text keys / values of every block are projected once, before the first computed step)
  * A miss (m < tau, or an empty cache) runs N plain steps from the caller's latent.
  * One cached latent per entry serves both the stage-1 copy and the stage-2 fusion.
  * Two host synchronisations: after the lookup and after the compaction count.

@@ -97,6 +97,11 @@ def load():
         "chorus_dit_block_workspace_bytes": (sz, [C.POINTER(BlockShape), i64]),
         "chorus_dit_block_step": (i32, [C.POINTER(BlockShape), C.POINTER(BlockWeights), vp, i64, vp, vp, vp, vp, f32,
                                         vp, sz, vp]),
+        "chorus_text_kv_bytes": (sz, [C.POINTER(BlockShape)]),
+        "chorus_text_kv_workspace_bytes": (sz, [C.POINTER(BlockShape)]),
+        "chorus_text_kv_project": (i32, [C.POINTER(BlockShape), C.POINTER(BlockWeights), vp, vp, vp, sz, vp]),
+        "chorus_dit_block_step_kv": (i32, [C.POINTER(BlockShape), C.POINTER(BlockWeights), vp, i64, vp, vp, vp, vp, f32,
+                                           vp, sz, vp]),
         "chorus_region_blend": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
         "chorus_region_compact_workspace_bytes": (sz, [i64]),
         "chorus_region_compact": (i32, [vp, i64, vp, vp, vp, sz, vp]),
@@ -136,6 +141,10 @@ def _bind_ops(lib):
         "chorus_denoise_run": (i32, [MS, C.POINTER(BlockWeights), GW, C.POINTER(Request), vp, C.POINTER(RunResult), vp,
                                      sz, vp]),
         "chorus_stage1_copy": (i32, [vp, vp, i64, vp]),
+        "chorus_model_text_kv_bytes": (sz, [MS]),
+        "chorus_model_text_kv_project": (i32, [MS, C.POINTER(BlockWeights), vp, vp, vp, sz, vp]),
+        "chorus_denoise_step_kv": (i32, [MS, C.POINTER(BlockWeights), GW, vp, vp, i64, vp, vp, vp, vp, f32, f32, vp, vp, vp,
+                                         sz, vp]),
         "chorus_mask_pooled_extent": (i32, [i32, i32, i32]),
         "chorus_mask_project": (i32, [vp, i32, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]),
         "chorus_mask_hierarchy": (i32, [vp, i32, i32, i32, C.POINTER(i32), C.POINTER(i32), vp, vp, vp]),
@@ -330,6 +339,39 @@ def chorus_dit_block_step(shape: BlockShape, weights: DeviceBlock, x, Ls, token_
     return x
 
 
+def chorus_text_kv_project(shape: BlockShape, weights: DeviceBlock, text_ctx, text_kv=None):
+    """Projects one block's text keys / values; returns the uint8 device buffer that chorus_dit_block_step_kv takes."""
+    lib = load()
+    _chk(text_ctx, torch.bfloat16, "text_ctx", (shape.Lt, shape.D))
+    need = lib.chorus_text_kv_bytes(C.byref(shape))
+    if text_kv is None:
+        text_kv = torch.empty(need, dtype=torch.uint8, device=text_ctx.device)
+    _chk(text_kv, torch.uint8, "text_kv", (need,))
+    ws = _ws(lib.chorus_text_kv_workspace_bytes(C.byref(shape)), text_ctx.device)
+    _status("chorus_text_kv_project", lib.chorus_text_kv_project(C.byref(shape), C.byref(weights.cstruct), _p(text_ctx),
+                                                                 _p(text_kv), _p(ws), ws.numel(), _stream()))
+    return text_kv
+
+
+def chorus_dit_block_step_kv(shape: BlockShape, weights: DeviceBlock, x, Ls, token_idx, text_kv, t_mod,
+                             tgaa_key_scale=None, gamma_o=1.0, ws=None):
+    lib = load()
+    _chk(x, torch.float32, "x")
+    _chk(token_idx, torch.int32, "token_idx")
+    _chk(text_kv, torch.uint8, "text_kv", (lib.chorus_text_kv_bytes(C.byref(shape)),))
+    _chk(t_mod, torch.float32, "t_mod", (6, shape.D))
+    _chk(tgaa_key_scale, torch.float32, "tgaa_key_scale", (shape.Lt,))
+    if x.shape[-1] != shape.D or x.shape[0] < Ls:
+        raise TypeError("x: wrong shape")
+    if ws is None:
+        ws = _ws(lib.chorus_dit_block_workspace_bytes(C.byref(shape), int(Ls)), x.device)
+    _status("chorus_dit_block_step_kv",
+            lib.chorus_dit_block_step_kv(C.byref(shape), C.byref(weights.cstruct), _p(x), int(Ls), _p(token_idx),
+                                         _p(text_kv), _p(t_mod), _p(tgaa_key_scale), float(gamma_o), _p(ws), ws.numel(),
+                                         _stream()))
+    return x
+
+
 # ------------------------------------------------------- single operations
 
 EPI_BF16, EPI_GELU_BF16, EPI_F32, EPI_RESID = 0, 1, 2, 3
@@ -518,6 +560,42 @@ def chorus_denoise_step(model: ModelShape, blocks_arr, glue: DeviceGlue, latent,
             lib.chorus_denoise_step(C.byref(model), blocks_arr, C.byref(glue.cstruct), _p(latent), _p(token_idx), int(Ls),
                                     _p(text_ctx), _p(t_mod), _p(t_head), _p(tgaa_key_scale), float(gamma_o),
                                     float(dsigma), _p(SL), _p(mask_edit), _p(ws), ws.numel(), _stream()))
+    return latent
+
+
+def chorus_model_text_kv_project(model: ModelShape, blocks_arr, text_ctx, text_kv=None):
+    """Text keys / values of every block for one request (uint8 device buffer for chorus_denoise_step_kv)."""
+    lib = load()
+    _chk(text_ctx, torch.bfloat16, "text_ctx", (model.block.Lt, model.block.D))
+    need = lib.chorus_model_text_kv_bytes(C.byref(model))
+    if text_kv is None:
+        text_kv = torch.empty(max(need, 1), dtype=torch.uint8, device=text_ctx.device)
+    ws = _ws(lib.chorus_text_kv_workspace_bytes(C.byref(model.block)), text_ctx.device)
+    _status("chorus_model_text_kv_project", lib.chorus_model_text_kv_project(C.byref(model), blocks_arr, _p(text_ctx),
+                                                                             _p(text_kv), _p(ws), ws.numel(), _stream()))
+    return text_kv
+
+
+def chorus_denoise_step_kv(model: ModelShape, blocks_arr, glue: DeviceGlue, latent, token_idx, Ls, text_kv, t_mod, t_head,
+                           tgaa_key_scale=None, gamma_o=1.0, dsigma=0.0, SL=None, mask_edit=None, ws=None):
+    lib = load()
+    D = model.block.D
+    _chk(latent, torch.float32, "latent", (model.C, model.T, model.Hl, model.Wl))
+    _chk(SL, torch.float32, "SL", latent.shape)
+    _chk(token_idx, torch.int32, "token_idx")
+    _chk(text_kv, torch.uint8, "text_kv")
+    _chk(t_mod, torch.float32, "t_mod", (6, D))
+    _chk(t_head, torch.float32, "t_head", (2, D))
+    _chk(tgaa_key_scale, torch.float32, "tgaa_key_scale", (model.block.Lt,))
+    _chk(mask_edit, torch.uint8, "mask_edit")
+    if text_kv.numel() < lib.chorus_model_text_kv_bytes(C.byref(model)):
+        raise TypeError("text_kv: too small")
+    if ws is None:
+        ws = _ws(lib.chorus_denoise_step_workspace_bytes(C.byref(model), int(Ls)), latent.device)
+    _status("chorus_denoise_step_kv",
+            lib.chorus_denoise_step_kv(C.byref(model), blocks_arr, C.byref(glue.cstruct), _p(latent), _p(token_idx), int(Ls),
+                                       _p(text_kv), _p(t_mod), _p(t_head), _p(tgaa_key_scale), float(gamma_o),
+                                       float(dsigma), _p(SL), _p(mask_edit), _p(ws), ws.numel(), _stream()))
     return latent
 
 

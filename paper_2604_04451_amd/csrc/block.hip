@@ -93,6 +93,9 @@ int32_t check_shape(const chorus_block_shape* sh) {
   return CHORUS_OK;
 }
 
+// cached text K / V of one block: K head-major [H, LtPad, dh], then V^T [D, LtPad], each padded to 256 bytes
+inline size_t text_kv_half_bytes(const chorus_block_shape& sh) { return align_up((size_t)pad_text(sh.Lt) * sh.D * 2, 256); }
+
 #define CHK(call)                   \
   do {                              \
     int32_t st__ = (call);          \
@@ -142,17 +145,42 @@ size_t chorus_dit_block_workspace_bytes(const chorus_block_shape* shape, int64_t
   return carve(*shape, Ls > 0 ? Ls : 1, nullptr).bytes;
 }
 
-int32_t chorus_dit_block_step(const chorus_block_shape* shape, const chorus_block_weights* w, float* x, int64_t Ls,
-                              const int32_t* token_idx, const uint16_t* text_ctx, const float* t_mod,
-                              const float* tgaa_key_scale, float gamma_o, void* ws, size_t ws_bytes, void* stream) {
+}  // extern "C"
+
+namespace chorus {
+namespace {
+
+// text K (normalised, head-major) and V^T of one block from the projected prompt embedding (cross-attention keys and
+// values depend only on the prompt, Sec. 2.1, so one projection serves every denoising step of a request)
+int32_t project_text_kv(const chorus_block_shape& sh, const chorus_block_weights* w, const uint16_t* text_ctx, uint16_t* tkv,
+                        uint16_t* kc, uint16_t* vct, void* stream) {
+  const int D = sh.D, H = sh.H, dh = sh.dh, Lt = sh.Lt;
+  const long LtPad = pad_text(Lt);
+  hipStream_t s = (hipStream_t)stream;
+  {
+    ProfScope p(CHORUS_PROF_GEMM, s);
+    CHK(chorus_gemm_bf16(text_ctx, w->w_ckv, Lt, 2 * D, D, CHORUS_EPI_BF16, tkv, w->b_ckv, nullptr, nullptr, 1.f, stream));
+  }
+  {
+    ProfScope p(CHORUS_PROF_NORM, s);
+    CHK(chorus_qk_norm_rope(tkv, 2L * D, w->g_ck, kc, Lt, LtPad, H, dh, nullptr, sh.gT, sh.gH, sh.gW, 0, stream));
+    CHK(chorus_v_transpose(tkv + D, 2L * D, vct, Lt, LtPad, D, stream));
+  }
+  return CHORUS_OK;
+}
+
+// one block; exactly one of text_ctx (project K / V here) and text_kv (use the cached projection) is given
+int32_t block_step_impl(const chorus_block_shape* shape, const chorus_block_weights* w, float* x, int64_t Ls,
+                        const int32_t* token_idx, const uint16_t* text_ctx, const uint16_t* text_kv, const float* t_mod,
+                        const float* tgaa_key_scale, float gamma_o, void* ws, size_t ws_bytes, void* stream) {
   CHK(check_shape(shape));
   if (Ls < 0) return CHORUS_E_ARG;
   if (Ls == 0) return CHORUS_OK;
-  if (!w || !x || !text_ctx || !t_mod) return CHORUS_E_ARG;
+  if (!w || !x || (!text_ctx && !text_kv) || !t_mod) return CHORUS_E_ARG;
   const chorus_block_shape& sh = *shape;
   if (Ls > (int64_t)sh.gT * sh.gH * sh.gW && token_idx == nullptr) return CHORUS_E_SHAPE;
   if (!ws) return CHORUS_E_WORKSPACE;
-  if (!aligned16(ws) || !aligned16(x) || !aligned16(text_ctx) || !aligned16(t_mod)) return CHORUS_E_ARG;
+  if (!aligned16(ws) || !aligned16(x) || !aligned16(text_ctx) || !aligned16(text_kv) || !aligned16(t_mod)) return CHORUS_E_ARG;
   BlockWs b = carve(sh, Ls, ws);
   if (ws_bytes < b.bytes) return CHORUS_E_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
@@ -194,18 +222,22 @@ int32_t chorus_dit_block_step(const chorus_block_shape* shape, const chorus_bloc
   {
     ProfScope p(CHORUS_PROF_GEMM, s);
     CHK(chorus_gemm_bf16(b.h, w->w_cq, Ls, D, D, CHORUS_EPI_BF16, b.qkv, w->b_cq, nullptr, nullptr, 1.f, stream));
-    CHK(chorus_gemm_bf16(text_ctx, w->w_ckv, Lt, 2 * D, D, CHORUS_EPI_BF16, b.tkv, w->b_ckv, nullptr, nullptr, 1.f,
-                         stream));
+  }
+  const uint16_t* kc = b.kc;
+  const uint16_t* vct = b.vct;
+  if (text_kv) {
+    kc = text_kv;
+    vct = text_kv + text_kv_half_bytes(sh) / 2;
+  } else {
+    CHK(project_text_kv(sh, w, text_ctx, b.tkv, b.kc, b.vct, stream));
   }
   {
     ProfScope p(CHORUS_PROF_NORM, s);
     CHK(chorus_qk_norm_rope(b.qkv, D, w->g_cq, b.qh, Ls, Lpad, H, dh, nullptr, sh.gT, sh.gH, sh.gW, 0, stream));
-    CHK(chorus_qk_norm_rope(b.tkv, 2L * D, w->g_ck, b.kc, Lt, LtPad, H, dh, nullptr, sh.gT, sh.gH, sh.gW, 0, stream));
-    CHK(chorus_v_transpose(b.tkv + D, 2L * D, b.vct, Lt, LtPad, D, stream));
   }
   {
     ProfScope p(CHORUS_PROF_CROSS_ATTN, s);
-    CHK(chorus_attention(b.qh, b.kc, b.vct, b.ao, tgaa_key_scale, Ls, Lt, Lpad, LtPad, H, dh, 0, stream));
+    CHK(chorus_attention(b.qh, kc, vct, b.ao, tgaa_key_scale, Ls, Lt, Lpad, LtPad, H, dh, 0, stream));
   }
   {
     ProfScope p(CHORUS_PROF_GEMM, s);
@@ -222,6 +254,44 @@ int32_t chorus_dit_block_step(const chorus_block_shape* shape, const chorus_bloc
     CHK(chorus_gemm_bf16(b.ffn, w->w_2, Ls, D, F, CHORUS_EPI_RESID, x, w->b_2, row(tab, 5), row(t_mod, 5), 1.f, stream));
   }
   return CHORUS_OK;
+}
+
+}  // namespace
+}  // namespace chorus
+
+extern "C" {
+
+int32_t chorus_dit_block_step(const chorus_block_shape* shape, const chorus_block_weights* w, float* x, int64_t Ls,
+                              const int32_t* token_idx, const uint16_t* text_ctx, const float* t_mod,
+                              const float* tgaa_key_scale, float gamma_o, void* ws, size_t ws_bytes, void* stream) {
+  if (Ls > 0 && !text_ctx) return CHORUS_E_ARG;
+  return block_step_impl(shape, w, x, Ls, token_idx, text_ctx, nullptr, t_mod, tgaa_key_scale, gamma_o, ws, ws_bytes, stream);
+}
+
+int32_t chorus_dit_block_step_kv(const chorus_block_shape* shape, const chorus_block_weights* w, float* x, int64_t Ls,
+                                 const int32_t* token_idx, const uint16_t* text_kv, const float* t_mod,
+                                 const float* tgaa_key_scale, float gamma_o, void* ws, size_t ws_bytes, void* stream) {
+  if (Ls > 0 && !text_kv) return CHORUS_E_ARG;
+  return block_step_impl(shape, w, x, Ls, token_idx, nullptr, text_kv, t_mod, tgaa_key_scale, gamma_o, ws, ws_bytes, stream);
+}
+
+size_t chorus_text_kv_bytes(const chorus_block_shape* shape) {
+  if (check_shape(shape) != CHORUS_OK) return 0;
+  return 2 * text_kv_half_bytes(*shape);
+}
+
+size_t chorus_text_kv_workspace_bytes(const chorus_block_shape* shape) {
+  if (check_shape(shape) != CHORUS_OK) return 0;
+  return align_up((size_t)shape->Lt * 2 * shape->D * 2, 256);
+}
+
+int32_t chorus_text_kv_project(const chorus_block_shape* shape, const chorus_block_weights* w, const uint16_t* text_ctx,
+                               uint16_t* text_kv, void* ws, size_t ws_bytes, void* stream) {
+  CHK(check_shape(shape));
+  if (!w || !text_ctx || !text_kv) return CHORUS_E_ARG;
+  if (!aligned16(text_ctx) || !aligned16(text_kv) || !aligned16(ws)) return CHORUS_E_ARG;
+  if (!ws || ws_bytes < chorus_text_kv_workspace_bytes(shape)) return CHORUS_E_WORKSPACE;
+  return project_text_kv(*shape, w, text_ctx, (uint16_t*)ws, text_kv, text_kv + text_kv_half_bytes(*shape) / 2, stream);
 }
 
 }  // extern "C"

@@ -51,18 +51,23 @@ size_t chorus_denoise_step_workspace_bytes(const chorus_model_shape* model, int6
   return carve_step(*model, Ls, nullptr).bytes;
 }
 
-int32_t chorus_denoise_step(const chorus_model_shape* model, const chorus_block_weights* blocks,
-                            const chorus_glue_weights* gw, float* latent, const int32_t* token_idx, int64_t Ls,
-                            const uint16_t* text_ctx, const float* t_mod, const float* t_head,
-                            const float* tgaa_key_scale, float gamma_o, float dsigma, const float* SL,
-                            const uint8_t* mask_edit, void* ws, size_t ws_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+// one computed step; the prompt enters either as text_ctx (K / V projected inside every block) or as text_kv, the
+// per-block projections made once per request by chorus_text_kv_project (block b at text_kv + b * chorus_text_kv_bytes)
+int32_t denoise_step_impl(const chorus_model_shape* model, const chorus_block_weights* blocks, const chorus_glue_weights* gw,
+                          float* latent, const int32_t* token_idx, int64_t Ls, const uint16_t* text_ctx,
+                          const uint8_t* text_kv, const float* t_mod, const float* t_head, const float* tgaa_key_scale,
+                          float gamma_o, float dsigma, const float* SL, const uint8_t* mask_edit, void* ws, size_t ws_bytes,
+                          void* stream) {
   int32_t st = check_model(model);
   if (st != CHORUS_OK) return st;
   const chorus_model_shape& m = *model;
   const int64_t Ltok = (int64_t)m.T * (m.Hl / m.ph) * (m.Wl / m.pw);
   if (Ls < 0 || Ls > Ltok) return CHORUS_E_ARG;
   if (!token_idx && Ls != Ltok) return CHORUS_E_ARG;
-  if (!latent || !gw || !text_ctx || !t_mod || !t_head || (m.n_blocks > 0 && !blocks)) return CHORUS_E_ARG;
+  if (!latent || !gw || (!text_ctx && !text_kv) || !t_mod || !t_head || (m.n_blocks > 0 && !blocks)) return CHORUS_E_ARG;
   if ((mask_edit != nullptr) != (SL != nullptr)) return CHORUS_E_ARG;
   if (!ws) return CHORUS_E_WORKSPACE;
   StepWs w = carve_step(m, Ls, ws);
@@ -71,9 +76,14 @@ int32_t chorus_denoise_step(const chorus_model_shape* model, const chorus_block_
     st = chorus_patch_embed(latent, m.C, m.T, m.Hl, m.Wl, m.ph, m.pw, token_idx, Ls, gw, m.block.D, w.x, w.glue,
                             w.glue_bytes, stream);
     if (st != CHORUS_OK) return st;
+    const size_t kv_bytes = chorus_text_kv_bytes(&m.block);
     for (int b = 0; b < m.n_blocks; ++b) {
-      st = chorus_dit_block_step(&m.block, &blocks[b], w.x, Ls, token_idx, text_ctx, t_mod, tgaa_key_scale, gamma_o,
-                                 w.block, w.block_bytes, stream);
+      if (text_kv)
+        st = chorus_dit_block_step_kv(&m.block, &blocks[b], w.x, Ls, token_idx, (const uint16_t*)(text_kv + b * kv_bytes),
+                                      t_mod, tgaa_key_scale, gamma_o, w.block, w.block_bytes, stream);
+      else
+        st = chorus_dit_block_step(&m.block, &blocks[b], w.x, Ls, token_idx, text_ctx, t_mod, tgaa_key_scale, gamma_o,
+                                   w.block, w.block_bytes, stream);
       if (st != CHORUS_OK) return st;
     }
     st = chorus_head_update(latent, w.x, Ls, token_idx, gw, t_head, dsigma, m.block.D, m.C, m.T, m.Hl, m.Wl, m.ph,
@@ -82,6 +92,49 @@ int32_t chorus_denoise_step(const chorus_model_shape* model, const chorus_block_
   }
   if (mask_edit) {
     st = chorus_region_blend(latent, latent, SL, mask_edit, m.C, m.T, m.Hl, m.Wl, m.ph, m.pw, stream);
+    if (st != CHORUS_OK) return st;
+  }
+  return CHORUS_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int32_t chorus_denoise_step(const chorus_model_shape* model, const chorus_block_weights* blocks,
+                            const chorus_glue_weights* gw, float* latent, const int32_t* token_idx, int64_t Ls,
+                            const uint16_t* text_ctx, const float* t_mod, const float* t_head,
+                            const float* tgaa_key_scale, float gamma_o, float dsigma, const float* SL,
+                            const uint8_t* mask_edit, void* ws, size_t ws_bytes, void* stream) {
+  if (!text_ctx) return CHORUS_E_ARG;
+  return denoise_step_impl(model, blocks, gw, latent, token_idx, Ls, text_ctx, nullptr, t_mod, t_head, tgaa_key_scale,
+                           gamma_o, dsigma, SL, mask_edit, ws, ws_bytes, stream);
+}
+
+int32_t chorus_denoise_step_kv(const chorus_model_shape* model, const chorus_block_weights* blocks,
+                               const chorus_glue_weights* gw, float* latent, const int32_t* token_idx, int64_t Ls,
+                               const void* text_kv, const float* t_mod, const float* t_head,
+                               const float* tgaa_key_scale, float gamma_o, float dsigma, const float* SL,
+                               const uint8_t* mask_edit, void* ws, size_t ws_bytes, void* stream) {
+  if (!text_kv) return CHORUS_E_ARG;
+  return denoise_step_impl(model, blocks, gw, latent, token_idx, Ls, nullptr, (const uint8_t*)text_kv, t_mod, t_head,
+                           tgaa_key_scale, gamma_o, dsigma, SL, mask_edit, ws, ws_bytes, stream);
+}
+
+size_t chorus_model_text_kv_bytes(const chorus_model_shape* model) {
+  if (check_model(model) != CHORUS_OK) return 0;
+  return (size_t)model->n_blocks * chorus_text_kv_bytes(&model->block);
+}
+
+int32_t chorus_model_text_kv_project(const chorus_model_shape* model, const chorus_block_weights* blocks,
+                                     const uint16_t* text_ctx, void* text_kv, void* ws, size_t ws_bytes, void* stream) {
+  int32_t st = check_model(model);
+  if (st != CHORUS_OK) return st;
+  if (model->n_blocks == 0) return CHORUS_OK;
+  if (!blocks || !text_ctx || !text_kv) return CHORUS_E_ARG;
+  const size_t kv_bytes = chorus_text_kv_bytes(&model->block);
+  for (int b = 0; b < model->n_blocks; ++b) {
+    st = chorus_text_kv_project(&model->block, &blocks[b], text_ctx, (uint16_t*)((uint8_t*)text_kv + b * kv_bytes), ws,
+                                ws_bytes, stream);
     if (st != CHORUS_OK) return st;
   }
   return CHORUS_OK;
@@ -147,6 +200,10 @@ struct RunWs {
   size_t compact_ws_bytes;
   void* step;
   size_t step_bytes;
+  void* text_kv;       // per-block text K / V of this request
+  size_t text_kv_bytes;
+  void* text_kv_ws;
+  size_t text_kv_ws_bytes;
   size_t bytes;
 };
 
@@ -170,6 +227,10 @@ RunWs carve_run(const chorus_model_shape& m, int64_t N, void* base) {
   w.compact_ws = take(w.compact_ws_bytes);
   w.step_bytes = chorus_denoise_step_workspace_bytes(&m, Ltok);
   w.step = take(w.step_bytes);
+  w.text_kv_bytes = (size_t)m.n_blocks * chorus_text_kv_bytes(&m.block);
+  w.text_kv = take(w.text_kv_bytes);
+  w.text_kv_ws_bytes = chorus_text_kv_workspace_bytes(&m.block);
+  w.text_kv_ws = take(w.text_kv_ws_bytes);
   w.bytes = off;
   return w;
 }
@@ -239,6 +300,12 @@ int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_w
     result->Ls = cnt;
   }
 
+  // cross-attention keys / values depend only on the prompt: project them once per block for all computed steps
+  if (K1 < rq->n_steps && m.n_blocks > 0) {
+    st = chorus_model_text_kv_project(model, blocks, rq->text_ctx, w.text_kv, w.text_kv_ws, w.text_kv_ws_bytes, stream);
+    if (st != CHORUS_OK) return st;
+  }
+
   for (int i = 0; i < rq->n_steps; ++i) {
     const chorus_step_plan& p = plan_buf[i];
     if (p.stage == 1) {
@@ -260,11 +327,11 @@ int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_w
     const float* t_mod = rq->t_mods + (size_t)i * 6 * D;
     const float* t_head = rq->t_heads + (size_t)i * 2 * D;
     if (p.stage == 2) {
-      st = chorus_denoise_step(model, blocks, gw, latent, w.idx, Ls, rq->text_ctx, t_mod, t_head, ks, p.gamma_o, dsigma,
-                               SL, rq->mask_edit, w.step, w.step_bytes, stream);
+      st = denoise_step_impl(model, blocks, gw, latent, w.idx, Ls, rq->text_ctx, m.n_blocks > 0 ? (const uint8_t*)w.text_kv : nullptr,
+                             t_mod, t_head, ks, p.gamma_o, dsigma, SL, rq->mask_edit, w.step, w.step_bytes, stream);
     } else {
-      st = chorus_denoise_step(model, blocks, gw, latent, nullptr, Ltok, rq->text_ctx, t_mod, t_head, ks, p.gamma_o,
-                               dsigma, nullptr, nullptr, w.step, w.step_bytes, stream);
+      st = denoise_step_impl(model, blocks, gw, latent, nullptr, Ltok, rq->text_ctx, m.n_blocks > 0 ? (const uint8_t*)w.text_kv : nullptr,
+                             t_mod, t_head, ks, p.gamma_o, dsigma, nullptr, nullptr, w.step, w.step_bytes, stream);
     }
     if (st != CHORUS_OK) return st;
   }

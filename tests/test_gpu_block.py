@@ -173,3 +173,50 @@ def test_block_deterministic():
     a = _run_block(bs, w, inp, gamma_o=1.5)
     b = _run_block(bs, w, inp, gamma_o=1.5)
     np.testing.assert_array_equal(a, b)
+
+
+@pytest.mark.parametrize("name", ["c1", "wan1p3b_small"])
+def test_block_cached_text_kv_is_bit_identical_and_right(name):
+    """Text keys / values projected once (cross-attention depends on the prompt only) and reused: the block gives the
+    bits of the call that projects them itself, with and without TGAA, and the cached keys are the oracle's."""
+    print(f"[case] block cached text K/V {name}", flush=True)
+    bs = synth.SHAPES[name]
+    w = synth.stress_block_weights(bs, 2) if name == "c1" else synth.block_weights(bs, 2)
+    inp = synth.block_inputs(bs, 2, x_std=1.0)
+    shape = P.make_block_shape(bs.D, bs.H, bs.dh, bs.F, bs.Lt, bs.grid)
+    dw = P.upload_block_weights(w)
+    ctx, tmod = dev_bf16(inp["text_ctx"]), dev_f32(inp["t_mod"])
+    kv = B.chorus_text_kv_project(shape, dw, ctx)
+    g = dev_f32(synth.tdiff_scale(bs.Lt, 1.5, seed=2, n_diff=max(1, bs.Lt // 4)))
+    for ks, go in ((None, 1.0), (g, 1.3)):
+        xa, xb = dev_f32(inp["x"]), dev_f32(inp["x"])
+        P.chorus_dit_block_step(shape, dw, xa, xa.shape[0], None, ctx, tmod, ks, go)
+        B.chorus_dit_block_step_kv(shape, dw, xb, xb.shape[0], None, kv, tmod, ks, go)
+        assert torch.equal(xa, xb)
+        # a second use of the same cache entry (the next denoising step) finds it unchanged
+        xc = dev_f32(inp["x"])
+        B.chorus_dit_block_step_kv(shape, dw, xc, xc.shape[0], None, kv, tmod, ks, go)
+        assert torch.equal(xa, xc)
+    # the cached keys against the oracle: k = RMSNorm(ctx W_ck^T + b) head-major, one bf16 rounding of the projection
+    # and one of the result
+    LtPad = (bs.Lt + 63) // 64 * 64
+    half = (LtPad * bs.D * 2 + 255) // 256 * 256
+    kc = kv[:LtPad * bs.D * 2].view(torch.bfloat16).view(bs.H, LtPad, bs.dh)
+    vt = kv[half:half + LtPad * bs.D * 2].view(torch.bfloat16).view(bs.D, LtPad)
+    kvp = O.linear(inp["text_ctx"], w["w_ckv"], w["b_ckv"])
+    k_ref = O.rmsnorm(kvp[:, :bs.D], w["g_ck"]).reshape(bs.Lt, bs.H, bs.dh).transpose(1, 0, 2)
+    a, r = errs(kc[:, :bs.Lt].float().cpu().numpy(), k_ref)
+    print(f"[parity] cached text K: max_abs={a:.3e} rel_l2={r:.3e}", flush=True)
+    assert r <= 5e-3
+    assert float(kc[:, bs.Lt:].float().abs().max()) == 0.0 if LtPad > bs.Lt else True     # pad keys are zero
+    # V^T holds token 8u+4c+i of every group of 16 at position 8c+4u+i (the attention kernel's operand order)
+    v_ref = kvp[:, bs.D:]
+    pos = np.arange(LtPad)
+    grp, o = pos // 16 * 16, pos % 16
+    c, u, i = o // 8, (o % 8) // 4, o % 4
+    tok = grp + 8 * u + 4 * c + i
+    vt_h = vt.float().cpu().numpy()
+    valid = tok < bs.Lt
+    a, r = errs(vt_h[:, valid], v_ref[tok[valid]].T)
+    print(f"[parity] cached text V^T: max_abs={a:.3e} rel_l2={r:.3e}", flush=True)
+    assert r <= 5e-3

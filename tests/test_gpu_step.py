@@ -152,3 +152,31 @@ def test_denoise_run_four_step_schedule(name, n_blocks):
                                md.d_theads, md.d_ctx)
     assert (res["index"], res["hit"], res["K1"], res["K2"]) == (-1, False, 0, 0)
     check(host(dl), ref, "run empty cache latent")
+
+
+def test_denoise_step_with_cached_text_kv_is_bit_identical():
+    print("[case] denoise_step_kv vs denoise_step (c1, 2 blocks, stage 3 and stage 2)", flush=True)
+    bs = synth.SHAPES["c1"]
+    md = Model(bs, 2, stress=True)
+    lat = synth.latent(bs, 3, std=1.0)
+    SL = synth.latent(bs, 3, "SL", std=1.0)
+    kv = B.chorus_model_text_kv_project(md.model, md.arr, md.d_ctx)
+    g = dev_f32(synth.tdiff_scale(bs.Lt, 1.5))
+    # stage 3, two consecutive steps through the same cache
+    da, db = dev_f32(lat), dev_f32(lat)
+    for i in (2, 3):
+        B.chorus_denoise_step(md.model, md.arr, md.dglue, da, None, bs.L, md.d_ctx, md.d_tmods[i], md.d_theads[i], dsigma=-0.25)
+        B.chorus_denoise_step_kv(md.model, md.arr, md.dglue, db, None, bs.L, kv, md.d_tmods[i], md.d_theads[i], dsigma=-0.25)
+        assert torch.equal(da, db)
+    # stage 2 with TGAA
+    T, Hg, Wg = bs.grid
+    see = synth.box_mask(bs.grid, T, Hg - 2, Wg - 2, 0, 1, 1)
+    idx_d, cnt = P.chorus_region_compact(torch.from_numpy(see).to(DEV))
+    Ls = int(cnt.cpu()[0])
+    da, db = dev_f32(lat), dev_f32(lat)
+    m_d = torch.from_numpy(see).to(DEV)
+    B.chorus_denoise_step(md.model, md.arr, md.dglue, da, idx_d, Ls, md.d_ctx, md.d_tmods[1], md.d_theads[1],
+                          tgaa_key_scale=g, gamma_o=1.5, dsigma=-0.25, SL=dev_f32(SL), mask_edit=m_d)
+    B.chorus_denoise_step_kv(md.model, md.arr, md.dglue, db, idx_d, Ls, kv, md.d_tmods[1], md.d_theads[1],
+                             tgaa_key_scale=g, gamma_o=1.5, dsigma=-0.25, SL=dev_f32(SL), mask_edit=m_d)
+    assert torch.equal(da, db)
