@@ -65,6 +65,18 @@ int32_t chorus_cache_lookup(const float* cache_emb, int64_t N, int32_t d, const 
                             chorus_lookup_result* out, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Cache update (Sec. 3.1 "Cache Update"): after a miss the request's prompt embedding and
+ * an intermediate latent are stored for later requests. Two device copies, bit for bit.
+ *   cache_emb      dev [capacity, d] fp32, row `slot` is overwritten with emb [d]
+ *   cache_latents  dev [capacity, latent_elems] fp32, row `slot` is overwritten with latent
+ * Which entry to replace is the caller's policy. A never-written (all-zero) row scores
+ * -inf in chorus_cache_lookup, so a zero-filled cache is an empty one.
+ * Errors: CHORUS_E_ARG (null pointer, slot outside [0, capacity), d or latent_elems <= 0).
+ * ------------------------------------------------------------------------ */
+int32_t chorus_cache_insert(float* cache_emb, float* cache_latents, int64_t capacity, int64_t slot, int32_t d,
+                            int64_t latent_elems, const float* emb, const float* latent, void* stream);
+
+/* ------------------------------------------------------------------------
  * Stage boundaries (Eq. 1) and TGAA decay (Eq. 4). Host only.
  * The paper fixes properties, not formulas: 0 <= K1 <= K2 <= N, both monotone in
  * the matching score m, K1 = K2 = 0 when m < tau, amplification factors >= 1 that

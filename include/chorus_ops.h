@@ -160,6 +160,9 @@ int32_t chorus_denoise_step_kv(const chorus_model_shape* model, const chorus_blo
  *      steps [K2, N): chorus_denoise_step on all tokens
  *      (the text keys / values of every block are projected once, before the first computed step)
  * A miss (m < tau, or an empty cache) runs N plain steps from the caller's latent.
+ * Cache update: when store_slot >= 0 and the request is a miss, the query and the latent after
+ * store_after steps (1 <= store_after <= n_steps; the intermediate state a later hit with
+ * K1 = store_after resumes from) are written to entry store_slot with chorus_cache_insert.
  * One cached latent per entry serves both the stage-1 copy and the stage-2 fusion.
  * Two host synchronisations: after the lookup and after the compaction count.
  *   cache_emb dev [N, d]; cache_latents dev [N, C, T, Hl, Wl] fp32; query dev [d]
@@ -172,8 +175,8 @@ int32_t chorus_denoise_step_kv(const chorus_model_shape* model, const chorus_blo
  * chorus_stage1_copy is the full-reuse copy on its own (n fp32 elements).
  * ------------------------------------------------------------------------ */
 typedef struct {
-  const float* cache_emb;
-  const float* cache_latents;
+  float* cache_emb;      /* read; entry store_slot is written on a miss */
+  float* cache_latents;
   int64_t cache_N;
   int32_t cache_d;
   const float* query;
@@ -187,6 +190,8 @@ typedef struct {
   const uint8_t* tdiff;
   const uint8_t* mask_see;
   const uint8_t* mask_edit;
+  int64_t store_slot;    /* -1: no cache update */
+  int32_t store_after;
 } chorus_request;
 
 typedef struct {

@@ -73,6 +73,18 @@ DEFAULT_SCHED = dict(a1=0.25, b1=0.25, a2=0.25, b2=0.25, r3=1, Gamma_k=1.5, Gamm
                      gamma_override=0.0)
 
 
+def cache_insert(cache_emb, cache_latents, slot, emb, latent):
+    """Cache update (Sec. 3.1 "Cache Update"): after a miss the request's prompt embedding and an
+    intermediate latent are stored for later requests. Which entry is replaced is the caller's
+    policy (the paper names none). Returns new arrays; the inputs are left untouched."""
+    ce = np.array(cache_emb, copy=True)
+    cl = np.array(cache_latents, copy=True)
+    assert 0 <= slot < ce.shape[0] == cl.shape[0]
+    ce[slot] = np.asarray(emb, ce.dtype)
+    cl[slot] = np.asarray(latent, cl.dtype).reshape(cl.shape[1:])
+    return ce, cl
+
+
 def denoise_schedule(m, tau, N, params=None):
     """(K1, K2, plan) with plan[i] = (stage, gamma_k, gamma_o) for step i (0-based).
 
@@ -457,12 +469,17 @@ def denoise_step(latent, blocks, gw, shape, text_ctx, t_mod, t_head, dsigma,
 
 
 def run_schedule(plan, sigmas, latent0, SL, blocks, gw, shape, text_ctx, t_mods, t_heads,
-                 mask_see=None, mask_edit=None, key_scale_of=None):
+                 mask_see=None, mask_edit=None, key_scale_of=None, store_after=None):
     """The three-stage loop (Sec. 3.1): stage-1 steps take the source latent as is,
     stage-2 steps run the selective region path, stage-3 steps run everything.
-    key_scale_of(gamma_k) builds the per-text-token key scale for a step."""
+    key_scale_of(gamma_k) builds the per-text-token key scale for a step.
+    With store_after = k the latent after k steps (the intermediate state a cache update keeps)
+    is returned as well."""
     lat = np.asarray(latent0, F64)
+    snap = None
     for i, (stage, gk, go) in enumerate(plan):
+        if store_after is not None and i == store_after:
+            snap = lat.copy()
         if stage == 1:
             lat = np.asarray(SL, F64).copy()
             continue
@@ -474,4 +491,6 @@ def run_schedule(plan, sigmas, latent0, SL, blocks, gw, shape, text_ctx, t_mods,
         else:
             lat = denoise_step(lat, blocks, gw, shape, text_ctx, t_mods[i], t_heads[i], ds,
                                key_scale=ks, gamma_o=go)
+    if store_after is not None:
+        return lat, (lat.copy() if store_after == len(plan) else snap)
     return lat

@@ -65,7 +65,8 @@ class Request(C.Structure):
                 ("cache_d", C.c_int32), ("query", C.c_void_p), ("tau", C.c_float),
                 ("sched", C.POINTER(SchedParams)), ("n_steps", C.c_int32), ("sigmas", C.POINTER(C.c_float)),
                 ("t_mods", C.c_void_p), ("t_heads", C.c_void_p), ("text_ctx", C.c_void_p), ("tdiff", C.c_void_p),
-                ("mask_see", C.c_void_p), ("mask_edit", C.c_void_p)]
+                ("mask_see", C.c_void_p), ("mask_edit", C.c_void_p), ("store_slot", C.c_int64),
+                ("store_after", C.c_int32)]
 
 
 class RunResult(C.Structure):
@@ -92,6 +93,7 @@ def load():
         "chorus_last_hip_error": (i32, []),
         "chorus_cache_lookup_workspace_bytes": (sz, [i64]),
         "chorus_cache_lookup": (i32, [vp, i64, i32, vp, f32, vp, vp, sz, vp]),
+        "chorus_cache_insert": (i32, [vp, vp, i64, i64, i32, i64, vp, vp, vp]),
         "chorus_denoise_schedule": (i32, [f32, f32, i32, C.POINTER(SchedParams), C.POINTER(i32), C.POINTER(i32),
                                           C.POINTER(StepPlan)]),
         "chorus_dit_block_workspace_bytes": (sz, [C.POINTER(BlockShape), i64]),
@@ -230,6 +232,20 @@ def chorus_denoise_schedule(m, tau, N, params=None):
             lib.chorus_denoise_schedule(float(m), float(tau), int(N), C.byref(sp) if sp is not None else None,
                                         C.byref(k1), C.byref(k2), plan))
     return k1.value, k2.value, [(plan[i].stage, plan[i].gamma_k, plan[i].gamma_o) for i in range(N)]
+
+
+def chorus_cache_insert(cache_emb, cache_latents, slot, emb, latent):
+    """Overwrites cache entry `slot` with the embedding and the latent (device copies)."""
+    _chk(cache_emb, torch.float32, "cache_emb")
+    _chk(cache_latents, torch.float32, "cache_latents")
+    _chk(emb, torch.float32, "emb")
+    _chk(latent, torch.float32, "latent")
+    cap, d = cache_emb.shape
+    elems = latent.numel()
+    if emb.numel() != d or cache_latents.shape[0] != cap or cache_latents[0].numel() != elems:
+        raise TypeError("cache_insert: shapes do not match")
+    _status("chorus_cache_insert", load().chorus_cache_insert(_p(cache_emb), _p(cache_latents), cap, int(slot), d, elems,
+                                                              _p(emb), _p(latent), _stream()))
 
 
 # ---------------------------------------------------------------- region
@@ -650,8 +666,9 @@ def chorus_denoise_run_workspace_bytes(model: ModelShape, N: int) -> int:
 
 def chorus_denoise_run(model: ModelShape, blocks_arr, glue: DeviceGlue, latent, cache_emb, cache_latents, query, tau,
                        sigmas, t_mods, t_heads, text_ctx, tdiff=None, mask_see=None, mask_edit=None, sched=None,
-                       ws=None):
-    """Runs one request; returns a dict with the lookup result, K1, K2 and the stage-2 token count."""
+                       ws=None, store_slot=-1, store_after=0):
+    """Runs one request; returns a dict with the lookup result, K1, K2 and the stage-2 token count.
+    store_slot >= 0: on a miss, the query and the latent after store_after steps go into that cache entry."""
     lib = load()
     D = model.block.D
     n_steps = len(sigmas) - 1
@@ -676,7 +693,8 @@ def chorus_denoise_run(model: ModelShape, blocks_arr, glue: DeviceGlue, latent, 
     rq = Request(cache_emb.data_ptr() if N else 0, cache_latents.data_ptr() if N else 0, N, d, query.data_ptr(),
                  float(tau), C.pointer(sp) if sp is not None else None, n_steps, sig, t_mods.data_ptr(),
                  t_heads.data_ptr(), text_ctx.data_ptr(), 0 if tdiff is None else tdiff.data_ptr(),
-                 0 if mask_see is None else mask_see.data_ptr(), 0 if mask_edit is None else mask_edit.data_ptr())
+                 0 if mask_see is None else mask_see.data_ptr(), 0 if mask_edit is None else mask_edit.data_ptr(),
+                 int(store_slot), int(store_after))
     if ws is None:
         ws = _ws(lib.chorus_denoise_run_workspace_bytes(C.byref(model), N), latent.device)
     res = RunResult()

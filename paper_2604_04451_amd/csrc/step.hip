@@ -249,6 +249,16 @@ int32_t chorus_stage1_copy(float* latent, const float* SL, int64_t n, void* stre
   return device_copy(latent, SL, (long)n, (hipStream_t)stream);
 }
 
+int32_t chorus_cache_insert(float* cache_emb, float* cache_latents, int64_t capacity, int64_t slot, int32_t d,
+                            int64_t latent_elems, const float* emb, const float* latent, void* stream) {
+  if (!cache_emb || !cache_latents || !emb || !latent) return CHORUS_E_ARG;
+  if (capacity <= 0 || slot < 0 || slot >= capacity || d <= 0 || latent_elems <= 0) return CHORUS_E_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  int32_t st = device_copy(cache_emb + slot * d, emb, d, s);
+  if (st != CHORUS_OK) return st;
+  return device_copy(cache_latents + slot * latent_elems, latent, (long)latent_elems, s);
+}
+
 int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_weights* blocks,
                            const chorus_glue_weights* gw, const chorus_request* rq, float* latent,
                            chorus_run_result* result, void* ws, size_t ws_bytes, void* stream) {
@@ -258,6 +268,8 @@ int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_w
   if (rq->n_steps < 0 || rq->cache_N < 0 || rq->cache_d <= 0) return CHORUS_E_ARG;
   if (rq->n_steps > 0 && (!rq->sigmas || !rq->t_mods || !rq->t_heads || !rq->text_ctx)) return CHORUS_E_ARG;
   if (!rq->query || (rq->cache_N > 0 && (!rq->cache_emb || !rq->cache_latents))) return CHORUS_E_ARG;
+  if (rq->store_slot >= 0 && (rq->store_slot >= rq->cache_N || rq->store_after < 1 || rq->store_after > rq->n_steps))
+    return CHORUS_E_ARG;
   if (!ws) return CHORUS_E_WORKSPACE;
   const chorus_model_shape& m = *model;
   RunWs w = carve_run(m, rq->cache_N, ws);
@@ -334,6 +346,12 @@ int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_w
                              t_mod, t_head, ks, p.gamma_o, dsigma, nullptr, nullptr, w.step, w.step_bytes, stream);
     }
     if (st != CHORUS_OK) return st;
+    // cache update after a miss: keep the prompt embedding and this intermediate latent for later requests
+    if (!lr.hit && rq->store_slot >= 0 && i + 1 == rq->store_after) {
+      st = chorus_cache_insert(rq->cache_emb, rq->cache_latents, rq->cache_N, rq->store_slot, rq->cache_d, lat_elems,
+                               rq->query, latent, stream);
+      if (st != CHORUS_OK) return st;
+    }
   }
   return CHORUS_OK;
 }

@@ -117,3 +117,13 @@ def test_mask_entry_points_validate_and_pooled_extent_matches_oracle():
     assert lib.chorus_mask_hierarchy(p16, 2, 4, 4, r(0, 1, 1), r(0, 1, 1), null, null, null) == B.E_ARG
     assert lib.chorus_mask_hierarchy(p16, 2, 4, 4, None, r(0, 1, 1), C.c_void_p(32), C.c_void_p(64), null) == B.E_ARG
     assert lib.chorus_mask_hierarchy(null, 0, 4, 4, r(0, 1, 1), r(0, 1, 1), null, null, null) == B.OK
+
+
+def test_cache_insert_validates():
+    lib = P.load()
+    null, p16 = C.c_void_p(0), C.c_void_p(16)
+    assert lib.chorus_cache_insert(p16, p16, 8, 8, 16, 64, p16, p16, null) == B.E_ARG     # slot == capacity
+    assert lib.chorus_cache_insert(p16, p16, 8, -1, 16, 64, p16, p16, null) == B.E_ARG
+    assert lib.chorus_cache_insert(null, p16, 8, 0, 16, 64, p16, p16, null) == B.E_ARG
+    assert lib.chorus_cache_insert(p16, p16, 8, 0, 0, 64, p16, p16, null) == B.E_ARG
+    assert lib.chorus_cache_insert(p16, p16, 0, 0, 16, 64, p16, p16, null) == B.E_ARG

@@ -180,3 +180,61 @@ def test_denoise_step_with_cached_text_kv_is_bit_identical():
     B.chorus_denoise_step_kv(md.model, md.arr, md.dglue, db, idx_d, Ls, kv, md.d_tmods[1], md.d_theads[1],
                              tgaa_key_scale=g, gamma_o=1.5, dsigma=-0.25, SL=dev_f32(SL), mask_edit=m_d)
     assert torch.equal(da, db)
+
+
+def test_cache_insert_bit_exact():
+    print("[case] cache_insert", flush=True)
+    cap, d, shape = 6, 64, (3, 2, 4, 5)
+    emb0 = synth.normal(0, "ci.emb", (cap, d))
+    lat0 = synth.normal(0, "ci.lat", (cap,) + shape)
+    q, lat = synth.normal(0, "ci.q", (d,)), synth.normal(0, "ci.new", shape)
+    de, dl = dev_f32(emb0), dev_f32(lat0)
+    B.chorus_cache_insert(de, dl, 3, dev_f32(q), dev_f32(lat))
+    oe, ol = O.cache_insert(emb0, lat0, 3, q, lat)
+    assert host(de).tobytes() == oe.tobytes() and host(dl).tobytes() == ol.tobytes()
+    with pytest.raises(B.ChorusError):
+        B.chorus_cache_insert(de, dl, cap, dev_f32(q), dev_f32(lat))
+
+
+def test_cold_start_miss_stores_then_same_prompt_hits():
+    """Sec. 3.1 end to end: an empty (zero-filled) cache misses and runs plain generation, the cache update keeps the
+    prompt embedding and the latent after one step; the same prompt then hits that entry with score 1 and resumes
+    from the stored latent (stage 1), a region step (stage 2) and full steps (stage 3)."""
+    print("[case] cold start -> store -> hit (c1, 2 blocks)", flush=True)
+    bs = synth.SHAPES["c1"]
+    md = Model(bs, 2)
+    cap, slot = 8, 5
+    cache = torch.zeros(cap, bs.cache_d, device=DEV)
+    cache_lat = torch.zeros((cap,) + bs.latent_shape, device=DEV)
+    q = synth.normal(7, "cold.q", (bs.cache_d,))
+    noise = synth.latent(bs, 7, "noise", std=1.0)
+    see = synth.box_mask(bs.grid, bs.grid[0], bs.grid[1] - 2, bs.grid[2] // 2, 0, 1, 1)
+    d_see = torch.from_numpy(see).to(DEV)
+    sched = dict(gamma_override=1.5)
+    # 1. cold start
+    dl = dev_f32(noise)
+    res = B.chorus_denoise_run(md.model, md.arr, md.dglue, dl, cache, cache_lat, dev_f32(q), 0.75, md.sigmas, md.d_tmods,
+                               md.d_theads, md.d_ctx, mask_see=d_see, mask_edit=d_see, sched=sched, store_slot=slot,
+                               store_after=1)
+    assert not res["hit"] and (res["K1"], res["K2"]) == (0, 0)
+    plan = [(3, 1.0, 1.0)] * 4
+    ref, snap = O.run_schedule(plan, md.sigmas, noise, None, md.blocks, md.gw, bs, md.ctx, md.t_mods, md.t_heads, store_after=1)
+    check(host(dl), ref, "cold-start latent")
+    check(host(cache_lat[slot]), snap, "stored intermediate latent")
+    assert host(cache[slot]).tobytes() == q.tobytes()                       # the prompt embedding, bit for bit
+    others = [i for i in range(cap) if i != slot]
+    assert float(cache[others].abs().max()) == 0.0 and float(cache_lat[others].abs().max()) == 0.0
+    stored = host(cache_lat[slot]).copy()
+    # 2. the same prompt again: hit on the stored entry
+    noise2 = synth.latent(bs, 8, "noise", std=1.0)
+    dl = dev_f32(noise2)
+    res = B.chorus_denoise_run(md.model, md.arr, md.dglue, dl, cache, cache_lat, dev_f32(q), 0.75, md.sigmas, md.d_tmods,
+                               md.d_theads, md.d_ctx, mask_see=d_see, mask_edit=d_see, sched=sched, store_slot=slot,
+                               store_after=1)
+    assert res["hit"] and res["index"] == slot and abs(res["score"] - 1.0) < 1e-5
+    K1, K2, plan = O.denoise_schedule(float(np.float32(res["score"])), float(np.float32(0.75)), 4, sched)
+    assert (res["K1"], res["K2"]) == (K1, K2) and K1 >= 1
+    ref = O.run_schedule(plan, md.sigmas, noise2, stored, md.blocks, md.gw, bs, md.ctx, md.t_mods, md.t_heads,
+                         mask_see=see, mask_edit=see, key_scale_of=lambda gk: np.full(bs.Lt, gk))
+    check(host(dl), ref, "warm latent")
+    assert host(cache_lat[slot]).tobytes() == stored.tobytes()              # a hit does not update the cache

@@ -593,3 +593,46 @@ def test_keyframe_propagation():
         np.testing.assert_array_equal(fr[f], (km[fk[f]] != 0).astype(np.uint8))
     with pytest.raises(AssertionError):
         O.mask_propagate_keyframes(km, np.array([0, 3]))
+
+
+# ------------------------------------------------------------------ cache update (Sec. 3.1 "Cache Update")
+
+def test_cache_insert_then_lookup():
+    cache = np.zeros((6, 32), np.float32)                     # a zero-filled cache is an empty one
+    lats = np.zeros((6, 2, 3), np.float32)
+    q = synth.normal(0, "ins.q", (32,))
+    j0, m0, hit0 = O.cache_lookup(cache, q, 0.75)
+    assert not hit0 and m0 == -np.inf
+    lat = synth.normal(0, "ins.lat", (2, 3))
+    c2, l2 = O.cache_insert(cache, lats, 4, q, lat)
+    assert not cache.any() and not lats.any()                 # inputs untouched
+    j, m, hit = O.cache_lookup(c2, q, 0.75)
+    assert (j, hit) == (4, True) and abs(m - 1.0) < 1e-6      # the stored prompt is found with cosine 1
+    np.testing.assert_array_equal(l2[4], lat)
+    np.testing.assert_array_equal(np.delete(c2, 4, 0), np.delete(cache, 4, 0))   # every other entry unchanged
+    np.testing.assert_array_equal(np.delete(l2, 4, 0), np.delete(lats, 4, 0))
+    # replacing an entry: the old prompt no longer matches
+    q2 = synth.normal(1, "ins.q", (32,))
+    c3, _ = O.cache_insert(c2, l2, 4, q2, lat)
+    assert not O.cache_lookup(c3, q, 0.75)[2] and O.cache_lookup(c3, q2, 0.75)[0] == 4
+    with pytest.raises(AssertionError):
+        O.cache_insert(cache, lats, 6, q, lat)
+
+
+def test_run_schedule_snapshot_is_the_prefix_run():
+    # the latent kept by a cache update after k steps equals running only the first k steps
+    bs = synth.SHAPES["c1"]
+    blocks = [synth.block_weights(bs, 0, 0)]
+    gw = synth.glue_weights(bs, 0)
+    ctx = synth.round_bf16(synth.normal(0, "snap.ctx", (bs.Lt, bs.D), 1.0))
+    t_mods = synth.normal(0, "t_mods", (4, 6, bs.D), 0.02)
+    t_heads = synth.normal(0, "t_heads", (4, 2, bs.D), 0.02)
+    sig = [1.0, 0.75, 0.5, 0.25, 0.0]
+    lat0 = synth.latent(bs, 0, "noise", std=1.0)
+    plan = [(3, 1.0, 1.0)] * 4
+    full, snap = O.run_schedule(plan, sig, lat0, None, blocks, gw, bs, ctx, t_mods, t_heads, store_after=2)
+    two = O.run_schedule(plan[:2], sig[:3], lat0, None, blocks, gw, bs, ctx, t_mods[:2], t_heads[:2])
+    np.testing.assert_array_equal(snap, two)
+    assert not np.array_equal(full, snap)
+    _, last = O.run_schedule(plan, sig, lat0, None, blocks, gw, bs, ctx, t_mods, t_heads, store_after=4)
+    np.testing.assert_array_equal(last, full)
