@@ -191,7 +191,7 @@ def main():
                      "traffic": (SELF_ATTN_TRAFFIC_BYTES_DEFAULT if (args.workload == "wan1p3b_480p" and args.blocks is None
                                                                       and args.region == 0.4 and not args.bernoulli) else None),
                      "algorithmic_bytes": (30 * 4 * 2.0 * Ls * D + 60 * 4 * 2.0 * L * D) / 90.0,
-                     "kernel": "attention_kernel (self-attention)", "launches": attn_n},
+                     "kernel": "attention_pp_kernel<128,128,false> (self-attention)", "launches": attn_n},
     }
     if args.plain:
         torch.cuda.synchronize()

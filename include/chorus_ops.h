@@ -37,7 +37,8 @@ int32_t chorus_gemm_bf16(const uint16_t* A, const uint16_t* W, int64_t M, int32_
                          void* out, const float* bias, const float* gate0, const float* gate1, float scale,
                          void* stream);
 
-/* Benchmark hook: 0 = default kernel choice, 1 = never use the direct-to-LDS 256x256 kernel. Host only. */
+/* Benchmark hook: 0 = default kernel choice, 1 = never use the direct-to-LDS 256x256 kernel, 2 = always use it
+ * when the problem has at least 256 such tiles. Host only. */
 int32_t chorus_gemm_set_variant(int32_t v);
 
 /* out bf16 [L, D] = LN(x) * (mul_base + mul0 + mul1) + (add0 + add1), LN over D without

@@ -25,7 +25,7 @@ __device__ __forceinline__ float gelu_tanh_fast(float x) {
   return x * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
-int g_gemm_variant = 0;  // 0 = default choice, 1 = never use the direct-to-LDS kernel (benchmark comparisons)
+int g_gemm_variant = 0;  // 0 = default choice, 1 = never use the direct-to-LDS kernel, 2 = always when it has >= 256 tiles (comparisons)
 
 struct EpiArgs {
   void* out;
@@ -435,10 +435,15 @@ extern "C" int32_t chorus_gemm_bf16(const uint16_t* A, const uint16_t* W, int64_
     return CHORUS_E_ARG;
   EpiArgs ep{out, bias, gate0, gate1, scale};
   hipStream_t s = (hipStream_t)stream;
-  // small problems get the smaller tile so that more workgroups exist
+  // small problems get the smaller tile so that more workgroups exist; between the two large tiles the choice goes
+  // by rounds of 256 workgroups: a 256 x 128 tile takes about 0.6 of the time of a 256 x 256 one
   long big_tiles = ((M + 255) / 256) * ((N + 127) / 128);
   long dl_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-  if (g_gemm_variant != 1 && dl_tiles >= 256) return launch_gemm_dl(A, W, (long)M, N, K, epilogue, ep, s);
+  if (g_gemm_variant != 1 && dl_tiles >= 256) {
+    const double t_dl = (double)((dl_tiles + 255) / 256);
+    const double t_big = 0.6 * (double)((big_tiles + 255) / 256);
+    if (g_gemm_variant == 2 || t_dl <= t_big) return launch_gemm_dl(A, W, (long)M, N, K, epilogue, ep, s);
+  }
   if (big_tiles >= 256) return launch_gemm<256, 128, 128, 64>(A, W, (long)M, N, K, epilogue, ep, s);
   return launch_gemm<128, 64, 64, 32>(A, W, (long)M, N, K, epilogue, ep, s);
 }
