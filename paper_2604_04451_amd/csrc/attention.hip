@@ -407,7 +407,7 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    mx = fmaxf(mx, swap_halves(mx));
     const float mxs = COLSCALE ? mx : mx * scale_log2;
     if (__any(mxs > m_run + 8.0f)) {
       const float m_new = fmaxf(m_run, mxs);
