@@ -41,6 +41,50 @@ struct EpiArgs {
 template <int EPI, int TM, int TN>
 __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], const EpiArgs& ep, long m_base, int n_base,
                                               long M, int N) {
+  if constexpr (EPI == CHORUS_EPI_RESID) {
+    // Read-modify-write of the fp32 residual: all 4 * TM loads of a 32-column block are issued before the first store
+    // (the compiler cannot hoist them itself: it must assume a store may alias a later load), so the block costs one
+    // memory round trip instead of one per row group.
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int nj = n_base + 32 * j;
+      f32x4 cur[4][TM];
+      bool ok[4][TM];
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const long m = m_base + 32 * i;
+          ok[g][i] = (nj + 8 * g < N) && (m < M);
+          // unconditional loads from a clamped address (predicated ones end up in scratch)
+          const long mc = m < M ? m : M - 1;
+          const int nc = nj + 8 * g < N ? nj + 8 * g : 0;
+          cur[g][i] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(ep.out) + mc * N + nc);
+        }
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n = nj + 8 * g;
+        if (n >= N) continue;
+        f32x4 bias = {0.f, 0.f, 0.f, 0.f};
+        if (ep.bias) bias = *reinterpret_cast<const f32x4*>(ep.bias + n);
+        f32x4 gate = {1.f, 1.f, 1.f, 1.f};
+        if (ep.gate0 || ep.gate1) {
+          gate = f32x4{0.f, 0.f, 0.f, 0.f};
+          if (ep.gate0) gate += *reinterpret_cast<const f32x4*>(ep.gate0 + n);
+          if (ep.gate1) gate += *reinterpret_cast<const f32x4*>(ep.gate1 + n);
+        }
+        gate *= ep.scale;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          if (!ok[g][i]) continue;
+          const long m = m_base + 32 * i;
+          f32x4 v = {acc[i][j][4 * g + 0], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(ep.out) + m * N + n) = cur[g][i] + gate * (v + bias);
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
 #pragma unroll
@@ -142,6 +186,60 @@ __device__ __forceinline__ void gemm_epilogue_bf16_lds(const f32x16 (&acc)[4][2]
   }
 }
 
+// fp32 residual epilogue through LDS for a 128 x 64 wave tile: 32 rows at a time are written to a private LDS
+// region as [32][64] floats (row stride 68 floats, so the 16-byte writes of 16 lanes fall in distinct banks), then
+// read back with 16 lanes per row, so every global load / store instruction moves four full 256-byte row segments
+// of the residual instead of 32-byte pieces of 32 rows. `cw` is this wave's region of 32 x 68 floats; the caller
+// guarantees that no wave still reads the main-loop LDS it overlays.
+constexpr int EPI_F32_STRIDE = 64 + 4;
+constexpr int EPI_F32_WAVE = 32 * EPI_F32_STRIDE;  // floats per wave
+
+__device__ __forceinline__ void gemm_epilogue_resid_lds(const f32x16 (&acc)[4][2], const EpiArgs& ep, float* cw, long m_wave0,
+                                                        int n_wave0, long M, int N, int lane) {
+  const int lrow = lane & 31, c4 = (lane >> 5) * 4;
+  const int rrow = lane >> 4, rcol = (lane & 15) * 4;  // read-back: 4 rows per instruction, 16 lanes per row
+  const int n = n_wave0 + rcol;
+  const bool n_ok = n < N;  // N % 8 == 0: the four columns are in or out together
+  f32x4 bias = {0.f, 0.f, 0.f, 0.f}, gate = {1.f, 1.f, 1.f, 1.f};
+  if (n_ok) {
+    if (ep.bias) bias = *reinterpret_cast<const f32x4*>(ep.bias + n);
+    if (ep.gate0 || ep.gate1) {
+      gate = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (ep.gate0) gate += *reinterpret_cast<const f32x4*>(ep.gate0 + n);
+      if (ep.gate1) gate += *reinterpret_cast<const f32x4*>(ep.gate1 + n);
+    }
+    gate *= ep.scale;
+  }
+  float* out = reinterpret_cast<float*>(ep.out);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    // the residual rows of this pass are requested before the LDS round trip
+    f32x4 cur[8];
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      long m = m_wave0 + 32 * i + 4 * it + rrow;
+      if (m > M - 1) m = M - 1;  // rows past the end read the last row (never stored)
+      cur[it] = *reinterpret_cast<const f32x4*>(out + m * N + (n_ok ? n : 0));
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x4 v = {acc[i][j][4 * g + 0], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        *reinterpret_cast<f32x4*>(cw + lrow * EPI_F32_STRIDE + 32 * j + 8 * g + c4) = v;
+      }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");  // LDS ops of one wave stay in order
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(cw + (4 * it + rrow) * EPI_F32_STRIDE + rcol);
+      const long m = m_wave0 + 32 * i + 4 * it + rrow;
+      if (n_ok && m < M) *reinterpret_cast<f32x4*>(out + m * N + n) = cur[it] + gate * (v + bias);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 template <int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
                                                         long M, int N, int K, EpiArgs ep, int tiles_m, int tiles_n) {
@@ -237,7 +335,12 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t* __res
     }
   }
 
-  gemm_epilogue<EPI, TM, TN>(acc, ep, m0 + wm * WM + lrow, n0 + wn * WN + (lane >> 5) * 4, M, N);
+  if constexpr (EPI == CHORUS_EPI_RESID && TM == 4 && TN == 2 && BM * LS * 2 >= 4 * EPI_F32_WAVE * 4) {
+    __syncthreads();  // the staging regions overlay the A tile
+    gemm_epilogue_resid_lds(acc, ep, reinterpret_cast<float*>(sA) + wave * EPI_F32_WAVE, m0 + wm * WM, n0 + wn * WN, M, N, lane);
+  } else {
+    gemm_epilogue<EPI, TM, TN>(acc, ep, m0 + wm * WM + lrow, n0 + wn * WN + (lane >> 5) * 4, M, N);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -360,6 +463,10 @@ __global__ __launch_bounds__(512, 2) void gemm_dl_kernel(const uint16_t* __restr
   if constexpr (EPI == CHORUS_EPI_BF16 || EPI == CHORUS_EPI_GELU_BF16) {
     lds_barrier();  // the staging regions overlay the operand stages
     gemm_epilogue_bf16_lds<EPI>(acc, ep, smem + wave * EPI_LDS_WAVE, m0 + wm * WM, n0 + wn * WN, M, N, lane);
+  } else if constexpr (EPI == CHORUS_EPI_RESID) {
+    lds_barrier();
+    gemm_epilogue_resid_lds(acc, ep, reinterpret_cast<float*>(smem_raw) + wave * EPI_F32_WAVE, m0 + wm * WM, n0 + wn * WN, M, N,
+                            lane);
   } else {
     gemm_epilogue<EPI, TM, TN>(acc, ep, m0 + wm * WM + lrow, n0 + wn * WN + (lane >> 5) * 4, M, N);
   }
