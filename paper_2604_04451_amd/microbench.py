@@ -77,6 +77,14 @@ def main():
         report(f"region_blend {name}", 2 * lat_bytes + L, med, best)
     med, best = timeit(lambda i: B.chorus_stage1_copy(bufs[i % 24][2], bufs[i % 24][0]), n)
     report("stage1_copy", 2 * lat_bytes, med, best)
+    # the same kernels on 16 latents per call (C = 256 planes): large enough to leave the launch floor behind
+    big = [torch.randn(3, 16 * C_, T, Hl, Wl, device=DEV, generator=g) for _ in range(3)]
+    for name, m in (("box 40 %", box.reshape(-1)), ("Bernoulli 50 %", bern)):
+        med, best = timeit(lambda i: B.chorus_region_blend(big[i % 3][2], big[i % 3][0], big[i % 3][1], m), n)
+        report(f"region_blend {name}, 16 latents per call", 16 * (2 * lat_bytes) + L, med, best)
+    med, best = timeit(lambda i: B.chorus_stage1_copy(big[i % 3][2], big[i % 3][0]), n)
+    report("stage1_copy, 16 latents per call", 32 * lat_bytes, med, best)
+    del big
 
     # ---- compaction and row moves
     idx = torch.empty(L, dtype=torch.int32, device=DEV)
