@@ -24,6 +24,10 @@ What the paper fixes and what it leaves open
   arithmetic here is the Wan2.1-shaped block the benchmark configurations name
   (AdaLN modulation, RMSNorm on q/k, 3-D RoPE, tanh-GELU FFN); each choice is
   stated at the function that makes it.
+* The sampler (Sec. 4.1: DPM++ with default settings, no formulas given): the published
+  DPM-Solver++ multistep update of order <= 2 in data-prediction form on the rectified-flow
+  path, plus classifier-free guidance for the models that use it. The Euler update of
+  `denoise_step` is its first-order case.
 """
 from __future__ import annotations
 
@@ -409,8 +413,8 @@ def region_blend(L, SL, mask_edit_tok, grid, patch):
 
 # --------------------------------------------------------------------------
 # Step glue: declared stand-ins that close the denoising loop around the blocks
-# (the paper's sampler is DPM++ with default settings, Sec. 4.1; its coefficients
-#  are not given, so an Euler flow-matching update stands in)
+# (the paper's sampler is DPM++ with default settings, Sec. 4.1; the Euler flow-matching update
+#  used here is that solver's first-order step, the multistep form follows further down)
 # --------------------------------------------------------------------------
 
 
@@ -493,4 +497,129 @@ def run_schedule(plan, sigmas, latent0, SL, blocks, gw, shape, text_ctx, t_mods,
                                key_scale=ks, gamma_o=go)
     if store_after is not None:
         return lat, (lat.copy() if store_after == len(plan) else snap)
+    return lat
+
+
+# --------------------------------------------------------------------------
+# Sampler (Sec. 4.1 names the DPM++ solver with default settings and gives no formulas):
+# DPM-Solver++ in data-prediction form, multistep, order <= 2, as published by its authors,
+# on the rectified-flow path x_sigma = alpha x0 + sigma eps with alpha = 1 - sigma, the path
+# the Wan2.1 models are trained on. Notation of the solver paper: lambda = log(alpha / sigma),
+# h = lambda_t - lambda_s, r = h_prev / h, D = the (extrapolated) data prediction.
+# --------------------------------------------------------------------------
+
+
+def flow_alpha(sigma):
+    return 1.0 - np.asarray(sigma, F64)
+
+
+def flow_lambda(sigma):
+    """Half log-SNR of the rectified-flow path; +inf at sigma = 0, -inf at sigma = 1."""
+    sigma = np.asarray(sigma, F64)
+    with np.errstate(divide="ignore"):
+        return np.log(flow_alpha(sigma)) - np.log(sigma)
+
+
+def velocity_to_x0(x, v, sigma):
+    """The models predict the velocity v = eps - x0 of the path, so x0 = x - sigma v."""
+    return np.asarray(x, F64) - float(sigma) * np.asarray(v, F64)
+
+
+def cfg_combine(v_cond, v_uncond, guidance):
+    """Classifier-free guidance: v = v_uncond + g (v_cond - v_uncond)."""
+    v_cond = np.asarray(v_cond, F64)
+    v_uncond = np.asarray(v_uncond, F64)
+    return v_uncond + float(guidance) * (v_cond - v_uncond)
+
+
+def dpmpp_update(x_s, D, sigma_s, sigma_t):
+    """x_t = (sigma_t / sigma_s) x_s - alpha_t (exp(-h) - 1) D: the exact solution of the
+    diffusion ODE from s to t when the data prediction is the constant D."""
+    with np.errstate(invalid="ignore"):
+        h = flow_lambda(sigma_t) - flow_lambda(sigma_s)
+    h = np.inf if np.isnan(h) else h          # sigma_s = 1 and sigma_t = 0 at once: one step over the whole path
+    return (sigma_t / sigma_s) * np.asarray(x_s, F64) - flow_alpha(sigma_t) * np.expm1(-h) * np.asarray(D, F64)
+
+
+def dpmpp_first_order(x_s, x0_s, sigma_s, sigma_t):
+    return dpmpp_update(x_s, x0_s, sigma_s, sigma_t)
+
+
+def dpmpp_2m(x_s, x0_s, x0_prev, sigma_prev, sigma_s, sigma_t):
+    """Second-order multistep update: D = x0_s + (x0_s - x0_prev) / (2 r), r = h_prev / h, the
+    linear extrapolation in lambda of the last two data predictions to the middle of the step."""
+    lam_prev, lam_s, lam_t = flow_lambda(sigma_prev), flow_lambda(sigma_s), flow_lambda(sigma_t)
+    h = lam_t - lam_s
+    h_prev = lam_s - lam_prev
+    r = h_prev / h
+    x0_s = np.asarray(x0_s, F64)
+    D = x0_s + (x0_s - np.asarray(x0_prev, F64)) / (2.0 * r)
+    return dpmpp_update(x_s, D, sigma_s, sigma_t)
+
+
+def model_velocity(latent, idx, blocks, gw, shape, text_ctx, t_mod, t_head, key_scale=None, gamma_o=1.0):
+    """The model's velocity prediction on the tokens idx: patch embedding, every block, head."""
+    toks = patchify(np.asarray(latent, F64), shape.patch)
+    x = patch_embed(gather_rows(toks, idx), gw)
+    for w in blocks:
+        x = dit_block(x, w, shape, text_ctx, t_mod, token_idx=idx, key_scale=key_scale, gamma_o=gamma_o)
+    return head(x, gw, t_head)
+
+
+def denoise_step_dpmpp(latent, blocks, gw, shape, text_ctx, t_mod, t_head, sigma_prev, sigma_s, sigma_t,
+                       x0_prev, hist, order=2, text_ctx_uncond=None, guidance=1.0,
+                       mask_see=None, mask_edit=None, SL=None, key_scale=None, gamma_o=1.0):
+    """One computed step with the DPM-Solver++ update in place of the Euler one.
+
+    x0_prev is latent-shaped and holds the previous step's data prediction where hist (one
+    flag per token) is set. A token takes the second-order update when order >= 2, it has
+    history, and the step does not end at sigma = 0 (there h is infinite and only the
+    first-order form is defined); otherwise the first-order one. With text_ctx_uncond the model
+    runs twice and the velocities are combined by classifier-free guidance; TGAA belongs to the
+    conditional branch only (an unconditional prompt has no differential tokens).
+    Returns (latent, x0 history, history flags) after the step.
+    """
+    lat = np.asarray(latent, F64)
+    patch = shape.patch
+    idx = np.arange(shape.L) if mask_see is None else region_compact(mask_see)
+    v = model_velocity(lat, idx, blocks, gw, shape, text_ctx, t_mod, t_head, key_scale=key_scale, gamma_o=gamma_o)
+    if text_ctx_uncond is not None:
+        v_u = model_velocity(lat, idx, blocks, gw, shape, text_ctx_uncond, t_mod, t_head)
+        v = cfg_combine(v, v_u, guidance)
+    toks = patchify(lat, patch)
+    x_s = gather_rows(toks, idx)
+    x0 = velocity_to_x0(x_s, v, sigma_s)
+    new = dpmpp_first_order(x_s, x0, sigma_s, sigma_t)
+    if order >= 2 and sigma_t > 0.0:
+        x0_old = gather_rows(patchify(np.asarray(x0_prev, F64), patch), idx)
+        second = dpmpp_2m(x_s, x0, x0_old, sigma_prev, sigma_s, sigma_t)
+        use = np.asarray(hist).reshape(-1)[idx] != 0
+        new = np.where(use[:, None], second, new)
+    out = unpatchify(scatter_rows(toks, new, idx), lat.shape, patch)
+    if mask_edit is not None:
+        out = region_blend(out, np.asarray(SL, F64), mask_edit, shape.grid, patch)
+    x0_hist = unpatchify(scatter_rows(patchify(np.asarray(x0_prev, F64), patch), x0, idx), lat.shape, patch)
+    hist_new = np.zeros(shape.L, np.uint8)
+    hist_new[idx] = 1
+    return out, x0_hist, hist_new
+
+
+def run_schedule_dpmpp(plan, sigmas, latent0, SL, blocks, gw, shape, text_ctx, t_mods, t_heads, order=2,
+                       text_ctx_uncond=None, guidance=1.0, mask_see=None, mask_edit=None, key_scale_of=None):
+    """The three-stage loop with the multistep solver. History starts empty at the first
+    computed step; a token skipped by a step (outside M_see in stage 2) has none in the next."""
+    lat = np.asarray(latent0, F64)
+    x0_prev = np.zeros_like(lat)
+    hist = np.zeros(shape.L, np.uint8)
+    for i, (stage, gk, go) in enumerate(plan):
+        if stage == 1:
+            lat = np.asarray(SL, F64).copy()
+            continue
+        ks = key_scale_of(gk) if key_scale_of is not None else None
+        s_prev = sigmas[i - 1] if i > 0 else sigmas[i]
+        kw = dict(order=order, text_ctx_uncond=text_ctx_uncond, guidance=guidance, key_scale=ks, gamma_o=go)
+        if stage == 2:
+            kw.update(mask_see=mask_see, mask_edit=mask_edit, SL=SL)
+        lat, x0_prev, hist = denoise_step_dpmpp(lat, blocks, gw, shape, text_ctx, t_mods[i], t_heads[i], s_prev,
+                                                sigmas[i], sigmas[i + 1], x0_prev, hist, **kw)
     return lat

@@ -636,3 +636,165 @@ def test_run_schedule_snapshot_is_the_prefix_run():
     assert not np.array_equal(full, snap)
     _, last = O.run_schedule(plan, sig, lat0, None, blocks, gw, bs, ctx, t_mods, t_heads, store_after=4)
     np.testing.assert_array_equal(last, full)
+
+
+# ------------------------------------------------------------------ sampler: DPM-Solver++ on the rectified-flow path (Sec. 4.1)
+
+def _gauss_x0(x, sig, mu, s):
+    """E[x0 | x_sigma] for data ~ N(mu, s^2) on the path x = (1 - sigma) x0 + sigma eps."""
+    a = 1.0 - sig
+    return mu + a * s * s / (a * a * s * s + sig * sig) * (x - a * mu)
+
+
+def _gauss_flow_exact(x_a, sig_a, sig_b, mu, s):
+    """The probability-flow ODE keeps (x - alpha mu) / std(x_sigma) fixed for Gaussian data."""
+    f = lambda sg: math.sqrt((1.0 - sg) ** 2 * s * s + sg * sg)
+    return (1.0 - sig_b) * mu + f(sig_b) * (x_a - (1.0 - sig_a) * mu) / f(sig_a)
+
+
+def _solve_gauss(n, order, grid="sigma"):
+    mu, s = 0.7, 0.5
+    if grid == "sigma":
+        sig = np.linspace(0.9, 0.1, n + 1)          # uniform in sigma: h changes from step to step, r != 1
+    else:
+        u = np.linspace(0.0, 1.0, n + 1) ** 1.5
+        sig = 0.9 - 0.8 * u
+    x = np.array([1.3, -0.4, 0.05])
+    start, prev = x.copy(), None
+    for i in range(n):
+        x0 = _gauss_x0(x, sig[i], mu, s)
+        if order == 2 and prev is not None:
+            x = O.dpmpp_2m(x, x0, prev, sig[i - 1], sig[i], sig[i + 1])
+        else:
+            x = O.dpmpp_first_order(x, x0, sig[i], sig[i + 1])
+        prev = x0
+    return np.abs(x - _gauss_flow_exact(start, 0.9, 0.1, mu, s)).max()
+
+
+@pytest.mark.parametrize("grid", ["sigma", "warped"])
+def test_dpmpp_convergence_order_on_gaussian_flow(grid):
+    """Against the closed-form flow of Gaussian data: halving the step halves the error of the
+    first-order update and quarters that of the multistep one. A wrong sign or a wrong r in the
+    extrapolation term leaves only first-order convergence."""
+    e1 = [_solve_gauss(n, 1, grid) for n in (64, 128, 256)]
+    e2 = [_solve_gauss(n, 2, grid) for n in (64, 128, 256)]
+    for a, b in zip(e1, e1[1:]):
+        assert 1.8 < a / b < 2.2
+    for a, b in zip(e2, e2[1:]):
+        assert 3.6 < a / b < 4.4
+    assert e2[-1] < 0.02 * e1[-1]
+
+
+def test_dpmpp_closed_forms():
+    rng = synth.stream(3, "dpmpp")
+    x0 = rng.standard_normal(11)
+    eps = rng.standard_normal(11)
+    # constant data prediction: every order lands on the path through (x0, eps) exactly
+    sig = [1.0, 0.83, 0.6, 0.41, 0.2, 0.0]
+    x = sig[0] * eps + (1 - sig[0]) * x0
+    for i in range(5):
+        if i == 0 or sig[i + 1] == 0.0:
+            x = O.dpmpp_first_order(x, x0, sig[i], sig[i + 1])
+        else:
+            x = O.dpmpp_2m(x, x0, x0, sig[i - 1], sig[i], sig[i + 1])
+        np.testing.assert_allclose(x, sig[i + 1] * eps + (1 - sig[i + 1]) * x0, rtol=0, atol=1e-14)
+    # first order on the rectified-flow path is the Euler step in the velocity
+    xs = rng.standard_normal(11)
+    v = rng.standard_normal(11)
+    for s_, t_ in ((1.0, 0.7), (0.7, 0.3), (0.3, 0.0), (1.0, 0.0)):
+        got = O.dpmpp_first_order(xs, O.velocity_to_x0(xs, v, s_), s_, t_)
+        np.testing.assert_allclose(got, xs + (t_ - s_) * v, rtol=0, atol=1e-14)
+    # a step that ends at sigma = 0 returns the data prediction itself
+    np.testing.assert_allclose(O.dpmpp_first_order(xs, x0, 0.4, 0.0), x0, rtol=0, atol=1e-15)
+    # equal predictions: nothing to extrapolate; history taken at sigma = 1 (lambda = -inf) has no weight
+    a = O.dpmpp_2m(xs, x0, x0, 0.9, 0.6, 0.3)
+    np.testing.assert_allclose(a, O.dpmpp_first_order(xs, x0, 0.6, 0.3), rtol=0, atol=1e-14)
+    b = O.dpmpp_2m(xs, x0, eps, 1.0, 0.6, 0.3)
+    np.testing.assert_allclose(b, O.dpmpp_first_order(xs, x0, 0.6, 0.3), rtol=0, atol=1e-14)
+    # equal steps in lambda (r = 1): D = 1.5 x0 - 0.5 x0_prev
+    lam = np.array([-1.0, -0.2, 0.6])
+    sg = 1.0 / (1.0 + np.exp(lam))                 # lambda = log((1 - sigma) / sigma)
+    np.testing.assert_allclose(O.flow_lambda(sg), lam, atol=1e-14)
+    c = O.dpmpp_2m(xs, x0, eps, sg[0], sg[1], sg[2])
+    np.testing.assert_allclose(c, O.dpmpp_update(xs, 1.5 * x0 - 0.5 * eps, sg[1], sg[2]), rtol=0, atol=1e-13)
+    # the velocity of the path is eps - x0
+    xt = 0.35 * eps + 0.65 * x0
+    np.testing.assert_allclose(O.velocity_to_x0(xt, eps - x0, 0.35), x0, atol=1e-14)
+
+
+def test_cfg_combine_ends():
+    rng = synth.stream(4, "cfg")
+    vc, vu = rng.standard_normal(9), rng.standard_normal(9)
+    np.testing.assert_array_equal(O.cfg_combine(vc, vu, 0.0), vu)
+    np.testing.assert_allclose(O.cfg_combine(vc, vu, 1.0), vc, atol=1e-15)
+    np.testing.assert_allclose(O.cfg_combine(vc, vu, 5.0) - vc, 4.0 * (vc - vu), atol=1e-14)
+    np.testing.assert_array_equal(O.cfg_combine(vc, vc, 7.5), vc)
+
+
+def test_step_dpmpp_reduces_to_the_euler_step_and_tracks_history():
+    bs, blocks, gw, ctx, t_mods, t_heads = _tiny_model()
+    lat = synth.latent(bs, 0)
+    SL = synth.latent(bs, 0, "SL")
+    junk = synth.latent(bs, 0, "x0prev")
+    none = np.zeros(bs.L, np.uint8)
+    ones = np.ones(bs.L, np.uint8)
+    euler = O.denoise_step(lat, blocks, gw, bs, ctx, t_mods[0], t_heads[0], 0.5 - 0.75)
+    for order, hist in ((1, ones), (2, none)):          # first order asked for, or no history to use
+        out, x0h, h = O.denoise_step_dpmpp(lat, blocks, gw, bs, ctx, t_mods[0], t_heads[0], 1.0, 0.75, 0.5, junk, hist,
+                                           order=order)
+        np.testing.assert_allclose(out, euler, rtol=0, atol=1e-12)
+        assert h.all()
+        v = O.model_velocity(lat, np.arange(bs.L), blocks, gw, bs, ctx, t_mods[0], t_heads[0])
+        np.testing.assert_allclose(x0h, lat - 0.75 * O.unpatchify(v, lat.shape, bs.patch), rtol=0, atol=1e-12)
+    # with history the second-order term moves the result, and only on tokens that have it
+    part = synth.exact_count_mask(bs.L, 5, seed=2)
+    out2, _, _ = O.denoise_step_dpmpp(lat, blocks, gw, bs, ctx, t_mods[0], t_heads[0], 1.0 - 1e-3, 0.75, 0.5, junk, part)
+    tok_changed = np.abs(O.patchify(out2 - euler, bs.patch)).max(axis=1) > 1e-9
+    np.testing.assert_array_equal(tok_changed, part != 0)
+    # the last step (sigma -> 0) is first order whatever the history
+    last, _, _ = O.denoise_step_dpmpp(lat, blocks, gw, bs, ctx, t_mods[0], t_heads[0], 0.5, 0.25, 0.0, junk, ones)
+    np.testing.assert_allclose(last, O.denoise_step(lat, blocks, gw, bs, ctx, t_mods[0], t_heads[0], -0.25), atol=1e-12)
+    # stage 2: computed tokens get history, the others lose it; outside M_edit the latent is the source latent
+    see = synth.exact_count_mask(bs.L, 7, seed=1)
+    edit = see.copy()
+    edit[O.region_compact(see)[:3]] = 0
+    out3, x0h3, h3 = O.denoise_step_dpmpp(lat, blocks, gw, bs, ctx, t_mods[0], t_heads[0], 1.0, 0.75, 0.5, junk, ones,
+                                          mask_see=see, mask_edit=edit, SL=SL)
+    np.testing.assert_array_equal(h3, see)
+    Me = O.expand_token_mask(edit, bs.grid, bs.patch, bs.C).astype(bool)
+    Ms = O.expand_token_mask(see, bs.grid, bs.patch, bs.C).astype(bool)
+    np.testing.assert_array_equal(out3[~Me], SL.astype(np.float64)[~Me])
+    np.testing.assert_array_equal(x0h3[~Ms], junk.astype(np.float64)[~Ms])
+    assert (x0h3[Ms] != junk.astype(np.float64)[Ms]).all()
+    # guidance 1 with any unconditional prompt is the conditional step; equal prompts cancel the guidance scale
+    ctx_u = O.text_project(synth.normal(5, "text_uncond", (bs.Lt, bs.text_dim)), gw)
+    g1, _, _ = O.denoise_step_dpmpp(lat, blocks, gw, bs, ctx, t_mods[0], t_heads[0], 1.0, 0.75, 0.5, junk, none,
+                                    text_ctx_uncond=ctx_u, guidance=1.0)
+    np.testing.assert_allclose(g1, euler, rtol=0, atol=1e-12)
+    g5, _, _ = O.denoise_step_dpmpp(lat, blocks, gw, bs, ctx, t_mods[0], t_heads[0], 1.0, 0.75, 0.5, junk, none,
+                                    text_ctx_uncond=ctx, guidance=5.0)
+    np.testing.assert_allclose(g5, euler, rtol=0, atol=1e-12)
+    g3, _, _ = O.denoise_step_dpmpp(lat, blocks, gw, bs, ctx, t_mods[0], t_heads[0], 1.0, 0.75, 0.5, junk, none,
+                                    text_ctx_uncond=ctx_u, guidance=3.0)
+    gu, _, _ = O.denoise_step_dpmpp(lat, blocks, gw, bs, ctx_u, t_mods[0], t_heads[0], 1.0, 0.75, 0.5, junk, none)
+    np.testing.assert_allclose(g3, gu + 3.0 * (euler - gu), rtol=0, atol=1e-11)    # the update is linear in v
+
+
+def test_run_schedule_dpmpp_first_order_is_the_euler_run():
+    bs, blocks, gw, ctx, t_mods, t_heads = _tiny_model()
+    lat = synth.latent(bs, 0)
+    SL = synth.latent(bs, 0, "SL")
+    sig = [1.0, 0.8, 0.55, 0.3, 0.0]
+    see = synth.exact_count_mask(bs.L, 7, seed=1)
+    edit = see.copy()
+    edit[O.region_compact(see)[:2]] = 0
+    plan = [(1, 1.0, 1.0), (2, 1.2, 1.1), (3, 1.1, 1.0), (3, 1.0, 1.0)]
+    ks = lambda g: synth.tdiff_scale(bs.Lt, g, seed=0)
+    a = O.run_schedule(plan, sig, lat, SL, blocks, gw, bs, ctx, t_mods, t_heads, mask_see=see, mask_edit=edit,
+                       key_scale_of=ks)
+    b = O.run_schedule_dpmpp(plan, sig, lat, SL, blocks, gw, bs, ctx, t_mods, t_heads, order=1, mask_see=see,
+                             mask_edit=edit, key_scale_of=ks)
+    np.testing.assert_allclose(a, b, rtol=0, atol=1e-11)
+    c = O.run_schedule_dpmpp(plan, sig, lat, SL, blocks, gw, bs, ctx, t_mods, t_heads, order=2, mask_see=see,
+                             mask_edit=edit, key_scale_of=ks)
+    assert np.abs(c - a).max() > 1e-6          # step 2 (stage 3, after a stage-2 step) extrapolates on the M_see tokens
