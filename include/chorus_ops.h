@@ -104,6 +104,53 @@ int32_t chorus_head_update(float* latent, const float* x, int64_t Ls, const int3
                            const chorus_glue_weights* gw, const float* t_head, float dsigma, int32_t D, int32_t C,
                            int32_t T, int32_t Hl, int32_t Wl, int32_t ph, int32_t pw, void* ws, size_t ws_bytes,
                            void* stream);
+/* ------------------------------------------------------------------------
+ * The sampler (Sec. 4.1: the DPM++ solver with default settings; the paper gives no
+ * formulas): DPM-Solver++ in data-prediction form, multistep, order <= 2, on the
+ * rectified-flow path x_sigma = alpha x0 + sigma eps, alpha = 1 - sigma, whose velocity
+ * v = eps - x0 the model predicts. With lambda = log(alpha / sigma), h = lambda_t - lambda_s,
+ * r = h_prev / h, one step from sigma_s to sigma_t is
+ *     x0 = x_s - sigma_s v
+ *     D  = x0                                   (first order, or no history)
+ *        = (1 + 1/(2r)) x0 - (1/(2r)) x0_prev   (second order)
+ *     x_t = (sigma_t / sigma_s) x_s - alpha_t (exp(-h) - 1) D
+ * chorus_head_update (above) is the first-order step in its Euler form x_s + (sigma_t - sigma_s) v.
+ *
+ * chorus_sampler_coefficients (host-only): the weights of step i of a schedule.
+ *   sigmas host [n_steps + 1], strictly decreasing, sigmas[0] <= 1, sigmas[n_steps] >= 0
+ *   order 1 or 2. Step 0 (no earlier level), a step that ends at sigma = 0 (h is infinite)
+ *   and a previous level of exactly 1 (lambda = -inf) give first-order weights.
+ *   Errors: CHORUS_E_ARG (null pointer, i outside [0, n_steps), order, levels out of order).
+ *
+ * chorus_head_update_solver: head + sampler step on the selected tokens in one pass over them:
+ *   v = head(x), or head(x_uncond) + guidance (head(x) - head(x_uncond)) when x_uncond is
+ *   given (classifier-free guidance; x, x_uncond dev [Ls, D] fp32);
+ *   x0_prev dev [C, T, Hl, Wl] fp32: read where the second-order form applies, then
+ *     overwritten with this step's x0 on every selected token (NULL: keep no history;
+ *     needs coef->c1 == 0);
+ *   hist dev [T*Hg*Wg] uint8 or NULL: tokens whose x0_prev entry is valid (NULL = all);
+ *     the others take the first-order form;
+ *   SL, mask_edit (both or neither): Eq. 6 on the selected tokens -- a selected token
+ *     with mask_edit = 0 receives SL instead of the update. Tokens that are not selected
+ *     are not touched.
+ *   latent, x0_prev and SL must not overlap. Workspace: chorus_head_solver_workspace_bytes.
+ * ------------------------------------------------------------------------ */
+typedef struct {
+  float sigma_s; /* noise level of the step's input */
+  float rho;     /* sigma_t / sigma_s */
+  float A;       /* -alpha_t (exp(-h) - 1) = alpha_t - sigma_t alpha_s / sigma_s */
+  float c0, c1;  /* D = c0 x0 + c1 x0_prev on tokens with history; (1, 0): first order */
+} chorus_sampler_coef;
+
+int32_t chorus_sampler_coefficients(const float* sigmas, int32_t n_steps, int32_t i, int32_t order,
+                                    chorus_sampler_coef* out);
+size_t chorus_head_solver_workspace_bytes(int32_t D, int32_t P, int64_t Ls, int32_t cfg);
+int32_t chorus_head_update_solver(float* latent, const float* x, const float* x_uncond, float guidance, int64_t Ls,
+                                  const int32_t* token_idx, const chorus_glue_weights* gw, const float* t_head,
+                                  const chorus_sampler_coef* coef, float* x0_prev, const uint8_t* hist, const float* SL,
+                                  const uint8_t* mask_edit, int32_t D, int32_t C, int32_t T, int32_t Hl, int32_t Wl,
+                                  int32_t ph, int32_t pw, void* ws, size_t ws_bytes, void* stream);
+
 size_t chorus_text_project_workspace_bytes(int32_t Lt, int32_t D);
 int32_t chorus_text_project(const uint16_t* text, int32_t Lt, int32_t text_dim, int32_t D, const uint16_t* w1,
                             const float* b1, const uint16_t* w2, const float* b2, uint16_t* ctx, void* ws,
@@ -149,6 +196,30 @@ int32_t chorus_denoise_step_kv(const chorus_model_shape* model, const chorus_blo
                                const float* tgaa_key_scale, float gamma_o, float dsigma, const float* SL,
                                const uint8_t* mask_edit, void* ws, size_t ws_bytes, void* stream);
 
+/* One computed step with the multistep solver and, optionally, classifier-free guidance:
+ *   x = patch_embed(latent[token_idx]); x_c = blocks(x; text_kv, TGAA);
+ *   x_u = blocks(x; text_kv_uncond, no TGAA) when text_kv_uncond is given;
+ *   chorus_head_update_solver(latent, x_c, x_u, ...) with Eq. 6 folded into its pass.
+ * TGAA (key scale, gamma_o) belongs to the conditional branch only: an unconditional
+ * prompt has no differential tokens.
+ *   text_kv, text_kv_uncond: from chorus_model_text_kv_project
+ *   coef: chorus_sampler_coefficients of this step (host struct, copied at the call)
+ *   x0_prev, hist: as in chorus_head_update_solver
+ *   SL, mask_edit (both or neither): stage 2. Eq. 6 also resets the tokens outside
+ *     token_idx to SL; outside_is_source != 0 states that they already hold SL (true after
+ *     the stage-1 copy and after any earlier stage-2 step with the same SL), and then no
+ *     extra pass over the latent is made; with 0, chorus_region_blend runs afterwards.
+ * Workspace: chorus_denoise_step_solver_workspace_bytes(model, Ls, cfg) with cfg != 0 iff
+ * text_kv_uncond is given. Errors as chorus_denoise_step. */
+size_t chorus_denoise_step_solver_workspace_bytes(const chorus_model_shape* model, int64_t Ls, int32_t cfg);
+int32_t chorus_denoise_step_solver(const chorus_model_shape* model, const chorus_block_weights* blocks,
+                                   const chorus_glue_weights* gw, float* latent, const int32_t* token_idx, int64_t Ls,
+                                   const void* text_kv, const void* text_kv_uncond, float guidance, const float* t_mod,
+                                   const float* t_head, const float* tgaa_key_scale, float gamma_o,
+                                   const chorus_sampler_coef* coef, float* x0_prev, const uint8_t* hist, const float* SL,
+                                   const uint8_t* mask_edit, int32_t outside_is_source, void* ws, size_t ws_bytes,
+                                   void* stream);
+
 /* ------------------------------------------------------------------------
  * The whole three-stage request (Sec. 3.1) on one stream:
  *   1. top-1 cosine lookup of `query` in the cache; the score m is read back
@@ -165,6 +236,12 @@ int32_t chorus_denoise_step_kv(const chorus_model_shape* model, const chorus_blo
  * store_after steps (1 <= store_after <= n_steps; the intermediate state a later hit with
  * K1 = store_after resumes from) are written to entry store_slot with chorus_cache_insert.
  * One cached latent per entry serves both the stage-1 copy and the stage-2 fusion.
+ * Sampler: solver_order 0 or 1 with text_ctx_uncond NULL takes the Euler form of the first-order
+ * step (chorus_denoise_step); solver_order 2 and / or text_ctx_uncond (classifier-free guidance
+ * with scale `guidance`, two model evaluations per step) take chorus_denoise_step_solver. The
+ * history of data predictions starts empty at the first computed step; a token that a step did
+ * not compute (outside M_see in stage 2) has none in the next, so the first stage-3 step after
+ * stage 2 is second-order on the M_see tokens and first-order elsewhere.
  * Two host synchronisations: after the lookup and after the compaction count.
  *   cache_emb dev [N, d]; cache_latents dev [N, C, T, Hl, Wl] fp32; query dev [d]
  *   sigmas host [n_steps + 1]; t_mods dev [n_steps, 6, D]; t_heads dev [n_steps, 2, D]
@@ -193,6 +270,9 @@ typedef struct {
   const uint8_t* mask_edit;
   int64_t store_slot;    /* -1: no cache update */
   int32_t store_after;
+  int32_t solver_order;             /* 0, 1: first order; 2: DPM-Solver++ multistep */
+  const uint16_t* text_ctx_uncond;  /* dev [Lt, D] bf16 or NULL: classifier-free guidance */
+  float guidance;
 } chorus_request;
 
 typedef struct {

@@ -590,10 +590,10 @@ def denoise_step_dpmpp(latent, blocks, gw, shape, text_ctx, t_mod, t_head, sigma
     x_s = gather_rows(toks, idx)
     x0 = velocity_to_x0(x_s, v, sigma_s)
     new = dpmpp_first_order(x_s, x0, sigma_s, sigma_t)
-    if order >= 2 and sigma_t > 0.0:
+    use = np.asarray(hist).reshape(-1)[idx] != 0
+    if order >= 2 and sigma_t > 0.0 and use.any():
         x0_old = gather_rows(patchify(np.asarray(x0_prev, F64), patch), idx)
         second = dpmpp_2m(x_s, x0, x0_old, sigma_prev, sigma_s, sigma_t)
-        use = np.asarray(hist).reshape(-1)[idx] != 0
         new = np.where(use[:, None], second, new)
     out = unpatchify(scatter_rows(toks, new, idx), lat.shape, patch)
     if mask_edit is not None:

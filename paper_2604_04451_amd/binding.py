@@ -66,7 +66,12 @@ class Request(C.Structure):
                 ("sched", C.POINTER(SchedParams)), ("n_steps", C.c_int32), ("sigmas", C.POINTER(C.c_float)),
                 ("t_mods", C.c_void_p), ("t_heads", C.c_void_p), ("text_ctx", C.c_void_p), ("tdiff", C.c_void_p),
                 ("mask_see", C.c_void_p), ("mask_edit", C.c_void_p), ("store_slot", C.c_int64),
-                ("store_after", C.c_int32)]
+                ("store_after", C.c_int32), ("solver_order", C.c_int32), ("text_ctx_uncond", C.c_void_p),
+                ("guidance", C.c_float)]
+
+
+class SamplerCoef(C.Structure):
+    _fields_ = [(n, C.c_float) for n in ("sigma_s", "rho", "A", "c0", "c1")]
 
 
 class RunResult(C.Structure):
@@ -147,6 +152,13 @@ def _bind_ops(lib):
         "chorus_model_text_kv_project": (i32, [MS, C.POINTER(BlockWeights), vp, vp, vp, sz, vp]),
         "chorus_denoise_step_kv": (i32, [MS, C.POINTER(BlockWeights), GW, vp, vp, i64, vp, vp, vp, vp, f32, f32, vp, vp, vp,
                                          sz, vp]),
+        "chorus_sampler_coefficients": (i32, [C.POINTER(f32), i32, i32, i32, C.POINTER(SamplerCoef)]),
+        "chorus_head_solver_workspace_bytes": (sz, [i32, i32, i64, i32]),
+        "chorus_head_update_solver": (i32, [vp, vp, vp, f32, i64, vp, GW, vp, C.POINTER(SamplerCoef), vp, vp, vp, vp, i32,
+                                            i32, i32, i32, i32, i32, i32, vp, sz, vp]),
+        "chorus_denoise_step_solver_workspace_bytes": (sz, [MS, i64, i32]),
+        "chorus_denoise_step_solver": (i32, [MS, C.POINTER(BlockWeights), GW, vp, vp, i64, vp, vp, f32, vp, vp, vp, f32,
+                                             C.POINTER(SamplerCoef), vp, vp, vp, vp, i32, vp, sz, vp]),
         "chorus_mask_pooled_extent": (i32, [i32, i32, i32]),
         "chorus_mask_project": (i32, [vp, i32, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]),
         "chorus_mask_hierarchy": (i32, [vp, i32, i32, i32, C.POINTER(i32), C.POINTER(i32), vp, vp, vp]),
@@ -546,6 +558,41 @@ def chorus_head_update(latent, x, Ls, token_idx, glue: DeviceGlue, t_head, dsigm
     return latent
 
 
+def chorus_sampler_coefficients(sigmas, i, order=2) -> SamplerCoef:
+    """Weights of step i (sigmas[i] -> sigmas[i + 1]) of the DPM-Solver++ update; host arithmetic in the library."""
+    n_steps = len(sigmas) - 1
+    sig = (C.c_float * (n_steps + 1))(*[float(v) for v in sigmas])
+    out = SamplerCoef()
+    _status("chorus_sampler_coefficients", load().chorus_sampler_coefficients(sig, n_steps, int(i), int(order),
+                                                                              C.byref(out)))
+    return out
+
+
+def chorus_head_update_solver(latent, x, Ls, token_idx, glue: DeviceGlue, t_head, coef: SamplerCoef, x0_prev=None,
+                              hist=None, x_uncond=None, guidance=1.0, SL=None, mask_edit=None, patch_hw=(2, 2), ws=None):
+    lib = load()
+    _chk(latent, torch.float32, "latent")
+    _chk(x, torch.float32, "x")
+    _chk(x_uncond, torch.float32, "x_uncond", x.shape)
+    _chk(token_idx, torch.int32, "token_idx")
+    D = x.shape[1]
+    _chk(t_head, torch.float32, "t_head", (2, D))
+    _chk(x0_prev, torch.float32, "x0_prev", latent.shape)
+    _chk(SL, torch.float32, "SL", latent.shape)
+    _chk(hist, torch.uint8, "hist")
+    _chk(mask_edit, torch.uint8, "mask_edit")
+    Cc, T, Hl, Wl = latent.shape
+    P = Cc * patch_hw[0] * patch_hw[1]
+    if ws is None:
+        ws = _ws(lib.chorus_head_solver_workspace_bytes(D, P, Ls, int(x_uncond is not None)), latent.device)
+    _status("chorus_head_update_solver",
+            lib.chorus_head_update_solver(_p(latent), _p(x), _p(x_uncond), float(guidance), Ls, _p(token_idx),
+                                          C.byref(glue.cstruct), _p(t_head), C.byref(coef), _p(x0_prev), _p(hist), _p(SL),
+                                          _p(mask_edit), D, Cc, T, Hl, Wl, patch_hw[0], patch_hw[1], _p(ws), ws.numel(),
+                                          _stream()))
+    return latent
+
+
 def block_array(blocks):
     """Host array of chorus_block_weights structs from a list of DeviceBlock."""
     arr = (BlockWeights * max(len(blocks), 1))()
@@ -615,6 +662,40 @@ def chorus_denoise_step_kv(model: ModelShape, blocks_arr, glue: DeviceGlue, late
     return latent
 
 
+def chorus_denoise_step_solver(model: ModelShape, blocks_arr, glue: DeviceGlue, latent, token_idx, Ls, text_kv, t_mod,
+                               t_head, coef: SamplerCoef, x0_prev=None, hist=None, text_kv_uncond=None, guidance=1.0,
+                               tgaa_key_scale=None, gamma_o=1.0, SL=None, mask_edit=None, outside_is_source=False,
+                               ws=None):
+    lib = load()
+    D = model.block.D
+    _chk(latent, torch.float32, "latent", (model.C, model.T, model.Hl, model.Wl))
+    _chk(SL, torch.float32, "SL", latent.shape)
+    _chk(x0_prev, torch.float32, "x0_prev", latent.shape)
+    _chk(token_idx, torch.int32, "token_idx")
+    _chk(text_kv, torch.uint8, "text_kv")
+    _chk(text_kv_uncond, torch.uint8, "text_kv_uncond")
+    _chk(t_mod, torch.float32, "t_mod", (6, D))
+    _chk(t_head, torch.float32, "t_head", (2, D))
+    _chk(tgaa_key_scale, torch.float32, "tgaa_key_scale", (model.block.Lt,))
+    Ltok = model.T * (model.Hl // model.ph) * (model.Wl // model.pw)
+    _chk(mask_edit, torch.uint8, "mask_edit", (Ltok,))
+    _chk(hist, torch.uint8, "hist", (Ltok,))
+    need = lib.chorus_model_text_kv_bytes(C.byref(model))
+    for kv in (text_kv, text_kv_uncond):
+        if kv is not None and kv.numel() < need:
+            raise TypeError("text_kv: too small")
+    cfg = int(text_kv_uncond is not None)
+    if ws is None:
+        ws = _ws(lib.chorus_denoise_step_solver_workspace_bytes(C.byref(model), int(Ls), cfg), latent.device)
+    _status("chorus_denoise_step_solver",
+            lib.chorus_denoise_step_solver(C.byref(model), blocks_arr, C.byref(glue.cstruct), _p(latent), _p(token_idx),
+                                           int(Ls), _p(text_kv), _p(text_kv_uncond), float(guidance), _p(t_mod),
+                                           _p(t_head), _p(tgaa_key_scale), float(gamma_o), C.byref(coef), _p(x0_prev),
+                                           _p(hist), _p(SL), _p(mask_edit), int(bool(outside_is_source)), _p(ws),
+                                           ws.numel(), _stream()))
+    return latent
+
+
 def chorus_stage1_copy(latent, SL):
     _chk(latent, torch.float32, "latent")
     _chk(SL, torch.float32, "SL", latent.shape)
@@ -666,9 +747,10 @@ def chorus_denoise_run_workspace_bytes(model: ModelShape, N: int) -> int:
 
 def chorus_denoise_run(model: ModelShape, blocks_arr, glue: DeviceGlue, latent, cache_emb, cache_latents, query, tau,
                        sigmas, t_mods, t_heads, text_ctx, tdiff=None, mask_see=None, mask_edit=None, sched=None,
-                       ws=None, store_slot=-1, store_after=0):
+                       ws=None, store_slot=-1, store_after=0, solver_order=1, text_ctx_uncond=None, guidance=1.0):
     """Runs one request; returns a dict with the lookup result, K1, K2 and the stage-2 token count.
-    store_slot >= 0: on a miss, the query and the latent after store_after steps go into that cache entry."""
+    store_slot >= 0: on a miss, the query and the latent after store_after steps go into that cache entry.
+    solver_order 2: DPM-Solver++ multistep update; text_ctx_uncond: classifier-free guidance with scale guidance."""
     lib = load()
     D = model.block.D
     n_steps = len(sigmas) - 1
@@ -680,6 +762,7 @@ def chorus_denoise_run(model: ModelShape, blocks_arr, glue: DeviceGlue, latent, 
     _chk(t_mods, torch.float32, "t_mods", (n_steps, 6, D))
     _chk(t_heads, torch.float32, "t_heads", (n_steps, 2, D))
     _chk(text_ctx, torch.bfloat16, "text_ctx", (model.block.Lt, D))
+    _chk(text_ctx_uncond, torch.bfloat16, "text_ctx_uncond", (model.block.Lt, D))
     _chk(tdiff, torch.uint8, "tdiff", (model.block.Lt,))
     Ltok = model.T * (model.Hl // model.ph) * (model.Wl // model.pw)
     _chk(mask_see, torch.uint8, "mask_see", (Ltok,))
@@ -694,7 +777,8 @@ def chorus_denoise_run(model: ModelShape, blocks_arr, glue: DeviceGlue, latent, 
                  float(tau), C.pointer(sp) if sp is not None else None, n_steps, sig, t_mods.data_ptr(),
                  t_heads.data_ptr(), text_ctx.data_ptr(), 0 if tdiff is None else tdiff.data_ptr(),
                  0 if mask_see is None else mask_see.data_ptr(), 0 if mask_edit is None else mask_edit.data_ptr(),
-                 int(store_slot), int(store_after))
+                 int(store_slot), int(store_after), int(solver_order),
+                 0 if text_ctx_uncond is None else text_ctx_uncond.data_ptr(), float(guidance))
     if ws is None:
         ws = _ws(lib.chorus_denoise_run_workspace_bytes(C.byref(model), N), latent.device)
     res = RunResult()

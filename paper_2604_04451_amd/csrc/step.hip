@@ -98,7 +98,103 @@ int32_t denoise_step_impl(const chorus_model_shape* model, const chorus_block_we
 }
 }  // namespace
 
+namespace {
+struct SolverWs {
+  float* x;
+  float* xu;
+  void* glue;
+  size_t glue_bytes;
+  void* block;
+  size_t block_bytes;
+  size_t bytes;
+};
+
+SolverWs carve_solver(const chorus_model_shape& m, long Ls, int cfg, void* base) {
+  SolverWs w;
+  uint8_t* p = (uint8_t*)base;
+  size_t off = 0;
+  const long rows = Ls > 0 ? Ls : 1;
+  const int P = m.C * m.ph * m.pw;
+  w.x = (float*)(p + off);
+  off += align_up((size_t)rows * m.block.D * 4, 256);
+  w.xu = nullptr;
+  if (cfg) {
+    w.xu = (float*)(p + off);
+    off += align_up((size_t)rows * m.block.D * 4, 256);
+  }
+  w.glue = p + off;
+  const size_t embed = chorus_glue_workspace_bytes(m.block.D, P, rows);
+  const size_t head = chorus_head_solver_workspace_bytes(m.block.D, P, rows, cfg);
+  w.glue_bytes = embed > head ? embed : head;
+  off += align_up(w.glue_bytes, 256);
+  w.block = p + off;
+  w.block_bytes = chorus_dit_block_workspace_bytes(&m.block, rows);
+  off += align_up(w.block_bytes, 256);
+  w.bytes = off;
+  return w;
+}
+
+int32_t device_copy(float* dst, const float* src, long n, hipStream_t s);
+}  // namespace
+
 extern "C" {
+
+size_t chorus_denoise_step_solver_workspace_bytes(const chorus_model_shape* model, int64_t Ls, int32_t cfg) {
+  if (check_model(model) != CHORUS_OK || Ls < 0) return 0;
+  return carve_solver(*model, Ls, cfg != 0, nullptr).bytes;
+}
+
+int32_t chorus_denoise_step_solver(const chorus_model_shape* model, const chorus_block_weights* blocks,
+                                   const chorus_glue_weights* gw, float* latent, const int32_t* token_idx, int64_t Ls,
+                                   const void* text_kv, const void* text_kv_uncond, float guidance, const float* t_mod,
+                                   const float* t_head, const float* tgaa_key_scale, float gamma_o,
+                                   const chorus_sampler_coef* coef, float* x0_prev, const uint8_t* hist, const float* SL,
+                                   const uint8_t* mask_edit, int32_t outside_is_source, void* ws, size_t ws_bytes,
+                                   void* stream) {
+  int32_t st = check_model(model);
+  if (st != CHORUS_OK) return st;
+  const chorus_model_shape& m = *model;
+  const int64_t Ltok = (int64_t)m.T * (m.Hl / m.ph) * (m.Wl / m.pw);
+  if (Ls < 0 || Ls > Ltok) return CHORUS_E_ARG;
+  if (!token_idx && Ls != Ltok) return CHORUS_E_ARG;
+  if (!latent || !gw || !t_mod || !t_head || !coef || (m.n_blocks > 0 && (!blocks || !text_kv))) return CHORUS_E_ARG;
+  if ((mask_edit != nullptr) != (SL != nullptr)) return CHORUS_E_ARG;
+  if (coef->c1 != 0.f && !x0_prev) return CHORUS_E_ARG;
+  if (!ws) return CHORUS_E_WORKSPACE;
+  const int cfg = text_kv_uncond != nullptr;
+  SolverWs w = carve_solver(m, Ls, cfg, ws);
+  if (ws_bytes < w.bytes) return CHORUS_E_WORKSPACE;
+  if (Ls > 0) {
+    st = chorus_patch_embed(latent, m.C, m.T, m.Hl, m.Wl, m.ph, m.pw, token_idx, Ls, gw, m.block.D, w.x, w.glue,
+                            w.glue_bytes, stream);
+    if (st != CHORUS_OK) return st;
+    if (cfg) {
+      st = device_copy(w.xu, w.x, (long)Ls * m.block.D, (hipStream_t)stream);
+      if (st != CHORUS_OK) return st;
+    }
+    const size_t kv_bytes = chorus_text_kv_bytes(&m.block);
+    for (int b = 0; b < m.n_blocks; ++b) {
+      st = chorus_dit_block_step_kv(&m.block, &blocks[b], w.x, Ls, token_idx,
+                                    (const uint16_t*)((const uint8_t*)text_kv + b * kv_bytes), t_mod, tgaa_key_scale,
+                                    gamma_o, w.block, w.block_bytes, stream);
+      if (st != CHORUS_OK) return st;
+    }
+    for (int b = 0; cfg && b < m.n_blocks; ++b) {
+      st = chorus_dit_block_step_kv(&m.block, &blocks[b], w.xu, Ls, token_idx,
+                                    (const uint16_t*)((const uint8_t*)text_kv_uncond + b * kv_bytes), t_mod, nullptr, 1.f,
+                                    w.block, w.block_bytes, stream);
+      if (st != CHORUS_OK) return st;
+    }
+    st = chorus_head_update_solver(latent, w.x, w.xu, guidance, Ls, token_idx, gw, t_head, coef, x0_prev, hist, SL,
+                                   mask_edit, m.block.D, m.C, m.T, m.Hl, m.Wl, m.ph, m.pw, w.glue, w.glue_bytes, stream);
+    if (st != CHORUS_OK) return st;
+  }
+  if (mask_edit && !outside_is_source) {
+    st = chorus_region_blend(latent, latent, SL, mask_edit, m.C, m.T, m.Hl, m.Wl, m.ph, m.pw, stream);
+    if (st != CHORUS_OK) return st;
+  }
+  return CHORUS_OK;
+}
 
 int32_t chorus_denoise_step(const chorus_model_shape* model, const chorus_block_weights* blocks,
                             const chorus_glue_weights* gw, float* latent, const int32_t* token_idx, int64_t Ls,
@@ -204,6 +300,8 @@ struct RunWs {
   size_t text_kv_bytes;
   void* text_kv_ws;
   size_t text_kv_ws_bytes;
+  void* text_kv_uncond;  // the same for the unconditional prompt of classifier-free guidance
+  float* x0_prev;        // data predictions of the previous step (multistep solver)
   size_t bytes;
 };
 
@@ -226,11 +324,15 @@ RunWs carve_run(const chorus_model_shape& m, int64_t N, void* base) {
   w.compact_ws_bytes = chorus_region_compact_workspace_bytes(Ltok);
   w.compact_ws = take(w.compact_ws_bytes);
   w.step_bytes = chorus_denoise_step_workspace_bytes(&m, Ltok);
+  const size_t solver_bytes = chorus_denoise_step_solver_workspace_bytes(&m, Ltok, 1);
+  if (solver_bytes > w.step_bytes) w.step_bytes = solver_bytes;
   w.step = take(w.step_bytes);
   w.text_kv_bytes = (size_t)m.n_blocks * chorus_text_kv_bytes(&m.block);
   w.text_kv = take(w.text_kv_bytes);
   w.text_kv_ws_bytes = chorus_text_kv_workspace_bytes(&m.block);
   w.text_kv_ws = take(w.text_kv_ws_bytes);
+  w.text_kv_uncond = take(w.text_kv_bytes);
+  w.x0_prev = (float*)take((size_t)m.C * m.T * m.Hl * m.Wl * 4);
   w.bytes = off;
   return w;
 }
@@ -270,8 +372,10 @@ int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_w
   if (!rq->query || (rq->cache_N > 0 && (!rq->cache_emb || !rq->cache_latents))) return CHORUS_E_ARG;
   if (rq->store_slot >= 0 && (rq->store_slot >= rq->cache_N || rq->store_after < 1 || rq->store_after > rq->n_steps))
     return CHORUS_E_ARG;
+  if (rq->solver_order < 0 || rq->solver_order > 2) return CHORUS_E_ARG;
   if (!ws) return CHORUS_E_WORKSPACE;
   const chorus_model_shape& m = *model;
+  const bool use_solver = rq->solver_order == 2 || rq->text_ctx_uncond != nullptr;
   RunWs w = carve_run(m, rq->cache_N, ws);
   if (ws_bytes < w.bytes) return CHORUS_E_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
@@ -316,8 +420,15 @@ int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_w
   if (K1 < rq->n_steps && m.n_blocks > 0) {
     st = chorus_model_text_kv_project(model, blocks, rq->text_ctx, w.text_kv, w.text_kv_ws, w.text_kv_ws_bytes, stream);
     if (st != CHORUS_OK) return st;
+    if (rq->text_ctx_uncond) {
+      st = chorus_model_text_kv_project(model, blocks, rq->text_ctx_uncond, w.text_kv_uncond, w.text_kv_ws,
+                                        w.text_kv_ws_bytes, stream);
+      if (st != CHORUS_OK) return st;
+    }
   }
 
+  // which tokens hold a data prediction from the previous step: 0 none, 1 the M_see tokens, 2 all
+  int history = 0;
   for (int i = 0; i < rq->n_steps; ++i) {
     const chorus_step_plan& p = plan_buf[i];
     if (p.stage == 1) {
@@ -338,7 +449,26 @@ int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_w
     const float dsigma = rq->sigmas[i + 1] - rq->sigmas[i];
     const float* t_mod = rq->t_mods + (size_t)i * 6 * D;
     const float* t_head = rq->t_heads + (size_t)i * 2 * D;
-    if (p.stage == 2) {
+    if (use_solver) {
+      chorus_sampler_coef cf;
+      st = chorus_sampler_coefficients(rq->sigmas, rq->n_steps, i, (history && rq->solver_order == 2) ? 2 : 1, &cf);
+      if (st != CHORUS_OK) return st;
+      const void* kv = m.n_blocks > 0 ? w.text_kv : nullptr;
+      const void* kvu = (m.n_blocks > 0 && rq->text_ctx_uncond) ? w.text_kv_uncond : nullptr;
+      const uint8_t* hist = history == 1 ? rq->mask_see : nullptr;
+      if (p.stage == 2) {
+        // the latent outside M_see already is the source latent once a reused step or an earlier stage-2 step ran
+        st = chorus_denoise_step_solver(model, blocks, gw, latent, w.idx, Ls, kv, kvu, rq->guidance, t_mod, t_head, ks,
+                                        p.gamma_o, &cf, w.x0_prev, hist, SL, rq->mask_edit, i > 0, w.step, w.step_bytes,
+                                        stream);
+        history = 1;
+      } else {
+        st = chorus_denoise_step_solver(model, blocks, gw, latent, nullptr, Ltok, kv, kvu, rq->guidance, t_mod, t_head,
+                                        ks, p.gamma_o, &cf, w.x0_prev, hist, nullptr, nullptr, 0, w.step, w.step_bytes,
+                                        stream);
+        history = 2;
+      }
+    } else if (p.stage == 2) {
       st = denoise_step_impl(model, blocks, gw, latent, w.idx, Ls, rq->text_ctx, m.n_blocks > 0 ? (const uint8_t*)w.text_kv : nullptr,
                              t_mod, t_head, ks, p.gamma_o, dsigma, SL, rq->mask_edit, w.step, w.step_bytes, stream);
     } else {

@@ -127,3 +127,64 @@ def test_cache_insert_validates():
     assert lib.chorus_cache_insert(null, p16, 8, 0, 16, 64, p16, p16, null) == B.E_ARG
     assert lib.chorus_cache_insert(p16, p16, 8, 0, 0, 64, p16, p16, null) == B.E_ARG
     assert lib.chorus_cache_insert(p16, p16, 0, 0, 16, 64, p16, p16, null) == B.E_ARG
+
+
+def _shifted_sigmas(n, shift):
+    """Linear levels from 1 to 0 warped by sigma -> shift sigma / (1 + (shift - 1) sigma), the
+    usual timestep shift of flow-matching video models."""
+    s = np.linspace(1.0, 0.0, n + 1)
+    return shift * s / (1.0 + (shift - 1.0) * s)
+
+
+@pytest.mark.parametrize("n,shift,top", [(4, 3.0, 1.0), (4, 5.0, 0.999), (50, 3.0, 0.999), (8, 1.0, 1.0)])
+def test_sampler_coefficients_reproduce_the_oracle_update(n, shift, top):
+    """The host-side weights of step i, applied as rho x + A (c0 x0 + c1 x0_prev), give the
+    oracle's DPM-Solver++ update for every step of a schedule."""
+    sig = [float(np.float32(v)) for v in top * _shifted_sigmas(n, shift)]
+    rng = np.random.default_rng(0)
+    x, x0, x0p = rng.standard_normal(5), rng.standard_normal(5), rng.standard_normal(5)
+    for i in range(n):
+        for order in (1, 2):
+            cf = B.chorus_sampler_coefficients(sig, i, order)
+            got = cf.rho * x + cf.A * (cf.c0 * x0 + cf.c1 * x0p)
+            if order == 2 and i > 0 and sig[i + 1] > 0:
+                want = O.dpmpp_2m(x, x0, x0p, sig[i - 1], sig[i], sig[i + 1])
+            else:
+                want = O.dpmpp_first_order(x, x0, sig[i], sig[i + 1])
+                assert cf.c0 == 1.0 and cf.c1 == 0.0
+            np.testing.assert_allclose(got, want, rtol=0, atol=2e-6 * (1 + abs(cf.c0) + abs(cf.c1)))
+            assert cf.sigma_s == np.float32(sig[i])
+            assert abs(cf.c0 + cf.c1 - 1.0) < 1e-6      # the extrapolation weights sum to one
+    lib = P.load()
+    out = B.SamplerCoef()
+    arr = lambda v: (C.c_float * len(v))(*v)
+    assert lib.chorus_sampler_coefficients(None, 4, 0, 1, C.byref(out)) == B.E_ARG
+    assert lib.chorus_sampler_coefficients(arr([1, .5, 0]), 2, 2, 1, C.byref(out)) == B.E_ARG      # i out of range
+    assert lib.chorus_sampler_coefficients(arr([1, .5, 0]), 2, 0, 3, C.byref(out)) == B.E_ARG      # order
+    assert lib.chorus_sampler_coefficients(arr([.5, .5, 0]), 2, 0, 1, C.byref(out)) == B.E_ARG     # not decreasing
+    assert lib.chorus_sampler_coefficients(arr([.4, .5, .2]), 2, 1, 2, C.byref(out)) == B.E_ARG    # previous level below
+    assert lib.chorus_sampler_coefficients(arr([1.5, .5, 0]), 2, 0, 1, C.byref(out)) == B.E_ARG    # above 1
+
+
+def test_solver_entry_points_validate():
+    lib = P.load()
+    null, p16 = C.c_void_p(0), C.c_void_p(16)
+    cf = B.SamplerCoef(0.5, 0.5, 0.5, 1.5, -0.5)
+    gw = B.GlueWeights(16, 16, 16, 16, 16)
+    args = lambda **k: [k.get("latent", p16), p16, null, 1.0, k.get("Ls", 4), null, C.byref(gw), p16, C.byref(cf),
+                        k.get("x0_prev", C.c_void_p(32)), null, k.get("SL", null), k.get("mask", null), 64, 16, 1, 4, 4, 2,
+                        2, k.get("ws", p16), k.get("ws_bytes", 1 << 30), null]
+    assert lib.chorus_head_update_solver(*args(x0_prev=null)) == B.E_ARG          # second order without history
+    assert lib.chorus_head_update_solver(*args(SL=C.c_void_p(48))) == B.E_ARG     # SL without mask
+    assert lib.chorus_head_update_solver(*args(x0_prev=p16)) == B.E_ARG           # history aliases the latent
+    assert lib.chorus_head_update_solver(*args(ws=null)) == B.E_WORKSPACE
+    assert lib.chorus_head_update_solver(*args(ws_bytes=8)) == B.E_WORKSPACE
+    assert lib.chorus_head_update_solver(*args(Ls=-1)) == B.E_ARG
+    assert lib.chorus_head_update_solver(*args(Ls=0)) == B.OK
+    assert lib.chorus_head_solver_workspace_bytes(64, 64, 100, 1) > lib.chorus_head_solver_workspace_bytes(64, 64, 100, 0)
+    bs = B.make_block_shape(128, 2, 64, 256, 8, (1, 2, 2))
+    ms = B.make_model_shape(bs, (16, 1, 4, 4), (2, 2), 1)
+    a = lib.chorus_denoise_step_solver_workspace_bytes(C.byref(ms), 4, 0)
+    b = lib.chorus_denoise_step_solver_workspace_bytes(C.byref(ms), 4, 1)
+    assert 0 < a < b
+    assert lib.chorus_denoise_run_workspace_bytes(C.byref(ms), 4) >= b
