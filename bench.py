@@ -193,6 +193,14 @@ def main():
                      "algorithmic_bytes": (30 * 4 * 2.0 * Ls * D + 60 * 4 * 2.0 * L * D) / 90.0,
                      "kernel": "attention_pp_kernel<128,128,false> (self-attention)", "launches": attn_n},
     }
+    # what a bare MFMA loop sustains on this device right now (the part is power-managed: the rate depends on the
+    # operand values and on the LDS reads and exponentials that accompany the MFMAs); context for roofline.frac
+    out["mfma_ceiling_tflops"] = {
+        "ones_registers_only": round(B.chorus_mfma_ceiling(False, 0, 20), 1),
+        "normal_registers_only": round(B.chorus_mfma_ceiling(True, 0, 20), 1),
+        "normal_lds_operand": round(B.chorus_mfma_ceiling(True, 1, 20), 1),
+        "normal_lds_operand_exp2": round(B.chorus_mfma_ceiling(True, 3, 20), 1),
+    }
     if args.plain:
         torch.cuda.synchronize()
         t0 = time.perf_counter()

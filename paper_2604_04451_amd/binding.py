@@ -162,6 +162,8 @@ def _bind_ops(lib):
         "chorus_mask_pooled_extent": (i32, [i32, i32, i32]),
         "chorus_mask_project": (i32, [vp, i32, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]),
         "chorus_mask_hierarchy": (i32, [vp, i32, i32, i32, C.POINTER(i32), C.POINTER(i32), vp, vp, vp]),
+        "chorus_mfma_ceiling_workspace_bytes": (sz, []),
+        "chorus_mfma_ceiling": (i32, [i32, i32, i32, C.POINTER(C.c_double), vp, sz, vp]),
         "chorus_prof_enable": (i32, [i32]),
         "chorus_prof_reset": (i32, []),
         "chorus_prof_read": (i32, [i32, C.POINTER(C.c_double), C.POINTER(i32)]),
@@ -803,3 +805,14 @@ def prof_read(kernel_class):
     ms, n = C.c_double(0), C.c_int32(0)
     _status("chorus_prof_read", load().chorus_prof_read(kernel_class, C.byref(ms), C.byref(n)))
     return ms.value, n.value
+
+
+def chorus_mfma_ceiling(normal_data=True, mix=0, launches=20, device="cuda"):
+    """Sustained TFLOP/s of a bare bf16 MFMA loop on this device (mix bit 0: operands read from LDS,
+    bit 1: exp2 at the softmax ratio); see include/chorus_ops.h."""
+    lib = load()
+    ws = _ws(lib.chorus_mfma_ceiling_workspace_bytes(), device)
+    out = C.c_double(0)
+    _status("chorus_mfma_ceiling", lib.chorus_mfma_ceiling(int(bool(normal_data)), int(mix), int(launches), C.byref(out),
+                                                           _p(ws), ws.numel(), _stream()))
+    return out.value

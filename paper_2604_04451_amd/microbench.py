@@ -1,7 +1,8 @@
 """Per-entry-point timing of the memory-bound steps of the Chorus hot path on one MI355X:
 cache lookup, stage-1 copy, latent fusion, compaction, row gather / scatter, the
 region-mask pipeline and the per-token normalisation kernels, at the Wan2.1-1.3B 480p
-shapes. Each call is timed with HIP events on the launch stream over a rotation of
+shapes; then the matrix-pipe ceiling this device sustains (a bare MFMA loop, by operand
+data and by what accompanies the MFMAs). Each call is timed with HIP events on the launch stream over a rotation of
 buffers larger than the last-level cache, so every launch reads cold data.
 
     python -m paper_2604_04451_amd.microbench [--iters 48]
@@ -128,6 +129,40 @@ def main():
     report("qk_norm_rope 32760x1536 (one of q, k)", L * D * 4, med, best)
     med, best = timeit(lambda i: B.chorus_v_transpose(qkv[i % 4], 2 * D, vt[i % 4], L), n)
     report("v_transpose 32760x1536", L * D * 4, med, best)
+
+    # ---- self-attention at the 480p length on N(0,1) operands and on constant ones: same launches, same instruction
+    #      stream, different power draw
+    Q = torch.empty(H, Lpad, dh, dtype=torch.bfloat16, device=DEV)
+    K = torch.empty(H, Lpad, dh, dtype=torch.bfloat16, device=DEV)
+    Vt = torch.empty(D, Lpad, dtype=torch.bfloat16, device=DEV)
+    Oo = torch.empty(L, D, dtype=torch.bfloat16, device=DEV)
+    for dname in ("N(0,1)", "all 1.0"):
+        for t in (Q, K, Vt):
+            if dname == "all 1.0":
+                t.fill_(1.0)
+            else:
+                t.copy_(torch.randn(t.shape, device=DEV, generator=g))
+        for _ in range(20):
+            B.chorus_attention(Q, K, Vt, Oo, None, L, L)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            B.chorus_attention(Q, K, Vt, Oo, None, L, L)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 20
+        tf = 4.0 * L * L * D / ms / 1e9
+        print(f"self_attention L={L} H={H}x{dh}, operands {dname:<8s} {ms:7.3f} ms  {tf:8.1f} TFLOP/s  "
+              f"({tf / 2500.0:.3f} of 2.5 PFLOP/s)", flush=True)
+    del Q, K, Vt, Oo
+
+    # ---- what the matrix pipe sustains on this device (power-managed: depends on data and instruction mix)
+    for data, dname in ((False, "operands all 1.0"), (True, "operands N(0,1)")):
+        for mix, mname in ((0, "registers only"), (1, "A operand from LDS"), (2, "+ exp2 at the softmax ratio"),
+                           (3, "A from LDS + exp2")):
+            tf = B.chorus_mfma_ceiling(data, mix, 20)
+            print(f"mfma_ceiling bf16 32x32x16, {dname}, {mname:<28s} {tf:8.1f} TFLOP/s  ({tf / 2500.0:.3f} of 2.5 PFLOP/s)",
+                  flush=True)
 
 
 if __name__ == "__main__":

@@ -188,3 +188,15 @@ def test_solver_entry_points_validate():
     b = lib.chorus_denoise_step_solver_workspace_bytes(C.byref(ms), 4, 1)
     assert 0 < a < b
     assert lib.chorus_denoise_run_workspace_bytes(C.byref(ms), 4) >= b
+
+
+def test_mfma_ceiling_validates():
+    lib = P.load()
+    out = C.c_double(0)
+    need = lib.chorus_mfma_ceiling_workspace_bytes()
+    assert need > 0
+    assert lib.chorus_mfma_ceiling(1, 4, 1, C.byref(out), C.c_void_p(16), need, None) == B.E_ARG       # mix out of range
+    assert lib.chorus_mfma_ceiling(1, 0, 0, C.byref(out), C.c_void_p(16), need, None) == B.E_ARG       # no launches
+    assert lib.chorus_mfma_ceiling(1, 0, 1, None, C.c_void_p(16), need, None) == B.E_ARG
+    assert lib.chorus_mfma_ceiling(1, 0, 1, C.byref(out), None, need, None) == B.E_WORKSPACE
+    assert lib.chorus_mfma_ceiling(1, 0, 1, C.byref(out), C.c_void_p(16), need - 1, None) == B.E_WORKSPACE

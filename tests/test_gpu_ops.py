@@ -160,3 +160,14 @@ def test_attention_tgaa_column_scale(H, dh, Lq, Lt, variant):
     a = _attn_case(H, dh, Lq, Lt, variant, col_scale=np.ones(Lt, np.float32), q_std=1.5, name="tgaa-neutral")
     b = _attn_case(H, dh, Lq, Lt, variant, col_scale=None, q_std=1.5, name="plain")
     assert abs(a[1] - b[1]) < 1e-3
+
+
+def test_mfma_ceiling_runs_and_orders():
+    """The benchmark diagnostic: a bare MFMA loop. Constant operands sustain more than random ones, and
+    LDS operand reads plus exponentials cost throughput; all within the part's nominal 2.5 PFLOP/s."""
+    print("[case] mfma_ceiling", flush=True)
+    ones = B.chorus_mfma_ceiling(False, 0, 5)
+    rnd = B.chorus_mfma_ceiling(True, 0, 5)
+    mix = B.chorus_mfma_ceiling(True, 3, 5)
+    print(f"[info] mfma ceiling TFLOP/s: ones {ones:.0f}, normal {rnd:.0f}, normal + LDS operand + exp2 {mix:.0f}", flush=True)
+    assert 300.0 < mix < rnd * 1.02 and rnd < ones * 1.02 and ones < 2700.0
