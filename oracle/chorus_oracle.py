@@ -89,8 +89,14 @@ def cache_insert(cache_emb, cache_latents, slot, emb, latent):
     return ce, cl
 
 
-def denoise_schedule(m, tau, N, params=None):
+def denoise_schedule(m, tau, N, params=None, stored_steps=None):
     """(K1, K2, plan) with plan[i] = (stage, gamma_k, gamma_o) for step i (0-based).
+
+    stored_steps (optional): the depths k at which the matched entry holds an intermediate
+    latent (the state after k steps; Sec. 3.1 "Cache Update" keeps several). Full reuse can
+    only resume from a stored state, so K1 becomes the largest stored depth not above the
+    K1 of Eq. 1; with none the request has no usable source latent and runs as a miss.
+    The stage-2 length K2 - K1 is kept.
 
     m < tau  =>  K1 = K2 = 0 and every step is a plain stage-3 step.
     Otherwise s = clip((m - tau)/(1 - tau), 0, 1) and
@@ -114,6 +120,11 @@ def denoise_schedule(m, tau, N, params=None):
     s = min(max((float(m) - tau) / (1.0 - tau), 0.0), 1.0) if tau < 1.0 else 1.0
     hi = max(N - int(p["r3"]), 0)
     K1 = min(max(int(math.floor(N * (p["a1"] + p["b1"] * s) + 1e-9)), 0), hi)
+    if stored_steps is not None:
+        usable = [int(k) for k in stored_steps if 1 <= int(k) <= K1]
+        if not usable:
+            return 0, 0, [(3, 1.0, 1.0) for _ in range(N)]
+        K1 = max(usable)
     K2 = min(max(K1 + int(math.floor(N * (p["a2"] + p["b2"] * s) + 1e-9)), K1), hi)
     plan = []
     for i in range(N):
@@ -478,8 +489,18 @@ def run_schedule(plan, sigmas, latent0, SL, blocks, gw, shape, text_ctx, t_mods,
     stage-2 steps run the selective region path, stage-3 steps run everything.
     key_scale_of(gamma_k) builds the per-text-token key scale for a step.
     With store_after = k the latent after k steps (the intermediate state a cache update keeps)
-    is returned as well."""
+    is returned as well; with a list of depths, the list of those states."""
     lat = np.asarray(latent0, F64)
+    if store_after is not None and not np.isscalar(store_after):
+        depths = [int(k) for k in store_after]
+        snaps = {}
+        for k in sorted(set(depths)):
+            assert 1 <= k <= len(plan)
+            snaps[k] = run_schedule(plan[:k], sigmas, lat, SL, blocks, gw, shape, text_ctx, t_mods, t_heads,
+                                    mask_see=mask_see, mask_edit=mask_edit, key_scale_of=key_scale_of)
+        final = run_schedule(plan, sigmas, lat, SL, blocks, gw, shape, text_ctx, t_mods, t_heads,
+                             mask_see=mask_see, mask_edit=mask_edit, key_scale_of=key_scale_of)
+        return final, [snaps[k] for k in depths]
     snap = None
     for i, (stage, gk, go) in enumerate(plan):
         if store_after is not None and i == store_after:

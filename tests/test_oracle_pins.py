@@ -798,3 +798,53 @@ def test_run_schedule_dpmpp_first_order_is_the_euler_run():
     c = O.run_schedule_dpmpp(plan, sig, lat, SL, blocks, gw, bs, ctx, t_mods, t_heads, order=2, mask_see=see,
                              mask_edit=edit, key_scale_of=ks)
     assert np.abs(c - a).max() > 1e-6          # step 2 (stage 3, after a stage-2 step) extrapolates on the M_see tokens
+
+
+# ------------------------------------------------------------------ several stored depths per entry (Sec. 3.1 "Cache Update")
+
+@pytest.mark.parametrize("N", [4, 8, 50])
+def test_schedule_with_stored_depths(N):
+    tau = 0.75
+    every = list(range(1, N + 1))
+    prev = -1
+    for m in np.linspace(0.0, 1.0, 41):
+        K1, K2, plan = O.denoise_schedule(m, tau, N)
+        # every depth stored: nothing changes
+        assert O.denoise_schedule(m, tau, N, stored_steps=every) == (K1, K2, plan)
+        for stored in ([1], [2], [1, 3], [N // 2, N // 4 + 1], [N]):
+            k1, k2, pl = O.denoise_schedule(m, tau, N, stored_steps=stored)
+            assert k1 in stored or (k1, k2) == (0, 0)
+            assert k1 <= K1 and 0 <= k1 <= k2 <= max(N - 1, 0)
+            ok = [k for k in stored if 1 <= k <= K1]
+            assert k1 == (max(ok) if ok else 0)
+            if ok:
+                assert k2 - k1 >= K2 - K1                       # the region stage is never shortened
+                if K2 < N - 1:
+                    assert k2 - k1 == K2 - K1                   # and keeps its length where Eq. 1 was not clipped
+                assert [p[0] for p in pl] == [1] * k1 + [2] * (k2 - k1) + [3] * (N - k2)
+                # the factors are those of a schedule whose Eq. 1 lands on k1 directly
+                for i in range(k1, N):
+                    w = max(0.0, 1.0 - (i - k1) / max(1, k2 - k1))
+                    assert pl[i][1] >= 1.0 and (w > 0 or pl[i][1] == 1.0)
+            else:
+                assert pl == [(3, 1.0, 1.0)] * N
+        k1, _, _ = O.denoise_schedule(m, tau, N, stored_steps=[1, 3])
+        assert k1 >= prev                      # still monotone in the similarity
+        prev = k1
+    assert O.denoise_schedule(0.5, tau, N, stored_steps=every)[:2] == (0, 0)      # a miss stays a miss
+
+
+def test_run_schedule_snapshots_at_several_depths():
+    bs, blocks, gw, ctx, t_mods, t_heads = _tiny_model()
+    lat = synth.latent(bs, 0)
+    sig = [1.0, 0.75, 0.5, 0.25, 0.0]
+    plan = [(3, 1.0, 1.0)] * 4
+    final, snaps = O.run_schedule(plan, sig, lat, None, blocks, gw, bs, ctx, t_mods, t_heads, store_after=[1, 3])
+    one, s1 = O.run_schedule(plan, sig, lat, None, blocks, gw, bs, ctx, t_mods, t_heads, store_after=1)
+    _, s3 = O.run_schedule(plan, sig, lat, None, blocks, gw, bs, ctx, t_mods, t_heads, store_after=3)
+    np.testing.assert_array_equal(final, one)
+    np.testing.assert_array_equal(snaps[0], s1)
+    np.testing.assert_array_equal(snaps[1], s3)
+    # resuming from the depth-3 state reproduces the rest of the run
+    rest = O.denoise_step(snaps[1], blocks, gw, bs, ctx, t_mods[3], t_heads[3], sig[4] - sig[3])
+    np.testing.assert_array_equal(rest, final)
