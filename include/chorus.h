@@ -106,6 +106,16 @@ typedef struct {
 
 int32_t chorus_denoise_schedule(float m, float tau, int32_t N, const chorus_sched_params* params, int32_t* K1,
                                 int32_t* K2, chorus_step_plan* plan);
+/* The same schedule when the matched entry holds intermediate latents only at some depths
+ * (Sec. 3.1 "Cache Update": the states after stored_steps[j] steps). Full reuse can only
+ * resume from a stored state: K1 becomes the largest stored depth in [1, K1 of Eq. 1], K2 is
+ * K1 plus the same region-stage length (clipped to N - r3), and *slot is that depth's
+ * position in stored_steps. With no such depth (or on a miss) the plan is N plain steps,
+ * K1 = K2 = 0 and *slot = -1.
+ *   stored_steps host [n_stored] (any order; n_stored may be 0); slot host (may be NULL) */
+int32_t chorus_denoise_schedule_stored(float m, float tau, int32_t N, const chorus_sched_params* params,
+                                       const int32_t* stored_steps, int32_t n_stored, int32_t* K1, int32_t* K2,
+                                       int32_t* slot, chorus_step_plan* plan);
 
 /* ------------------------------------------------------------------------
  * One DiT block forward on Ls token rows, in place on the fp32 residual stream

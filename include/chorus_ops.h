@@ -236,6 +236,11 @@ int32_t chorus_denoise_step_solver(const chorus_model_shape* model, const chorus
  * store_after steps (1 <= store_after <= n_steps; the intermediate state a later hit with
  * K1 = store_after resumes from) are written to entry store_slot with chorus_cache_insert.
  * One cached latent per entry serves both the stage-1 copy and the stage-2 fusion.
+ * Several depths per entry: with latent_steps (host [n_latent_steps], distinct, each in [1, n_steps])
+ * cache_latents is [N, n_latent_steps, C, T, Hl, Wl]; a hit takes its boundaries from
+ * chorus_denoise_schedule_stored and resumes from the latent stored at depth K1 (also the SL of the
+ * stage-2 fusion); a miss with store_slot >= 0 writes the latent after latent_steps[j] steps to
+ * [store_slot, j] for every j and the query once (store_after is then ignored).
  * Sampler: solver_order 0 or 1 with text_ctx_uncond NULL takes the Euler form of the first-order
  * step (chorus_denoise_step); solver_order 2 and / or text_ctx_uncond (classifier-free guidance
  * with scale `guidance`, two model evaluations per step) take chorus_denoise_step_solver. The
@@ -270,6 +275,8 @@ typedef struct {
   const uint8_t* mask_edit;
   int64_t store_slot;    /* -1: no cache update */
   int32_t store_after;
+  const int32_t* latent_steps;      /* host; NULL: one latent per entry, used whatever K1 is */
+  int32_t n_latent_steps;
   int32_t solver_order;             /* 0, 1: first order; 2: DPM-Solver++ multistep */
   const uint16_t* text_ctx_uncond;  /* dev [Lt, D] bf16 or NULL: classifier-free guidance */
   float guidance;

@@ -66,7 +66,8 @@ class Request(C.Structure):
                 ("sched", C.POINTER(SchedParams)), ("n_steps", C.c_int32), ("sigmas", C.POINTER(C.c_float)),
                 ("t_mods", C.c_void_p), ("t_heads", C.c_void_p), ("text_ctx", C.c_void_p), ("tdiff", C.c_void_p),
                 ("mask_see", C.c_void_p), ("mask_edit", C.c_void_p), ("store_slot", C.c_int64),
-                ("store_after", C.c_int32), ("solver_order", C.c_int32), ("text_ctx_uncond", C.c_void_p),
+                ("store_after", C.c_int32), ("latent_steps", C.POINTER(C.c_int32)), ("n_latent_steps", C.c_int32),
+                ("solver_order", C.c_int32), ("text_ctx_uncond", C.c_void_p),
                 ("guidance", C.c_float)]
 
 
@@ -101,6 +102,8 @@ def load():
         "chorus_cache_insert": (i32, [vp, vp, i64, i64, i32, i64, vp, vp, vp]),
         "chorus_denoise_schedule": (i32, [f32, f32, i32, C.POINTER(SchedParams), C.POINTER(i32), C.POINTER(i32),
                                           C.POINTER(StepPlan)]),
+        "chorus_denoise_schedule_stored": (i32, [f32, f32, i32, C.POINTER(SchedParams), C.POINTER(i32), i32, C.POINTER(i32),
+                                                 C.POINTER(i32), C.POINTER(i32), C.POINTER(StepPlan)]),
         "chorus_dit_block_workspace_bytes": (sz, [C.POINTER(BlockShape), i64]),
         "chorus_dit_block_step": (i32, [C.POINTER(BlockShape), C.POINTER(BlockWeights), vp, i64, vp, vp, vp, vp, f32,
                                         vp, sz, vp]),
@@ -233,7 +236,9 @@ def lookup_result(out):
 
 # -------------------------------------------------------------- schedule
 
-def chorus_denoise_schedule(m, tau, N, params=None):
+def chorus_denoise_schedule(m, tau, N, params=None, stored_steps=None):
+    """(K1, K2, plan); with stored_steps (the depths the matched entry holds) also the position of the
+    depth that full reuse resumes from, -1 if none: (K1, K2, plan, slot)."""
     lib = load()
     sp = None
     if params is not None:
@@ -242,6 +247,13 @@ def chorus_denoise_schedule(m, tau, N, params=None):
         sp = SchedParams(**d)
     plan = (StepPlan * max(N, 1))()
     k1, k2 = C.c_int32(0), C.c_int32(0)
+    if stored_steps is not None:
+        ss = (C.c_int32 * max(len(stored_steps), 1))(*[int(v) for v in stored_steps])
+        slot = C.c_int32(0)
+        _status("chorus_denoise_schedule_stored",
+                lib.chorus_denoise_schedule_stored(float(m), float(tau), int(N), C.byref(sp) if sp is not None else None, ss,
+                                                   len(stored_steps), C.byref(k1), C.byref(k2), C.byref(slot), plan))
+        return k1.value, k2.value, [(plan[i].stage, plan[i].gamma_k, plan[i].gamma_o) for i in range(N)], slot.value
     _status("chorus_denoise_schedule",
             lib.chorus_denoise_schedule(float(m), float(tau), int(N), C.byref(sp) if sp is not None else None,
                                         C.byref(k1), C.byref(k2), plan))
@@ -749,17 +761,21 @@ def chorus_denoise_run_workspace_bytes(model: ModelShape, N: int) -> int:
 
 def chorus_denoise_run(model: ModelShape, blocks_arr, glue: DeviceGlue, latent, cache_emb, cache_latents, query, tau,
                        sigmas, t_mods, t_heads, text_ctx, tdiff=None, mask_see=None, mask_edit=None, sched=None,
-                       ws=None, store_slot=-1, store_after=0, solver_order=1, text_ctx_uncond=None, guidance=1.0):
+                       ws=None, store_slot=-1, store_after=0, solver_order=1, text_ctx_uncond=None, guidance=1.0,
+                       latent_steps=None):
     """Runs one request; returns a dict with the lookup result, K1, K2 and the stage-2 token count.
     store_slot >= 0: on a miss, the query and the latent after store_after steps go into that cache entry.
-    solver_order 2: DPM-Solver++ multistep update; text_ctx_uncond: classifier-free guidance with scale guidance."""
+    solver_order 2: DPM-Solver++ multistep update; text_ctx_uncond: classifier-free guidance with scale guidance.
+    latent_steps: the depths every cache entry holds a latent for; cache_latents is then [N, len(latent_steps), ...]."""
     lib = load()
     D = model.block.D
     n_steps = len(sigmas) - 1
     N, d = cache_emb.shape
     _chk(latent, torch.float32, "latent", (model.C, model.T, model.Hl, model.Wl))
     _chk(cache_emb, torch.float32, "cache_emb")
-    _chk(cache_latents, torch.float32, "cache_latents", (N,) + tuple(latent.shape))
+    S = None if latent_steps is None else len(latent_steps)
+    _chk(cache_latents, torch.float32, "cache_latents", ((N,) if S is None else (N, S)) + tuple(latent.shape))
+    ls = None if S is None else (C.c_int32 * max(S, 1))(*[int(v) for v in latent_steps])
     _chk(query, torch.float32, "query", (d,))
     _chk(t_mods, torch.float32, "t_mods", (n_steps, 6, D))
     _chk(t_heads, torch.float32, "t_heads", (n_steps, 2, D))
@@ -779,7 +795,7 @@ def chorus_denoise_run(model: ModelShape, blocks_arr, glue: DeviceGlue, latent, 
                  float(tau), C.pointer(sp) if sp is not None else None, n_steps, sig, t_mods.data_ptr(),
                  t_heads.data_ptr(), text_ctx.data_ptr(), 0 if tdiff is None else tdiff.data_ptr(),
                  0 if mask_see is None else mask_see.data_ptr(), 0 if mask_edit is None else mask_edit.data_ptr(),
-                 int(store_slot), int(store_after), int(solver_order),
+                 int(store_slot), int(store_after), ls, 0 if S is None else S, int(solver_order),
                  0 if text_ctx_uncond is None else text_ctx_uncond.data_ptr(), float(guidance))
     if ws is None:
         ws = _ws(lib.chorus_denoise_run_workspace_bytes(C.byref(model), N), latent.device)

@@ -8,8 +8,27 @@ inline double clampd(double v, double lo, double hi) { return v < lo ? lo : (v >
 inline int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 }  // namespace
 
+namespace {
+int32_t schedule_impl(float m, float tau, int32_t N, const chorus_sched_params* params, const int32_t* stored_steps,
+                      int32_t n_stored, int32_t* K1, int32_t* K2, int32_t* slot, chorus_step_plan* plan);
+}
+
 extern "C" int32_t chorus_denoise_schedule(float m, float tau, int32_t N, const chorus_sched_params* params,
                                            int32_t* K1, int32_t* K2, chorus_step_plan* plan) {
+  return schedule_impl(m, tau, N, params, nullptr, -1, K1, K2, nullptr, plan);
+}
+
+extern "C" int32_t chorus_denoise_schedule_stored(float m, float tau, int32_t N, const chorus_sched_params* params,
+                                                  const int32_t* stored_steps, int32_t n_stored, int32_t* K1,
+                                                  int32_t* K2, int32_t* slot, chorus_step_plan* plan) {
+  if (n_stored < 0 || (n_stored > 0 && !stored_steps)) return CHORUS_E_ARG;
+  return schedule_impl(m, tau, N, params, stored_steps, n_stored, K1, K2, slot, plan);
+}
+
+namespace {
+int32_t schedule_impl(float m, float tau, int32_t N, const chorus_sched_params* params, const int32_t* stored_steps,
+                      int32_t n_stored, int32_t* K1, int32_t* K2, int32_t* slot, chorus_step_plan* plan) {
+  if (slot) *slot = -1;
   if (N < 0 || (N > 0 && !plan)) return CHORUS_E_ARG;
   chorus_sched_params p;
   if (params) {
@@ -32,7 +51,24 @@ extern "C" int32_t chorus_denoise_schedule(float m, float tau, int32_t N, const 
   const double dm = (double)m, dt = (double)tau;
   const double s = dt < 1.0 ? clampd((dm - dt) / (1.0 - dt), 0.0, 1.0) : 1.0;
   const int hi = N - p.r3 > 0 ? N - p.r3 : 0;
-  const int k1 = clampi((int)std::floor(N * (p.a1 + p.b1 * s) + 1e-9), 0, hi);
+  int k1 = clampi((int)std::floor(N * (p.a1 + p.b1 * s) + 1e-9), 0, hi);
+  if (n_stored >= 0) {
+    // full reuse resumes from a stored state: the deepest one not beyond Eq. 1's K1, else the request runs as a miss
+    int best = 0, best_slot = -1;
+    for (int j = 0; j < n_stored; ++j)
+      if (stored_steps[j] >= 1 && stored_steps[j] <= k1 && stored_steps[j] > best) {
+        best = stored_steps[j];
+        best_slot = j;
+      }
+    if (best_slot < 0) {
+      for (int i = 0; i < N; ++i) plan[i] = chorus_step_plan{3, 1.0f, 1.0f};
+      if (K1) *K1 = 0;
+      if (K2) *K2 = 0;
+      return CHORUS_OK;
+    }
+    k1 = best;
+    if (slot) *slot = best_slot;
+  }
   const int k2 = clampi(k1 + (int)std::floor(N * (p.a2 + p.b2 * s) + 1e-9), k1, hi);
   for (int i = 0; i < N; ++i) {
     if (i < k1) {
@@ -54,3 +90,4 @@ extern "C" int32_t chorus_denoise_schedule(float m, float tau, int32_t N, const 
   if (K2) *K2 = k2;
   return CHORUS_OK;
 }
+}  // namespace

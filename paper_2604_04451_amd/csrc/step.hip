@@ -370,8 +370,19 @@ int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_w
   if (rq->n_steps < 0 || rq->cache_N < 0 || rq->cache_d <= 0) return CHORUS_E_ARG;
   if (rq->n_steps > 0 && (!rq->sigmas || !rq->t_mods || !rq->t_heads || !rq->text_ctx)) return CHORUS_E_ARG;
   if (!rq->query || (rq->cache_N > 0 && (!rq->cache_emb || !rq->cache_latents))) return CHORUS_E_ARG;
-  if (rq->store_slot >= 0 && (rq->store_slot >= rq->cache_N || rq->store_after < 1 || rq->store_after > rq->n_steps))
+  const int S = rq->latent_steps ? rq->n_latent_steps : 1;  // latents per cache entry
+  if (rq->latent_steps) {
+    if (S < 1 || S > 64) return CHORUS_E_ARG;
+    for (int j = 0; j < S; ++j) {
+      if (rq->latent_steps[j] < 1 || rq->latent_steps[j] > rq->n_steps) return CHORUS_E_ARG;
+      for (int k = 0; k < j; ++k)
+        if (rq->latent_steps[k] == rq->latent_steps[j]) return CHORUS_E_ARG;
+    }
+    if (rq->store_slot >= rq->cache_N) return CHORUS_E_ARG;
+  } else if (rq->store_slot >= 0 &&
+             (rq->store_slot >= rq->cache_N || rq->store_after < 1 || rq->store_after > rq->n_steps)) {
     return CHORUS_E_ARG;
+  }
   if (rq->solver_order < 0 || rq->solver_order > 2) return CHORUS_E_ARG;
   if (!ws) return CHORUS_E_WORKSPACE;
   const chorus_model_shape& m = *model;
@@ -396,14 +407,19 @@ int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_w
 
   chorus_step_plan plan_buf[64];
   if (rq->n_steps > 64) return CHORUS_E_SHAPE;
-  int32_t K1 = 0, K2 = 0;
-  st = chorus_denoise_schedule(lr.score, rq->tau, rq->n_steps, rq->sched, &K1, &K2, plan_buf);
+  int32_t K1 = 0, K2 = 0, depth_slot = 0;
+  if (rq->latent_steps)
+    st = chorus_denoise_schedule_stored(lr.score, rq->tau, rq->n_steps, rq->sched, rq->latent_steps, S, &K1, &K2,
+                                        &depth_slot, plan_buf);
+  else
+    st = chorus_denoise_schedule(lr.score, rq->tau, rq->n_steps, rq->sched, &K1, &K2, plan_buf);
   if (st != CHORUS_OK) return st;
+  if (depth_slot < 0) depth_slot = 0;  // no usable depth: the plan has no reuse and SL is never read
   result->K1 = K1;
   result->K2 = K2;
   result->Ls = 0;
 
-  const float* SL = lr.hit ? rq->cache_latents + (int64_t)lr.index * lat_elems : nullptr;
+  const float* SL = lr.hit ? rq->cache_latents + ((int64_t)lr.index * S + depth_slot) * lat_elems : nullptr;
   int64_t Ls = 0;
   if (K2 > K1) {
     if (!rq->mask_see || !rq->mask_edit) return CHORUS_E_ARG;
@@ -477,10 +493,24 @@ int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_w
     }
     if (st != CHORUS_OK) return st;
     // cache update after a miss: keep the prompt embedding and this intermediate latent for later requests
-    if (!lr.hit && rq->store_slot >= 0 && i + 1 == rq->store_after) {
+    if (!lr.hit && rq->store_slot >= 0 && !rq->latent_steps && i + 1 == rq->store_after) {
       st = chorus_cache_insert(rq->cache_emb, rq->cache_latents, rq->cache_N, rq->store_slot, rq->cache_d, lat_elems,
                                rq->query, latent, stream);
       if (st != CHORUS_OK) return st;
+    }
+    if (!lr.hit && rq->store_slot >= 0 && rq->latent_steps) {
+      // the prompt embedding goes in with the shallowest stored state: no key without a latent, and one copy of it
+      int shallowest = rq->latent_steps[0];
+      for (int j = 1; j < S; ++j) shallowest = rq->latent_steps[j] < shallowest ? rq->latent_steps[j] : shallowest;
+      for (int j = 0; j < S; ++j) {
+        if (rq->latent_steps[j] != i + 1) continue;
+        st = device_copy(rq->cache_latents + ((int64_t)rq->store_slot * S + j) * lat_elems, latent, (long)lat_elems, s);
+        if (st != CHORUS_OK) return st;
+      }
+      if (i + 1 == shallowest) {
+        st = device_copy(rq->cache_emb + rq->store_slot * (int64_t)rq->cache_d, rq->query, rq->cache_d, s);
+        if (st != CHORUS_OK) return st;
+      }
     }
   }
   return CHORUS_OK;

@@ -200,3 +200,18 @@ def test_mfma_ceiling_validates():
     assert lib.chorus_mfma_ceiling(1, 0, 1, None, C.c_void_p(16), need, None) == B.E_ARG
     assert lib.chorus_mfma_ceiling(1, 0, 1, C.byref(out), None, need, None) == B.E_WORKSPACE
     assert lib.chorus_mfma_ceiling(1, 0, 1, C.byref(out), C.c_void_p(16), need - 1, None) == B.E_WORKSPACE
+
+
+@pytest.mark.parametrize("N", [4, 8, 50])
+def test_schedule_with_stored_depths_matches_oracle(N):
+    tau = 0.75
+    for stored in ([1], [2], [3, 1], [N // 2, N // 4 + 1, N], list(range(1, N + 1)), []):
+        for params in (None, dict(gamma_override=1.5), dict(a1=0.1, b1=0.5, a2=0.2, b2=0.3, r3=2)):
+            for m in list(np.linspace(0.0, 1.0, 41)) + [float("nan")]:
+                mf = float(np.float32(m))
+                k1, k2, plan, slot = P.chorus_denoise_schedule(mf, tau, N, params, stored_steps=stored)
+                ok1, ok2, oplan = O.denoise_schedule(mf, float(np.float32(tau)), N, params, stored_steps=stored)
+                assert (k1, k2) == (ok1, ok2), (m, stored, params)
+                assert slot == (stored.index(k1) if k1 > 0 else -1)
+                for (s, gk, go), (os_, ogk, ogo) in zip(plan, oplan):
+                    assert s == os_ and gk == np.float32(ogk) and go == np.float32(ogo)

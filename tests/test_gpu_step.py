@@ -238,3 +238,64 @@ def test_cold_start_miss_stores_then_same_prompt_hits():
                          mask_see=see, mask_edit=see, key_scale_of=lambda gk: np.full(bs.Lt, gk))
     check(host(dl), ref, "warm latent")
     assert host(cache_lat[slot]).tobytes() == stored.tobytes()              # a hit does not update the cache
+
+
+def test_several_stored_depths_per_entry():
+    """Sec. 3.1 "Cache Update" with more than one intermediate latent per entry: a cold start stores the states after
+    1 and 2 steps; the identical prompt (score 1, Eq. 1 gives K1 = 2) resumes from the depth-2 state, a near
+    duplicate (K1 = 1) from the depth-1 state, and an entry that only holds a depth beyond K1 gives no reuse."""
+    print("[case] cold start -> store depths (1, 2) -> hits at K1 = 2 and K1 = 1 (c1, 2 blocks)", flush=True)
+    bs = synth.SHAPES["c1"]
+    md = Model(bs, 2)
+    cap, slot, depths = 4, 2, [2, 1]                       # stored in this order on purpose
+    cache = torch.zeros(cap, bs.cache_d, device=DEV)
+    cache_lat = torch.zeros((cap, len(depths)) + bs.latent_shape, device=DEV)
+    q = synth.normal(9, "cold.q", (bs.cache_d,))
+    noise = synth.latent(bs, 9, "noise", std=1.0)
+    see = synth.box_mask(bs.grid, bs.grid[0], bs.grid[1] - 2, bs.grid[2] // 2, 0, 1, 1)
+    d_see = torch.from_numpy(see).to(DEV)
+    sched = dict(gamma_override=1.5)
+    run = lambda dl, dq, **kw: B.chorus_denoise_run(md.model, md.arr, md.dglue, dl, cache, cache_lat, dq, 0.75, md.sigmas,
+                                                    md.d_tmods, md.d_theads, md.d_ctx, mask_see=d_see, mask_edit=d_see,
+                                                    sched=sched, latent_steps=depths, **kw)
+    dl = dev_f32(noise)
+    res = run(dl, dev_f32(q), store_slot=slot)
+    assert not res["hit"] and (res["K1"], res["K2"]) == (0, 0)
+    plan = [(3, 1.0, 1.0)] * 4
+    ref, snaps = O.run_schedule(plan, md.sigmas, noise, None, md.blocks, md.gw, bs, md.ctx, md.t_mods, md.t_heads,
+                                store_after=depths)
+    check(host(dl), ref, "cold-start latent")
+    for j, k in enumerate(depths):
+        check(host(cache_lat[slot, j]), snaps[j], f"stored state after {k} steps")
+    assert host(cache[slot]).tobytes() == q.tobytes()
+    others = [i for i in range(cap) if i != slot]
+    assert float(cache[others].abs().max()) == 0.0 and float(cache_lat[others].abs().max()) == 0.0
+    stored = host(cache_lat[slot]).copy()
+    ks_all = lambda gk: np.full(bs.Lt, gk)
+    # identical prompt: the deepest state
+    noise2 = synth.latent(bs, 10, "noise", std=1.0)
+    dl = dev_f32(noise2)
+    res = run(dl, dev_f32(q), store_slot=slot)
+    K1, K2, plan = O.denoise_schedule(float(np.float32(res["score"])), float(np.float32(0.75)), 4, sched, stored_steps=depths)
+    assert res["hit"] and res["index"] == slot and (res["K1"], res["K2"]) == (K1, K2) and K1 == 2
+    ref = O.run_schedule(plan, md.sigmas, noise2, stored[depths.index(2)], md.blocks, md.gw, bs, md.ctx, md.t_mods,
+                         md.t_heads, mask_see=see, mask_edit=see, key_scale_of=ks_all)
+    check(host(dl), ref, "hit at depth 2")
+    assert host(cache_lat[slot]).tobytes() == stored.tobytes()          # a hit writes nothing
+    # near duplicate: cosine ~0.9 -> Eq. 1 gives K1 = 1 -> the depth-1 state
+    q2 = q + 0.45 * np.linalg.norm(q) * synth.normal(9, "cold.dq", (bs.cache_d,)) / np.sqrt(bs.cache_d)
+    dl = dev_f32(noise2)
+    res = run(dl, dev_f32(q2))
+    K1, K2, plan = O.denoise_schedule(float(np.float32(res["score"])), float(np.float32(0.75)), 4, sched, stored_steps=depths)
+    assert res["hit"] and 0.75 <= res["score"] < 0.999 and (res["K1"], res["K2"]) == (K1, K2) and K1 == 1
+    ref = O.run_schedule(plan, md.sigmas, noise2, stored[depths.index(1)], md.blocks, md.gw, bs, md.ctx, md.t_mods,
+                         md.t_heads, mask_see=see, mask_edit=see, key_scale_of=ks_all)
+    check(host(dl), ref, "hit at depth 1")
+    # an entry that only holds depth 2: the near duplicate (K1 = 1) finds no state to resume from and runs plain
+    dl = dev_f32(noise2)
+    res = B.chorus_denoise_run(md.model, md.arr, md.dglue, dl, cache, cache_lat[:, :1].contiguous(), dev_f32(q2), 0.75,
+                               md.sigmas, md.d_tmods, md.d_theads, md.d_ctx, mask_see=d_see, mask_edit=d_see, sched=sched,
+                               latent_steps=[2])
+    assert res["hit"] and (res["K1"], res["K2"]) == (0, 0)
+    ref = O.run_schedule([(3, 1.0, 1.0)] * 4, md.sigmas, noise2, None, md.blocks, md.gw, bs, md.ctx, md.t_mods, md.t_heads)
+    check(host(dl), ref, "hit without a usable depth")
