@@ -77,6 +77,28 @@ DEFAULT_SCHED = dict(a1=0.25, b1=0.25, a2=0.25, b2=0.25, r3=1, Gamma_k=1.5, Gamm
                      gamma_override=0.0)
 
 
+def cache_lookup_topk(cache_emb, queries, tau, k):
+    """The k best entries for each of several prompt embeddings (the retrieval of Sec. 3.1 for a
+    batch of queued requests; k > 1 gives the scheduler candidates to choose from).
+    Returns (index [Q, k], score [Q, k], hit [Q]): entries by descending cosine, equal scores by
+    ascending index; positions beyond the cache size hold index -1 and score -inf;
+    hit[q] = score[q, 0] >= tau. Column 0 is `cache_lookup` of that query."""
+    queries = np.asarray(queries, F64)
+    Q = queries.shape[0]
+    k = int(k)
+    idx = np.full((Q, k), -1, np.int64)
+    sc = np.full((Q, k), -np.inf, F64)
+    hit = np.zeros(Q, bool)
+    for qi in range(Q):
+        s = cosine_scores(cache_emb, queries[qi])
+        order = sorted(range(s.size), key=lambda j: (-s[j], j))[:k]
+        for r, j in enumerate(order):
+            idx[qi, r] = j
+            sc[qi, r] = s[j]
+        hit[qi] = bool(sc[qi, 0] >= tau) if k > 0 else False
+    return idx, sc, hit
+
+
 def cache_insert(cache_emb, cache_latents, slot, emb, latent):
     """Cache update (Sec. 3.1 "Cache Update"): after a miss the request's prompt embedding and an
     intermediate latent are stored for later requests. Which entry is replaced is the caller's

@@ -848,3 +848,44 @@ def test_run_schedule_snapshots_at_several_depths():
     # resuming from the depth-3 state reproduces the rest of the run
     rest = O.denoise_step(snaps[1], blocks, gw, bs, ctx, t_mods[3], t_heads[3], sig[4] - sig[3])
     np.testing.assert_array_equal(rest, final)
+
+
+# ------------------------------------------------------------------ batched top-k retrieval
+
+def test_lookup_topk_brute_force_and_reductions():
+    rng = synth.stream(21, "topk")
+    cache = rng.standard_normal((37, 12))
+    cache[9] = cache[4]                      # equal rows: equal scores, lower index first
+    cache[20] = 2.0 * cache[4]               # cosine ignores the scale (a power of two keeps the tie exact)
+    cache[30] = 0.0                          # zero norm: -inf, sorted last
+    queries = np.vstack([rng.standard_normal((5, 12)), cache[4][None], np.zeros((1, 12))])
+    k = 6
+    idx, sc, hit = O.cache_lookup_topk(cache, queries, 0.6, k)
+    assert idx.shape == (7, k) and sc.shape == (7, k) and hit.shape == (7,)
+    for qi, q in enumerate(queries):
+        # brute force: plain Python cosine, selection by repeated scan
+        scores = [_brute_lookup(cache[j:j + 1], q)[1] for j in range(cache.shape[0])]
+        left = list(range(cache.shape[0]))
+        for r in range(k):
+            best = left[0]
+            for j in left:
+                if scores[j] > scores[best]:
+                    best = j
+            left.remove(best)
+            assert idx[qi, r] == best and (sc[qi, r] == scores[best] or abs(sc[qi, r] - scores[best]) < 1e-12)
+        # column 0 is the single-query lookup
+        j, m, h = O.cache_lookup(cache, q, 0.6)
+        assert (idx[qi, 0], hit[qi]) == (j, h) and sc[qi, 0] == m
+        assert all(sc[qi, r] >= sc[qi, r + 1] for r in range(k - 1))
+    assert list(idx[5, :3]) == [4, 9, 20] and np.allclose(sc[5, :3], 1.0) and hit[5]
+    assert np.isinf(sc[6]).all() and list(idx[6]) == [0, 1, 2, 3, 4, 5] and not hit[6]   # zero query: all -inf, by index
+    # k beyond the cache size pads with (-1, -inf); k = 1 and an empty cache
+    idx, sc, hit = O.cache_lookup_topk(cache[:3], queries[:2], 0.6, 5)
+    assert (idx[:, 3:] == -1).all() and np.isinf(sc[:, 3:]).all() and sorted(idx[0, :3]) == [0, 1, 2]
+    idx, sc, hit = O.cache_lookup_topk(cache[:0], queries[:2], 0.6, 2)
+    assert (idx == -1).all() and np.isinf(sc).all() and not hit.any()
+    # a batch is the per-query results stacked
+    a = O.cache_lookup_topk(cache, queries, 0.6, 3)
+    for qi in range(queries.shape[0]):
+        b = O.cache_lookup_topk(cache, queries[qi:qi + 1], 0.6, 3)
+        assert (a[0][qi] == b[0][0]).all() and (a[1][qi] == b[1][0]).all() and a[2][qi] == b[2][0]
