@@ -65,6 +65,26 @@ int32_t chorus_cache_lookup(const float* cache_emb, int64_t N, int32_t d, const 
                             chorus_lookup_result* out, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * The same retrieval for a batch of queued requests, with candidates: the k best entries
+ * by cosine similarity for each of Q prompt embeddings. The cache is streamed once per 32
+ * queries (a [N, d] x [d, Q] fp32 contraction on the matrix pipe), not once per query.
+ *   queries    dev [Q, d] fp32
+ *   out_index  dev [Q, k] int32, out_score dev [Q, k] fp32: descending score, equal scores
+ *              by ascending index; positions beyond N hold index -1 and score -inf
+ *   out_hit    dev [Q] int32: out_score[q, 0] >= tau
+ *   ws         dev, chorus_cache_lookup_batch_workspace_bytes(N, d, Q) bytes
+ * Scores are fp32 with a summation order that depends only on (N, d), not on the row, so
+ * equal rows get equal scores; zero-norm rows or queries score -inf. Column 0 agrees with
+ * chorus_cache_lookup up to the fp32 rounding of a different summation order.
+ * 1 <= k <= 1024; d a multiple of 4; N < 2^31 - 256; Q == 0 is a no-op.
+ * Errors: CHORUS_E_ARG, CHORUS_E_SHAPE, CHORUS_E_WORKSPACE, CHORUS_E_HIP.
+ * ------------------------------------------------------------------------ */
+size_t chorus_cache_lookup_batch_workspace_bytes(int64_t N, int32_t d, int32_t Q);
+int32_t chorus_cache_lookup_batch(const float* cache_emb, int64_t N, int32_t d, const float* queries, int32_t Q, float tau,
+                                  int32_t k, int32_t* out_index, float* out_score, int32_t* out_hit, void* ws,
+                                  size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * Cache update (Sec. 3.1 "Cache Update"): after a miss the request's prompt embedding and
  * an intermediate latent are stored for later requests. Two device copies, bit for bit.
  *   cache_emb      dev [capacity, d] fp32, row `slot` is overwritten with emb [d]

@@ -100,6 +100,8 @@ def load():
         "chorus_cache_lookup_workspace_bytes": (sz, [i64]),
         "chorus_cache_lookup": (i32, [vp, i64, i32, vp, f32, vp, vp, sz, vp]),
         "chorus_cache_insert": (i32, [vp, vp, i64, i64, i32, i64, vp, vp, vp]),
+        "chorus_cache_lookup_batch_workspace_bytes": (sz, [i64, i32, i32]),
+        "chorus_cache_lookup_batch": (i32, [vp, i64, i32, vp, i32, f32, i32, vp, vp, vp, vp, sz, vp]),
         "chorus_denoise_schedule": (i32, [f32, f32, i32, C.POINTER(SchedParams), C.POINTER(i32), C.POINTER(i32),
                                           C.POINTER(StepPlan)]),
         "chorus_denoise_schedule_stored": (i32, [f32, f32, i32, C.POINTER(SchedParams), C.POINTER(i32), i32, C.POINTER(i32),
@@ -226,6 +228,27 @@ def chorus_cache_lookup(cache_emb, query, tau, out=None, ws=None):
     _status("chorus_cache_lookup", lib.chorus_cache_lookup(_p(cache_emb) if N else C.c_void_p(0), N, d, _p(query),
                                                            float(tau), _p(out), _p(ws), ws.numel(), _stream()))
     return out
+
+
+def chorus_cache_lookup_batch(cache_emb, queries, tau, k=1, ws=None):
+    """Top-k entries for each row of queries: (index [Q, k] int32, score [Q, k] fp32, hit [Q] int32) on the device."""
+    lib = load()
+    _chk(cache_emb, torch.float32, "cache_emb")
+    _chk(queries, torch.float32, "queries")
+    N, d = cache_emb.shape
+    Q = queries.shape[0]
+    if queries.dim() != 2 or queries.shape[1] != d:
+        raise TypeError("queries: expected [Q, d]")
+    dev = queries.device
+    idx = torch.empty(Q, k, dtype=torch.int32, device=dev)
+    sc = torch.empty(Q, k, dtype=torch.float32, device=dev)
+    hit = torch.empty(Q, dtype=torch.int32, device=dev)
+    if ws is None:
+        ws = _ws(lib.chorus_cache_lookup_batch_workspace_bytes(N, d, Q), dev)
+    _status("chorus_cache_lookup_batch",
+            lib.chorus_cache_lookup_batch(cache_emb.data_ptr() if N else 0, N, d, _p(queries), Q, float(tau), int(k), _p(idx),
+                                          _p(sc), _p(hit), _p(ws), ws.numel(), _stream()))
+    return idx, sc, hit
 
 
 def lookup_result(out):

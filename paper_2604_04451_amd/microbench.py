@@ -62,6 +62,12 @@ def main():
     ws = torch.empty(1 << 16, dtype=torch.uint8, device=DEV)
     med, best = timeit(lambda i: B.chorus_cache_lookup(caches[i % 10], q, 0.75, out, ws), n)
     report("cache_lookup 4096x4096 fp32 (2 launches)", N * d * 4 + d * 4, med, best)
+    # the same scan for a batch of queries with top-8 candidates each (the cache is streamed once per 32 queries)
+    for Q in (1, 16, 32):
+        qs = torch.randn(Q, d, device=DEV, generator=g)
+        wsb = torch.empty(B.load().chorus_cache_lookup_batch_workspace_bytes(N, d, Q), dtype=torch.uint8, device=DEV)
+        med, best = timeit(lambda i: B.chorus_cache_lookup_batch(caches[i % 10], qs, 0.75, 8, wsb), n)
+        report(f"cache_lookup_batch Q={Q} k=8 (2 launches)", N * d * 4 + Q * d * 4, med, best)
     del caches
 
     # ---- latent-sized kernels: 24 triples of 8.4 MB

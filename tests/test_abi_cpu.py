@@ -215,3 +215,20 @@ def test_schedule_with_stored_depths_matches_oracle(N):
                 assert slot == (stored.index(k1) if k1 > 0 else -1)
                 for (s, gk, go), (os_, ogk, ogo) in zip(plan, oplan):
                     assert s == os_ and gk == np.float32(ogk) and go == np.float32(ogo)
+
+
+def test_lookup_batch_validates():
+    lib = P.load()
+    null, p16 = C.c_void_p(0), C.c_void_p(16)
+    need = lib.chorus_cache_lookup_batch_workspace_bytes(4096, 4096, 32)
+    assert need > lib.chorus_cache_lookup_batch_workspace_bytes(4096, 4096, 16) > 0
+    assert lib.chorus_cache_lookup_batch_workspace_bytes(-1, 8, 1) == 0
+    call = lambda **k: lib.chorus_cache_lookup_batch(k.get("cache", p16), k.get("N", 8), k.get("d", 8), k.get("q", p16),
+                                                      k.get("Q", 2), 0.5, k.get("k", 1), p16, p16, p16, k.get("ws", p16),
+                                                      k.get("wsb", 1 << 30), null)
+    assert call(d=6) == B.E_SHAPE
+    assert call(k=0) == B.E_ARG and call(k=2000) == B.E_ARG
+    assert call(N=-1) == B.E_ARG and call(q=null) == B.E_ARG and call(cache=null) == B.E_ARG
+    assert call(cache=C.c_void_p(8)) == B.E_ARG                   # not 16-byte aligned
+    assert call(ws=null) == B.E_WORKSPACE and call(wsb=16) == B.E_WORKSPACE
+    assert call(Q=0) == B.OK

@@ -185,3 +185,75 @@ def test_blend_full_shape():
     print("[case] blend 1.3B latent bernoulli", flush=True)
     _blend_case(bs.latent_shape, bs.grid, synth.bernoulli_mask(bs.L, 0.4, 0))
     _blend_case(bs.latent_shape, bs.grid, np.zeros(bs.L, np.uint8), inplace=True)
+
+
+# ------------------------------------------------------------------ batched top-k retrieval
+
+def _check_topk(cache, queries, tau, k):
+    N, d = cache.shape
+    idx, sc, hit = P.chorus_cache_lookup_batch(dev_f32(cache).reshape(cache.shape), dev_f32(queries), tau, k)
+    idx, sc, hit = host(idx), host(sc), host(hit)
+    oidx, osc, ohit = O.cache_lookup_topk(cache, queries, tau, k)
+    tol = 4e-7 * max(8.0, math.sqrt(d))
+    for q in range(queries.shape[0]):
+        s = O.cosine_scores(cache, queries[q])
+        n_valid = min(k, N)
+        assert (idx[q, n_valid:] == -1).all() and np.isneginf(sc[q, n_valid:]).all()
+        got = idx[q, :n_valid]
+        assert len(set(got.tolist())) == n_valid and (got >= 0).all() and (got < N).all()
+        for r in range(n_valid):
+            j = int(got[r])
+            if np.isfinite(s[j]):
+                assert abs(sc[q, r] - s[j]) <= tol, (q, r, sc[q, r], s[j])
+            else:
+                assert sc[q, r] == s[j]
+            if r + 1 < n_valid:                                   # descending score, equal scores by index
+                assert sc[q, r] > sc[q, r + 1] or (sc[q, r] == sc[q, r + 1] and got[r] < got[r + 1])
+            # position r holds the oracle's entry unless that entry is within rounding of a neighbour in the order
+            oj = int(oidx[q, r])
+            if j != oj:
+                assert np.isfinite(osc[q, r]) and abs(s[j] - osc[q, r]) <= 2 * tol, (q, r, j, oj)
+        if n_valid and np.isfinite(osc[q, 0]) and abs(osc[q, 0] - tau) > tol:
+            assert bool(hit[q]) == bool(ohit[q])
+        if n_valid == 0 or not np.isfinite(osc[q, 0]):
+            assert hit[q] == 0
+    return idx, sc, hit
+
+
+def test_lookup_batch_edges():
+    print("[case] lookup_batch edges", flush=True)
+    cache = synth.cache_embeddings(64, 512, seed=3)
+    cache[40] = cache[7]                      # equal rows: equal scores, the lower index first
+    cache[63] = 2.0 * cache[7]
+    cache[11] = 0.0                           # zero norm: -inf, after everything else
+    queries = np.stack([cache[7], synth.cache_query(cache, seed=3, near=20), synth.cache_query(cache, seed=3),
+                        np.zeros(512, np.float32)])
+    idx, sc, hit = _check_topk(cache, queries, 0.75, 5)
+    assert list(idx[0, :3]) == [7, 40, 63] and sc[0, 0] == sc[0, 1] == sc[0, 2] and hit[0] == 1
+    assert idx[1, 0] == 20 and hit[1] == 1 and hit[2] == 0
+    assert list(idx[3]) == [0, 1, 2, 3, 4] and np.isneginf(sc[3]).all() and hit[3] == 0
+    # the zero-norm row comes last when k covers the whole cache
+    idx, sc, hit = _check_topk(cache, queries[:2], 0.75, 64)
+    assert idx[0, 63] == 11 and np.isneginf(sc[0, 63])
+    # k beyond the cache size, one entry, an empty cache, one query, 33 queries (two passes)
+    _check_topk(cache[:3], queries, 0.75, 5)
+    _check_topk(cache[:1], queries[:1], 0.75, 1)
+    _check_topk(cache[:0], queries, 0.75, 2)
+    many = np.stack([synth.cache_query(cache, seed=3, near=(3 * t) % 64 if t % 3 else None, trial=t) for t in range(33)])
+    _check_topk(cache, many, 0.75, 3)
+    # column 0 against the single-query entry point (these queries have no near ties at the top)
+    idx1, sc1, hit1 = _check_topk(cache, queries, 0.75, 1)
+    for t in range(4):
+        j, m, h = _lookup(cache, queries[t])
+        assert (j, h) == (int(idx1[t, 0]), bool(hit1[t]))
+        assert m == sc1[t, 0] or abs(m - sc1[t, 0]) <= 4e-7 * math.sqrt(512)
+
+
+@pytest.mark.parametrize("N,d,Q,k", [(1000, 768, 5, 4), (257, 4, 16, 8), (33, 2052, 17, 2), (4096, 4096, 32, 8),
+                                     (4096, 4096, 1, 1), (70000, 256, 32, 16)])
+def test_lookup_batch_shapes(N, d, Q, k):
+    print(f"[case] lookup_batch N={N} d={d} Q={Q} k={k}", flush=True)
+    cache = synth.cache_embeddings(N, d, seed=1)
+    queries = np.stack([synth.cache_query(cache, seed=1, near=(N // 3 + 17 * t) % N if t % 4 else None, trial=t)
+                        for t in range(Q)])
+    _check_topk(cache, queries, 0.75, k)
