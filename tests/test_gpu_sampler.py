@@ -233,3 +233,51 @@ def test_head_update_solver_full_shape_token_sampled():
     np.testing.assert_array_equal(got[Mse], SL[Mse])
     Me = O.expand_token_mask(edit, bs.grid, bs.patch, bs.C).astype(bool)
     assert np.isfinite(got).all() and (got[Me] != lat[Me]).mean() > 0.99
+
+
+def test_denoise_run_region_stage_first_and_fifty_steps():
+    """Two schedules the 4-step default never produces: (a) a hit whose region stage starts at step 0 (no reused step
+    before it, so Eq. 6 needs its own pass over the tokens outside M_see), Euler and multistep; (b) the 50-step
+    configuration with guidance (threshold 0.65, Sec. 4.1 / Table 1) on the small model."""
+    bs = synth.SHAPES["c1"]
+    N = 16
+    cache = synth.cache_embeddings(N, bs.cache_d, seed=0)
+    cache_lat = synth.normal(0, "cache_lat", (N,) + bs.latent_shape)
+    noise = synth.latent(bs, 0, "noise", std=1.0)
+    T, Hg, Wg = bs.grid
+    see = synth.box_mask(bs.grid, T, Hg * 4 // 5, Wg // 2, 0, 1, 2)
+    edit = synth.box_mask(bs.grid, T, Hg * 4 // 5 - 2, Wg // 2 - 2, 0, 2, 3)
+    q = synth.cache_query(cache, seed=0, near=5)
+    ks_of = lambda gk: np.full(bs.Lt, gk)
+    # (a)
+    print("[case] denoise_run with the region stage at step 0 (c1)", flush=True)
+    md = Model(bs, 2)
+    sched = dict(a1=0.0, b1=0.0, a2=0.5, b2=0.0, gamma_override=1.5)
+    for order in (1, 2):
+        sig = md.sigmas if order == 1 else _shifted(4)
+        dl = dev_f32(noise)
+        res = B.chorus_denoise_run(md.model, md.arr, md.dglue, dl, dev_f32(cache), dev_f32(cache_lat), dev_f32(q), 0.75, sig,
+                                   md.d_tmods, md.d_theads, md.d_ctx, mask_see=_u8(see), mask_edit=_u8(edit), sched=sched,
+                                   solver_order=order)
+        K1, K2, plan = O.denoise_schedule(float(np.float32(res["score"])), float(np.float32(0.75)), 4, sched)
+        assert res["hit"] and (res["K1"], res["K2"]) == (K1, K2) == (0, 2)
+        run = O.run_schedule if order == 1 else (lambda *a, **k: O.run_schedule_dpmpp(*a, order=2, **k))
+        ref = run(plan, sig, noise, cache_lat[5], md.blocks, md.gw, bs, md.ctx, md.t_mods, md.t_heads, mask_see=see,
+                  mask_edit=edit, key_scale_of=ks_of)
+        check(host(dl), ref, f"region stage first, solver order {order}")
+    # (b)
+    print("[case] denoise_run 50 steps with guidance (c1)", flush=True)
+    md = Model(bs, 2, n_steps=50)
+    sig = _shifted(50, top=0.999)
+    d_ctx_u, ctx_u = _uncond(md)
+    dl = dev_f32(noise)
+    res = B.chorus_denoise_run(md.model, md.arr, md.dglue, dl, dev_f32(cache), dev_f32(cache_lat), dev_f32(q), 0.65, sig,
+                               md.d_tmods, md.d_theads, md.d_ctx, mask_see=_u8(see), mask_edit=_u8(edit), solver_order=2,
+                               text_ctx_uncond=d_ctx_u, guidance=2.0)
+    K1, K2, plan = O.denoise_schedule(float(np.float32(res["score"])), float(np.float32(0.65)), 50)
+    assert res["hit"] and (res["K1"], res["K2"]) == (K1, K2) and 1 <= K1 < K2 < 50
+    print(f"[info] 50-step plan: K1={K1} K2={K2}", flush=True)
+    ref = O.run_schedule_dpmpp(plan, sig, noise, cache_lat[5], md.blocks, md.gw, bs, md.ctx, md.t_mods, md.t_heads, order=2,
+                               text_ctx_uncond=ctx_u, guidance=2.0, mask_see=see, mask_edit=edit,
+                               key_scale_of=lambda gk: np.full(bs.Lt, gk))
+    check(host(dl), ref, "50-step run with guidance")
