@@ -471,6 +471,30 @@ def text_project(text_emb, gw):
     return linear(gelu_tanh(linear(text_emb, gw["w_text1"], gw["b_text1"])), gw["w_text2"], gw["b_text2"])
 
 
+def sinusoidal_features(t, freq_dim):
+    """[cos(t w_i), sin(t w_i)] with w_i = 10000^(-i / half), i < half = freq_dim / 2."""
+    half = freq_dim // 2
+    w = np.power(10000.0, -np.arange(half, dtype=F64) / half)
+    a = float(t) * w
+    return np.concatenate([np.cos(a), np.sin(a)])
+
+
+def silu(x):
+    x = np.asarray(x, F64)
+    return x / (1.0 + np.exp(-x))
+
+
+def time_mod(t, tw, D, freq_dim=256):
+    """Timestep injection (Sec. 2.1 / Fig. 2 name it; the arithmetic is the Wan2.1-shaped one):
+    e = W2 silu(W1 f(t) + b1) + b2 with f the sinusoidal features; the six modulation rows of every
+    block are t_mod = reshape(Wp silu(e) + bp, [6, D]); the head takes e itself in both of its rows."""
+    f = sinusoidal_features(t, freq_dim)
+    e = linear(silu(linear(f, tw["w_t1"], tw["b_t1"])), tw["w_t2"], tw["b_t2"])
+    t_mod = linear(silu(e), tw["w_tp"], tw["b_tp"]).reshape(6, D)
+    t_head = np.stack([e, e])
+    return t_mod, t_head
+
+
 def patch_embed(patches, gw):
     return linear(patches, gw["w_patch"], gw["b_patch"])
 

@@ -188,6 +188,20 @@ def glue_weights(shape: BlockShape, seed: int = 0, std: float = 0.02) -> dict:
     return w
 
 
+def time_weights(shape: BlockShape, seed: int = 0, freq_dim: int = 256, std: float = 0.02) -> dict:
+    """Weights of the timestep embedding: two layers on the sinusoidal features, then the projection to the six
+    modulation rows of a block. Biases are non-zero so that every term matters."""
+    D = shape.D
+    return {
+        "w_t1": round_bf16(normal(seed, "time.w_t1", (D, freq_dim), std)),
+        "b_t1": normal(seed, "time.b_t1", (D,), std),
+        "w_t2": round_bf16(normal(seed, "time.w_t2", (D, D), std)),
+        "b_t2": normal(seed, "time.b_t2", (D,), std),
+        "w_tp": round_bf16(normal(seed, "time.w_tp", (6 * D, D), std)),
+        "b_tp": normal(seed, "time.b_tp", (6 * D,), std),
+    }
+
+
 def latent(shape: BlockShape, seed: int = 0, name: str = "latent", std: float | None = None) -> np.ndarray:
     return normal(seed, name, shape.latent_shape, shape.latent_std if std is None else std)
 

@@ -889,3 +889,33 @@ def test_lookup_topk_brute_force_and_reductions():
     for qi in range(queries.shape[0]):
         b = O.cache_lookup_topk(cache, queries[qi:qi + 1], 0.6, 3)
         assert (a[0][qi] == b[0][0]).all() and (a[1][qi] == b[1][0]).all() and a[2][qi] == b[2][0]
+
+
+# ------------------------------------------------------------------ timestep modulation
+
+def test_time_mod_vs_torch_and_closed_forms():
+    bs = synth.BlockShape("tiny", D=32, H=2, dh=16, F=48, Lt=4, text_dim=24, grid=(2, 2, 3), C=2)
+    tw = synth.time_weights(bs, 0, freq_dim=16, std=0.3)
+    f0 = O.sinusoidal_features(0.0, 16)
+    np.testing.assert_array_equal(f0, np.concatenate([np.ones(8), np.zeros(8)]))        # cos 0 = 1, sin 0 = 0
+    f = O.sinusoidal_features(37.5, 16)
+    for i in range(8):                                                                    # written out with math.*
+        w = 10000.0 ** (-i / 8)
+        assert abs(f[i] - math.cos(37.5 * w)) < 1e-12 and abs(f[8 + i] - math.sin(37.5 * w)) < 1e-12
+    np.testing.assert_allclose(f[:8] ** 2 + f[8:] ** 2, 1.0, atol=1e-12)
+    assert f[0] == math.cos(37.5) and abs(f[7] - math.cos(37.5 * 10000.0 ** (-7 / 8))) < 1e-12
+    np.testing.assert_allclose(O.silu(np.array([-2.0, 0.0, 3.0])), TF.silu(torch.tensor([-2.0, 0.0, 3.0], dtype=torch.float64)).numpy(),
+                               atol=1e-15)
+    t_mod, t_head = O.time_mod(421.0, tw, bs.D, 16)
+    T = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    ft = torch.cat([torch.cos(421.0 * T(10000.0 ** (-np.arange(8) / 8))), torch.sin(421.0 * T(10000.0 ** (-np.arange(8) / 8)))])
+    e = TF.linear(TF.silu(TF.linear(ft, T(tw["w_t1"]), T(tw["b_t1"]))), T(tw["w_t2"]), T(tw["b_t2"]))
+    tm = TF.linear(TF.silu(e), T(tw["w_tp"]), T(tw["b_tp"])).reshape(6, bs.D)
+    np.testing.assert_allclose(t_mod, tm.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(t_head, torch.stack([e, e]).numpy(), rtol=0, atol=1e-12)
+    assert t_mod.shape == (6, bs.D) and t_head.shape == (2, bs.D)
+    # row r of t_mod comes from rows [r D, (r + 1) D) of the projection
+    np.testing.assert_allclose(t_mod[4], O.linear(O.silu(t_head[0]), tw["w_tp"][4 * bs.D:5 * bs.D], tw["b_tp"][4 * bs.D:5 * bs.D]),
+                               atol=1e-12)
+    # different timesteps give different modulation
+    assert np.abs(O.time_mod(420.0, tw, bs.D, 16)[0] - t_mod).max() > 1e-4
