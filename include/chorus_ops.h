@@ -151,6 +151,29 @@ int32_t chorus_head_update_solver(float* latent, const float* x, const float* x_
                                   const uint8_t* mask_edit, int32_t D, int32_t C, int32_t T, int32_t Hl, int32_t Wl,
                                   int32_t ph, int32_t pw, void* ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------------
+ * Timestep injection (Sec. 2.1, Fig. 2): the projected timestep embedding of one step, i.e.
+ * the t_mod [6, D] and t_head [2, D] inputs of the block, step and run calls.
+ *   f = [cos(t w_i), sin(t w_i)], w_i = 10000^(-i / half), half = freq_dim / 2
+ *   e = W2 silu(W1 f + b1) + b2;  t_mod = reshape(Wp silu(e) + bp, [6, D]);  t_head = [e, e]
+ *   weights: bf16 [out, in] (w_t1 [D, freq_dim], w_t2 [D, D], w_tp [6 D, D]), fp32 biases (NULL = 0)
+ *   t_mod, t_head dev fp32 (written); ws: chorus_time_mod_workspace_bytes(D, freq_dim)
+ * freq_dim and D multiples of 8. For a fixed schedule the results are per-model constants:
+ * compute them once per noise level and keep them.
+ * ------------------------------------------------------------------------ */
+typedef struct {
+  const uint16_t* w_t1;
+  const float* b_t1;
+  const uint16_t* w_t2;
+  const float* b_t2;
+  const uint16_t* w_tp;
+  const float* b_tp;
+} chorus_time_weights;
+
+size_t chorus_time_mod_workspace_bytes(int32_t D, int32_t freq_dim);
+int32_t chorus_time_mod(float t, int32_t freq_dim, int32_t D, const chorus_time_weights* w, float* t_mod, float* t_head,
+                        void* ws, size_t ws_bytes, void* stream);
+
 size_t chorus_text_project_workspace_bytes(int32_t Lt, int32_t D);
 int32_t chorus_text_project(const uint16_t* text, int32_t Lt, int32_t text_dim, int32_t D, const uint16_t* w1,
                             const float* b1, const uint16_t* w2, const float* b2, uint16_t* ctx, void* ws,

@@ -75,6 +75,10 @@ class SamplerCoef(C.Structure):
     _fields_ = [(n, C.c_float) for n in ("sigma_s", "rho", "A", "c0", "c1")]
 
 
+class TimeWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("w_t1", "b_t1", "w_t2", "b_t2", "w_tp", "b_tp")]
+
+
 class RunResult(C.Structure):
     _fields_ = [("index", C.c_int32), ("score", C.c_float), ("hit", C.c_int32), ("K1", C.c_int32),
                 ("K2", C.c_int32), ("Ls", C.c_int32)]
@@ -167,6 +171,8 @@ def _bind_ops(lib):
         "chorus_mask_pooled_extent": (i32, [i32, i32, i32]),
         "chorus_mask_project": (i32, [vp, i32, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]),
         "chorus_mask_hierarchy": (i32, [vp, i32, i32, i32, C.POINTER(i32), C.POINTER(i32), vp, vp, vp]),
+        "chorus_time_mod_workspace_bytes": (sz, [i32, i32]),
+        "chorus_time_mod": (i32, [f32, i32, i32, C.POINTER(TimeWeights), vp, vp, vp, sz, vp]),
         "chorus_mfma_ceiling_workspace_bytes": (sz, []),
         "chorus_mfma_ceiling": (i32, [i32, i32, i32, C.POINTER(C.c_double), vp, sz, vp]),
         "chorus_prof_enable": (i32, [i32]),
@@ -855,3 +861,35 @@ def chorus_mfma_ceiling(normal_data=True, mix=0, launches=20, device="cuda"):
     _status("chorus_mfma_ceiling", lib.chorus_mfma_ceiling(int(bool(normal_data)), int(mix), int(launches), C.byref(out),
                                                            _p(ws), ws.numel(), _stream()))
     return out.value
+
+
+class DeviceTime:
+    """Device copies of the timestep-embedding weights and the struct of pointers to them."""
+
+    def __init__(self, tw: dict, device="cuda"):
+        import numpy as np
+        self.tensors = {}
+        for k, v in tw.items():
+            a = np.ascontiguousarray(v, dtype=np.float32)
+            t = torch.from_numpy(a).to(device)
+            self.tensors[k] = t.to(torch.bfloat16).contiguous() if k.startswith("w_") else t
+        self.freq_dim = tw["w_t1"].shape[1]
+        self.D = tw["w_t1"].shape[0]
+        self.cstruct = TimeWeights(*[self.tensors[n].data_ptr() for n in ("w_t1", "b_t1", "w_t2", "b_t2", "w_tp", "b_tp")])
+
+
+def chorus_time_mod(t, tw: DeviceTime, t_mod=None, t_head=None):
+    """(t_mod [6, D], t_head [2, D]) of one timestep value."""
+    lib = load()
+    dev = tw.tensors["w_t1"].device
+    D = tw.D
+    if t_mod is None:
+        t_mod = torch.empty(6, D, dtype=torch.float32, device=dev)
+    if t_head is None:
+        t_head = torch.empty(2, D, dtype=torch.float32, device=dev)
+    _chk(t_mod, torch.float32, "t_mod", (6, D))
+    _chk(t_head, torch.float32, "t_head", (2, D))
+    ws = _ws(lib.chorus_time_mod_workspace_bytes(D, tw.freq_dim), dev)
+    _status("chorus_time_mod", lib.chorus_time_mod(float(t), tw.freq_dim, D, C.byref(tw.cstruct), _p(t_mod), _p(t_head),
+                                                   _p(ws), ws.numel(), _stream()))
+    return t_mod, t_head

@@ -232,3 +232,19 @@ def test_lookup_batch_validates():
     assert call(cache=C.c_void_p(8)) == B.E_ARG                   # not 16-byte aligned
     assert call(ws=null) == B.E_WORKSPACE and call(wsb=16) == B.E_WORKSPACE
     assert call(Q=0) == B.OK
+
+
+def test_time_mod_validates():
+    lib = P.load()
+    null, p16 = C.c_void_p(0), C.c_void_p(16)
+    tw = B.TimeWeights(16, 16, 16, 16, 16, 16)
+    need = lib.chorus_time_mod_workspace_bytes(256, 256)
+    assert need > 0 and lib.chorus_time_mod_workspace_bytes(0, 256) == 0
+    call = lambda **k: lib.chorus_time_mod(500.0, k.get("F", 256), k.get("D", 256), k.get("w", C.byref(tw)), k.get("tm", p16),
+                                           p16, k.get("ws", p16), k.get("wsb", need), null)
+    assert call(w=None) == B.E_ARG and call(tm=null) == B.E_ARG and call(D=0) == B.E_ARG
+    assert call(F=12) == B.E_SHAPE and call(D=100) == B.E_SHAPE
+    assert call(tm=C.c_void_p(4)) == B.E_ARG
+    assert call(ws=null) == B.E_WORKSPACE and call(wsb=8) == B.E_WORKSPACE
+    bad = B.TimeWeights(16, 16, 0, 16, 16, 16)
+    assert call(w=C.byref(bad)) == B.E_ARG

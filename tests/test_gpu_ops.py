@@ -171,3 +171,18 @@ def test_mfma_ceiling_runs_and_orders():
     mix = B.chorus_mfma_ceiling(True, 3, 5)
     print(f"[info] mfma ceiling TFLOP/s: ones {ones:.0f}, normal {rnd:.0f}, normal + LDS operand + exp2 {mix:.0f}", flush=True)
     assert 300.0 < mix < rnd * 1.02 and rnd < ones * 1.02 and ones < 2700.0
+
+
+@pytest.mark.parametrize("name,freq_dim", [("c1", 256), ("wan1p3b_small", 256), ("c1", 64)])
+def test_time_mod(name, freq_dim):
+    print(f"[case] time_mod {name} freq_dim={freq_dim}", flush=True)
+    bs = synth.SHAPES[name]
+    tw = synth.time_weights(bs, 0, freq_dim=freq_dim)
+    dtw = B.DeviceTime(tw)
+    for t in (0.0, 1.0, 421.5, 999.0):
+        t_mod, t_head = B.chorus_time_mod(t, dtw)
+        rm, rh = O.time_mod(float(np.float32(t)), tw, bs.D, freq_dim)
+        # fp32 sincos of arguments up to 1000 rad, then three fp32 matrix-vector products
+        check(host(t_mod), rm, f"t_mod t={t}", max_abs=2e-4 * max(1.0, np.abs(rm).max()), rel_l2=2e-4)
+        check(host(t_head), rh, f"t_head t={t}", max_abs=2e-4 * max(1.0, np.abs(rh).max()), rel_l2=2e-4)
+        assert torch.equal(t_head[0], t_head[1])
