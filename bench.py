@@ -201,6 +201,18 @@ def main():
         "normal_lds_operand": round(B.chorus_mfma_ceiling(True, 1, 20), 1),
         "normal_lds_operand_exp2": round(B.chorus_mfma_ceiling(True, 3, 20), 1),
     }
+    # and what a plain streaming copy sustains (read + write of 2 x 268 MB, rotating buffers), for the HBM-bound steps
+    cp = [torch.empty(2, 67108864, dtype=torch.float32, device=dev) for _ in range(3)]
+    for i in range(6):
+        B.chorus_stage1_copy(cp[i % 3][1], cp[i % 3][0])
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(30):
+        B.chorus_stage1_copy(cp[i % 3][1], cp[i % 3][0])
+    e1.record()
+    torch.cuda.synchronize()
+    out["hbm_copy_ceiling_gbs"] = round(30 * 2 * 67108864 * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    del cp
     if args.plain:
         torch.cuda.synchronize()
         t0 = time.perf_counter()
