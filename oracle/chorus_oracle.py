@@ -24,6 +24,10 @@ What the paper fixes and what it leaves open
   arithmetic here is the Wan2.1-shaped block the benchmark configurations name
   (AdaLN modulation, RMSNorm on q/k, 3-D RoPE, tanh-GELU FFN); each choice is
   stated at the function that makes it.
+* Cache update (Sec. 3.1): `cache_insert`; several stored depths per entry enter the schedule as
+  `stored_steps` (K1 snaps to a stored depth). `cache_lookup_topk` is the batched retrieval with
+  candidates; its column 0 is `cache_lookup`.
+* Timestep injection (Sec. 2.1, Fig. 2): `time_mod`, Wan2.1-shaped like the block.
 * The sampler (Sec. 4.1: DPM++ with default settings, no formulas given): the published
   DPM-Solver++ multistep update of order <= 2 in data-prediction form on the rectified-flow
   path, plus classifier-free guidance for the models that use it. The Euler update of
