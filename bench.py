@@ -174,8 +174,7 @@ def main():
     attn_tflops = per_req_attn_flops * args.steps / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else 0.0
     plan_flops = n_blocks * (block_flops(Ls, D, F, Lt) + 2 * block_flops(L, D, F, Lt))
     out = {
-        "metric": "ms per 4-step video denoise (Chorus schedule: reuse, region step, 2 full steps) + self-attn TFLOP/s, "
-                  "Wan-1.3B-shape 480p block",
+        "metric": "ms per 4-step video denoise + self-attn TFLOP/s, Wan-1.3B-shape 480p block",
         "value": round(ms, 3), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 3), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
