@@ -248,3 +248,34 @@ def test_time_mod_validates():
     assert call(ws=null) == B.E_WORKSPACE and call(wsb=8) == B.E_WORKSPACE
     bad = B.TimeWeights(16, 16, 0, 16, 16, 16)
     assert call(w=C.byref(bad)) == B.E_ARG
+
+
+def test_denoise_run_validates_before_any_launch():
+    lib = P.load()
+    bs = B.make_block_shape(128, 2, 64, 256, 8, (1, 2, 2))
+    ms = B.make_model_shape(bs, (16, 1, 4, 4), (2, 2), 0)
+    gw = B.GlueWeights(16, 16, 16, 16, 16)
+    res = B.RunResult()
+    sig = (C.c_float * 5)(1.0, 0.75, 0.5, 0.25, 0.0)
+    need = lib.chorus_denoise_run_workspace_bytes(C.byref(ms), 4)
+    assert need > 0
+
+    def call(ws=C.c_void_p(256), wsb=None, **kw):
+        f = dict(cache_emb=16, cache_latents=16, cache_N=4, cache_d=8, query=16, tau=0.75, sched=None, n_steps=4, sigmas=sig,
+                 t_mods=16, t_heads=16, text_ctx=16, tdiff=0, mask_see=0, mask_edit=0, store_slot=-1, store_after=0,
+                 latent_steps=None, n_latent_steps=0, solver_order=1, text_ctx_uncond=0, guidance=1.0)
+        f.update(kw)
+        rq = B.Request(**f)
+        return lib.chorus_denoise_run(C.byref(ms), None, C.byref(gw), C.byref(rq), C.c_void_p(16), C.byref(res), ws,
+                                      need if wsb is None else wsb, None)
+
+    assert call(solver_order=3) == B.E_ARG and call(solver_order=-1) == B.E_ARG
+    assert call(store_slot=4, store_after=1) == B.E_ARG                      # slot outside the cache
+    assert call(store_slot=1, store_after=0) == B.E_ARG and call(store_slot=1, store_after=5) == B.E_ARG
+    steps = lambda *v: (C.c_int32 * len(v))(*v)
+    assert call(latent_steps=steps(1, 1), n_latent_steps=2) == B.E_ARG       # a depth listed twice
+    assert call(latent_steps=steps(0), n_latent_steps=1) == B.E_ARG          # depth 0 is the noise itself
+    assert call(latent_steps=steps(5), n_latent_steps=1) == B.E_ARG          # beyond the schedule
+    assert call(latent_steps=steps(1), n_latent_steps=0) == B.E_ARG
+    assert call(query=0) == B.E_ARG and call(sigmas=None) == B.E_ARG and call(n_steps=-1) == B.E_ARG
+    assert call(ws=None) == B.E_WORKSPACE and call(wsb=need - 1) == B.E_WORKSPACE
