@@ -147,8 +147,14 @@ __global__ __launch_bounds__(256) void blend_vec4_kernel(float4* out, const floa
       for (int e = 0; e < 4; ++e) m |= (mrow[(x + e) / pw] != 0) << e;
     }
     sel[u] = m;
-    if (m != 0) a[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(&Lc[v]));
-    if (m != 15) b[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(&SL[v]));
+  }
+  // all mask bytes are requested before the first data load depends on one of them
+#pragma unroll
+  for (int u = 0; u < kBlendU; ++u) {
+    const unsigned v = v0 + u * stride;
+    if (sel[u] < 0) continue;
+    if (sel[u] != 0) a[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(&Lc[v]));
+    if (sel[u] != 15) b[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(&SL[v]));
   }
 #pragma unroll
   for (int u = 0; u < kBlendU; ++u) {
