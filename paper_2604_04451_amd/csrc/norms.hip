@@ -87,6 +87,10 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
 
 // One wave per token row (rows >= L up to Lpad are written as zeros). Lanes own
 // 8-element chunks; chunk c covers dims [8c, 8c+8) of the D-wide row, inside one head.
+// NCH > 0: D == 512 * NCH and the row lives in registers: its loads are issued first, the rotation
+// angles are computed while they are in flight, and the row is read from HBM once. NCH == 0: any D % 8 == 0,
+// the row is read again (from cache) for the second pass.
+template <int NCH>
 __global__ __launch_bounds__(256) void qk_norm_rope_kernel(const uint16_t* __restrict__ in, long ld,
                                                            const float* __restrict__ gain, uint16_t* __restrict__ out,
                                                            long L, long Lpad, int H, int dh,
@@ -107,18 +111,11 @@ __global__ __launch_bounds__(256) void qk_norm_rope_kernel(const uint16_t* __res
     return;
   }
   const uint16_t* r = in + row * ld;
-  // pass 1: mean of squares
-  float ss = 0.f;
-  for (int c = lane; c < nchunk; c += 64) {
-    uint4 u = *reinterpret_cast<const uint4*>(r + c * 8);
-    uint32_t w[4] = {u.x, u.y, u.z, u.w};
+  u32x4 rv[NCH > 0 ? NCH : 1];
+  if (NCH > 0) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      float a = __uint_as_float(w[k] << 16), b = __uint_as_float(w[k] & 0xffff0000u);
-      ss += a * a + b * b;
-    }
+    for (int i = 0; i < NCH; ++i) rv[i] = *reinterpret_cast<const u32x4*>(r + (lane + 64 * i) * 8);
   }
-  const float rstd = rsqrtf(wave_sum(ss) / (float)D + kEps);
   if (rope) {
     // rotation angles depend on the pair index inside a head only: dh/2 <= 64 of them
     long n = token_idx ? (long)token_idx[row] : row;
@@ -140,9 +137,37 @@ __global__ __launch_bounds__(256) void qk_norm_rope_kernel(const uint16_t* __res
     }
     __builtin_amdgcn_wave_barrier();
   }
-  for (int c = lane; c < nchunk; c += 64) {
-    uint4 u = *reinterpret_cast<const uint4*>(r + c * 8);
-    uint32_t w[4] = {u.x, u.y, u.z, u.w};
+  // pass 1: mean of squares
+  float ss = 0.f;
+  if (NCH > 0) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        float a = __uint_as_float(rv[i][k] << 16), b = __uint_as_float(rv[i][k] & 0xffff0000u);
+        ss += a * a + b * b;
+      }
+  } else {
+    for (int c = lane; c < nchunk; c += 64) {
+      uint4 u = *reinterpret_cast<const uint4*>(r + c * 8);
+      uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        float a = __uint_as_float(w[k] << 16), b = __uint_as_float(w[k] & 0xffff0000u);
+        ss += a * a + b * b;
+      }
+    }
+  }
+  const float rstd = rsqrtf(wave_sum(ss) / (float)D + kEps);
+  const int iters = NCH > 0 ? NCH : (nchunk + 63) / 64;
+#pragma unroll
+  for (int it = 0; it < iters; ++it) {
+    const int c = lane + 64 * it;
+    if (NCH == 0 && c >= nchunk) break;
+    u32x4 u;
+    if (NCH > 0) u = rv[NCH > 0 ? it : 0];
+    else u = *reinterpret_cast<const u32x4*>(r + c * 8);
+    const uint32_t w[4] = {u[0], u[1], u[2], u[3]};
     const float4 ga = *reinterpret_cast<const float4*>(gain + c * 8);
     const float4 gb = *reinterpret_cast<const float4*>(gain + c * 8 + 4);
     const float gv[8] = {ga.x, ga.y, ga.z, ga.w, gb.x, gb.y, gb.z, gb.w};
@@ -241,8 +266,20 @@ int32_t chorus_qk_norm_rope(const uint16_t* in, int64_t ld, const float* gain, u
   if (rope && (gH <= 0 || gW <= 0)) return CHORUS_E_ARG;
   if (!aligned16(in) || !aligned16(out) || !aligned16(gain)) return CHORUS_E_ARG;
   hipStream_t s = (hipStream_t)stream;
-  hipLaunchKernelGGL(qk_norm_rope_kernel, dim3((unsigned)((Lpad + 3) / 4)), dim3(256), 0, s, in, (long)ld, gain, out,
+  const int D_ = H * dh;  // widths with a register-resident row: 512 elements per chunk round
+  if (D_ == 1536) {
+    hipLaunchKernelGGL(qk_norm_rope_kernel<3>, dim3((unsigned)((Lpad + 3) / 4)), dim3(256), 0, s, in, (long)ld, gain, out,
                      (long)L, (long)Lpad, H, dh, token_idx, gH, gW, rope);
+  } else if (D_ == 5120) {
+    hipLaunchKernelGGL(qk_norm_rope_kernel<10>, dim3((unsigned)((Lpad + 3) / 4)), dim3(256), 0, s, in, (long)ld, gain, out,
+                     (long)L, (long)Lpad, H, dh, token_idx, gH, gW, rope);
+  } else if (D_ == 512) {
+    hipLaunchKernelGGL(qk_norm_rope_kernel<1>, dim3((unsigned)((Lpad + 3) / 4)), dim3(256), 0, s, in, (long)ld, gain, out,
+                     (long)L, (long)Lpad, H, dh, token_idx, gH, gW, rope);
+  } else {
+    hipLaunchKernelGGL(qk_norm_rope_kernel<0>, dim3((unsigned)((Lpad + 3) / 4)), dim3(256), 0, s, in, (long)ld, gain, out,
+                     (long)L, (long)Lpad, H, dh, token_idx, gH, gW, rope);
+  }
   CHORUS_LAUNCH_CHECK();
   return CHORUS_OK;
 }
