@@ -44,7 +44,8 @@ int32_t chorus_gemm_set_variant(int32_t v);
 /* out bf16 [L, D] = LN(x) * (mul_base + mul0 + mul1) + (add0 + add1), LN over D without
  * affine, eps 1e-6; mul_base = 1 if plus_one else 0; mul1/add1 may be NULL.
  * AdaLN modulation: mul = scale rows of (table, t_mod), add = shift rows, plus_one = 1.
- * Affine LayerNorm: mul0 = weight, add0 = bias, plus_one = 0.  x dev [L, D] fp32. */
+ * Affine LayerNorm: mul0 = weight, add0 = bias, plus_one = 0.  x dev [L, D] fp32.
+ * D a multiple of 4, at most 8192 (CHORUS_E_SHAPE otherwise). */
 int32_t chorus_ln_modulate(const float* x, uint16_t* out, int64_t L, int32_t D, const float* mul0, const float* mul1,
                            const float* add0, const float* add1, int32_t plus_one, void* stream);
 

@@ -18,21 +18,47 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
                                                           const float* __restrict__ mul1,
                                                           const float* __restrict__ add0,
                                                           const float* __restrict__ add1, float mul_base) {
+  // the two modulation vectors are the same for every row: the workgroup combines them once into LDS
+  // ((base + mul0 + mul1) and (add0 + add1)) while the rows' loads are in flight
+  extern __shared__ __attribute__((aligned(16))) float s_tab[];  // [2][D]
   const int lane = threadIdx.x & 63;
-  const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= L) return;
+  const long row_raw = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const bool live = row_raw < L;
+  const long row = live ? row_raw : L - 1;  // a wave past the end keeps the barrier company and stores nothing
   const float4* xr = reinterpret_cast<const float4*>(x + row * (long)D);
   const int n4 = D >> 2;
   const float invD = 1.0f / (float)D;
   float mean, rstd;
   float4 v[NV > 0 ? NV : 1];
   if (NV > 0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) v[i] = xr[lane + 64 * i];
+  }
+  {
+    const float4* m0 = reinterpret_cast<const float4*>(mul0);
+    const float4* m1 = reinterpret_cast<const float4*>(mul1);
+    const float4* a0 = reinterpret_cast<const float4*>(add0);
+    const float4* a1 = reinterpret_cast<const float4*>(add1);
+    for (int i = threadIdx.x; i < n4; i += 256) {
+      float4 mu = m0[i];
+      mu.x += mul_base; mu.y += mul_base; mu.z += mul_base; mu.w += mul_base;
+      if (mul1) {
+        const float4 e = m1[i];
+        mu.x += e.x; mu.y += e.y; mu.z += e.z; mu.w += e.w;
+      }
+      float4 ad = a0[i];
+      if (add1) {
+        const float4 e = a1[i];
+        ad.x += e.x; ad.y += e.y; ad.z += e.z; ad.w += e.w;
+      }
+      reinterpret_cast<float4*>(s_tab)[i] = mu;
+      reinterpret_cast<float4*>(s_tab + D)[i] = ad;
+    }
+  }
+  if (NV > 0) {
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      v[i] = xr[lane + 64 * i];
-      s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
-    }
+    for (int i = 0; i < NV; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
     mean = wave_sum(s) * invD;
     float q = 0.f;
 #pragma unroll
@@ -56,31 +82,21 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
     }
     rstd = rsqrtf(wave_sum(q) * invD + kEps);
   }
+  __syncthreads();  // the combined vectors are in LDS
+  if (!live) return;
   uint2* orow = reinterpret_cast<uint2*>(out + row * (long)D);
-  const float4* m0 = reinterpret_cast<const float4*>(mul0);
-  const float4* m1 = reinterpret_cast<const float4*>(mul1);
-  const float4* a0 = reinterpret_cast<const float4*>(add0);
-  const float4* a1 = reinterpret_cast<const float4*>(add1);
   const int iters = NV > 0 ? NV : (n4 + 63) / 64;
 #pragma unroll
   for (int it = 0; it < iters; ++it) {
     int i = lane + 64 * it;
     if (NV == 0 && i >= n4) break;
     float4 t = NV > 0 ? v[NV > 0 ? it : 0] : xr[i];
-    float4 mu = m0[i];
-    if (mul1) {
-      float4 e = m1[i];
-      mu.x += e.x; mu.y += e.y; mu.z += e.z; mu.w += e.w;
-    }
-    float4 ad = a0[i];
-    if (add1) {
-      float4 e = a1[i];
-      ad.x += e.x; ad.y += e.y; ad.z += e.z; ad.w += e.w;
-    }
-    float r0 = (t.x - mean) * rstd * (mul_base + mu.x) + ad.x;
-    float r1 = (t.y - mean) * rstd * (mul_base + mu.y) + ad.y;
-    float r2 = (t.z - mean) * rstd * (mul_base + mu.z) + ad.z;
-    float r3 = (t.w - mean) * rstd * (mul_base + mu.w) + ad.w;
+    const float4 mu = reinterpret_cast<const float4*>(s_tab)[i];
+    const float4 ad = reinterpret_cast<const float4*>(s_tab + D)[i];
+    float r0 = (t.x - mean) * rstd * mu.x + ad.x;
+    float r1 = (t.y - mean) * rstd * mu.y + ad.y;
+    float r2 = (t.z - mean) * rstd * mu.z + ad.z;
+    float r3 = (t.w - mean) * rstd * mu.w + ad.w;
     orow[i] = make_uint2(pack_bf16x2(r0, r1), pack_bf16x2(r2, r3));
   }
 }
@@ -244,8 +260,10 @@ int32_t chorus_ln_modulate(const float* x, uint16_t* out, int64_t L, int32_t D, 
   hipStream_t s = (hipStream_t)stream;
   dim3 grid((unsigned)((L + 3) / 4)), block(256);
   float base = plus_one ? 1.0f : 0.0f;
+  const size_t tab_bytes = (size_t)2 * D * sizeof(float);
+  if (tab_bytes > 64 * 1024) return CHORUS_E_SHAPE;
 #define LAUNCH_LN(NV) \
-  hipLaunchKernelGGL((ln_modulate_kernel<NV>), grid, block, 0, s, x, out, (long)L, D, mul0, mul1, add0, add1, base)
+  hipLaunchKernelGGL((ln_modulate_kernel<NV>), grid, block, tab_bytes, s, x, out, (long)L, D, mul0, mul1, add0, add1, base)
   if (D == 256) LAUNCH_LN(1);
   else if (D == 1536) LAUNCH_LN(6);
   else if (D == 5120) LAUNCH_LN(20);
