@@ -37,9 +37,13 @@ int32_t chorus_gemm_bf16(const uint16_t* A, const uint16_t* W, int64_t M, int32_
                          void* out, const float* bias, const float* gate0, const float* gate1, float scale,
                          void* stream);
 
-/* Benchmark hook: 0 = default kernel choice, 1 = never use the direct-to-LDS 256x256 kernel, 2 = always use it
- * when the problem has at least 256 such tiles. Host only. */
-int32_t chorus_gemm_set_variant(int32_t v);
+/* chorus_gemm_bf16 with the tile kernel named by the caller, for tests and comparisons (every kernel is correct on
+ * every shape the call accepts; only the speed differs): kernel 0 = the default choice by problem size,
+ * 1 = 128 x 64 register-staged tiles, 2 = 256 x 128 register-staged tiles, 3 = 256 x 256 direct-to-LDS tiles.
+ * Anything else: CHORUS_E_ARG. */
+int32_t chorus_gemm_bf16_kernel(const uint16_t* A, const uint16_t* W, int64_t M, int32_t N, int32_t K, int32_t epilogue,
+                                void* out, const float* bias, const float* gate0, const float* gate1, float scale,
+                                int32_t kernel, void* stream);
 
 /* out bf16 [L, D] = LN(x) * (mul_base + mul0 + mul1) + (add0 + add1), LN over D without
  * affine, eps 1e-6; mul_base = 1 if plus_one else 0; mul1/add1 may be NULL.
@@ -74,7 +78,10 @@ int32_t chorus_v_transpose(const uint16_t* in, int64_t ld, uint16_t* out, int64_
  *   O   dev bf16 [Lq, H*dh] token-major
  *   col_scale dev [Lk] fp32 or NULL
  * dh in {64,128}; LkPad % 64 == 0, LkPad >= Lk >= 1; rows/cols beyond Lq/Lk are padding
- * (finite values). */
+ * (finite values).
+ * variant: 0 = the default choice (128-key tiles for col_scale == NULL, LkPad % 128 == 0 and Lk >= 2048, else
+ * 64-key tiles); 3 = 64-key tiles; 4 = 128-key tiles, CHORUS_E_SHAPE with a col_scale or LkPad % 128 != 0.
+ * Any other value: CHORUS_E_ARG. */
 int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O,
                          const float* col_scale, int64_t Lq, int64_t Lk, int64_t LqPad, int64_t LkPad, int32_t H,
                          int32_t dh, int32_t variant, void* stream);

@@ -140,7 +140,7 @@ def _bind_ops(lib):
     GW, MS = C.POINTER(GlueWeights), C.POINTER(ModelShape)
     ops = {
         "chorus_gemm_bf16": (i32, [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, f32, vp]),
-        "chorus_gemm_set_variant": (i32, [i32]),
+        "chorus_gemm_bf16_kernel": (i32, [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, f32, i32, vp]),
         "chorus_ln_modulate": (i32, [vp, vp, i64, i32, vp, vp, vp, vp, i32, vp]),
         "chorus_qk_norm_rope": (i32, [vp, i64, vp, vp, i64, i64, i32, i32, vp, i32, i32, i32, i32, vp]),
         "chorus_v_transpose": (i32, [vp, i64, vp, i64, i64, i32, vp]),
@@ -449,7 +449,7 @@ EPI_BF16, EPI_GELU_BF16, EPI_F32, EPI_RESID = 0, 1, 2, 3
 PROF_SELF_ATTN, PROF_CROSS_ATTN, PROF_GEMM, PROF_NORM = 0, 1, 2, 3
 
 
-def chorus_gemm_bf16(A, W, epilogue, out, bias=None, gate0=None, gate1=None, scale=1.0, M=None):
+def chorus_gemm_bf16(A, W, epilogue, out, bias=None, gate0=None, gate1=None, scale=1.0, M=None, kernel=0):
     lib = load()
     _chk(A, torch.bfloat16, "A")
     _chk(W, torch.bfloat16, "W")
@@ -463,6 +463,11 @@ def chorus_gemm_bf16(A, W, epilogue, out, bias=None, gate0=None, gate1=None, sca
         raise TypeError("out: wrong shape")
     for n, t in (("bias", bias), ("gate0", gate0), ("gate1", gate1)):
         _chk(t, torch.float32, n, (N,))
+    if kernel:
+        _status("chorus_gemm_bf16_kernel", lib.chorus_gemm_bf16_kernel(_p(A), _p(W), M, N, K, epilogue, _p(out), _p(bias),
+                                                                       _p(gate0), _p(gate1), float(scale), int(kernel),
+                                                                       _stream()))
+        return out
     _status("chorus_gemm_bf16", lib.chorus_gemm_bf16(_p(A), _p(W), M, N, K, epilogue, _p(out), _p(bias), _p(gate0),
                                                      _p(gate1), float(scale), _stream()))
     return out

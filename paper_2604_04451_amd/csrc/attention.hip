@@ -4,10 +4,10 @@
 // cross-attention with TGAA key amplification (Eq. 2: scaling key j by gamma_k
 // scales logit column j).
 //
-// Work split: a workgroup owns NW*QB*32 query rows of one head and sweeps all
-// keys in tiles of 64. K tiles [64][dh] and V^T tiles [dh][64] are staged through
-// LDS (double-buffered, rows padded by 16 bytes against bank conflicts) and shared
-// by the NW waves; each wave keeps QB blocks of 32 query rows entirely in registers.
+// Work split: a workgroup of 8 waves owns 256 query rows of one head (32 per wave, held in
+// registers) and sweeps all keys in tiles of 64 or 128. K tiles [keys][dh] and V^T tiles
+// [dh][keys] are staged through LDS (double-buffered, rows padded by 16 bytes against bank
+// conflicts) and shared by the 8 waves.
 //
 // The wave computes S^T = K Q^T, so a lane's 16 accumulator registers of a 32x32
 // block all belong to ONE query row (column l%32) and 16 different keys
@@ -26,239 +26,10 @@
 namespace chorus {
 namespace {
 
-constexpr int KT = 64;  // keys per tile
-
-template <int DH>
-struct AttnSmem {
-  static constexpr int KS = DH + 8;   // K row stride (elements)
-  static constexpr int VS = KT + 8;   // V^T row stride
-  uint16_t k[2][KT * KS];
-  uint16_t v[2][DH * VS];
-};
-
-template <int DH, int QB, int NW, bool COLSCALE>
-__global__ __launch_bounds__(NW * 64, NW / 4) void attention_kernel(
-    const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vt,
-    uint16_t* __restrict__ O, const float* __restrict__ col_scale, long Lq, long Lk, long LqPad, long LkPad, int H,
-    int n_qtiles, float scale_log2) {
-  constexpr int NT = NW * 64;
-  constexpr int KS = AttnSmem<DH>::KS, VS = AttnSmem<DH>::VS;
-  constexpr int K_LD = KT * (DH / 8) / NT;   // 16-byte chunks per thread per K tile
-  constexpr int V_LD = DH * (KT / 8) / NT;
-  constexpr int SK = DH / 16;                // MFMA k-steps over the head dim
-  constexpr int TD = DH / 32;                // 32-row blocks of O^T
-  constexpr int QROWS = NW * QB * 32;
-  static_assert(K_LD >= 1 && V_LD >= 1, "tile too small for the thread count");
-
-  extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
-  AttnSmem<DH>& sm = *reinterpret_cast<AttnSmem<DH>*>(smem_raw);
-
-  const int tile_id = xcd_remap(blockIdx.x, H * n_qtiles);
-  const int head = tile_id / n_qtiles;
-  const int qt = tile_id - head * n_qtiles;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int lrow = lane & 31, c = lane >> 5, lk = c * 8;
-  const long q_wave0 = (long)qt * QROWS + wave * (QB * 32);
-
-  const uint16_t* Kh = K + (long)head * LkPad * DH;
-  const uint16_t* Vh = Vt + (long)head * DH * LkPad;
-
-  // Q fragments (B operand of S^T = K Q^T): lane holds Q[q = lrow][16 s + 8 c .. +8]
-  bf16x8 qf[QB][SK];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    long q = q_wave0 + qb * 32 + lrow;
-    if (q > Lq - 1) q = Lq - 1;
-    const uint16_t* qp = Q + ((long)head * LqPad + q) * DH + lk;
-#pragma unroll
-    for (int s = 0; s < SK; ++s) qf[qb][s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
-  }
-
-  f32x16 o[QB][TD];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-    for (int t = 0; t < TD; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[qb][t][r] = 0.f;
-  float m_run[QB], l_run[QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    m_run[qb] = -INFINITY;
-    l_run[qb] = 0.f;
-  }
-
-  const int ntiles = (int)((Lk + KT - 1) / KT);
-  u32x4 rk[K_LD], rv[V_LD];
-
-  auto load_tile = [&](int kt) {
-#pragma unroll
-    for (int i = 0; i < K_LD; ++i) {
-      int id = tid + NT * i;  // the K tile is one contiguous 64*DH*2-byte run
-      rk[i] = *reinterpret_cast<const u32x4*>(Kh + (long)kt * KT * DH + id * 8);
-    }
-#pragma unroll
-    for (int i = 0; i < V_LD; ++i) {
-      int id = tid + NT * i, row = id >> 3, ch = id & 7;
-      rv[i] = *reinterpret_cast<const u32x4*>(Vh + (long)row * LkPad + (long)kt * KT + ch * 8);
-    }
-  };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < K_LD; ++i) {
-      int id = tid + NT * i, row = id / (DH / 8), ch = id % (DH / 8);
-      *reinterpret_cast<u32x4*>(&sm.k[buf][row * KS + ch * 8]) = rk[i];
-    }
-#pragma unroll
-    for (int i = 0; i < V_LD; ++i) {
-      int id = tid + NT * i, row = id >> 3, ch = id & 7;
-      *reinterpret_cast<u32x4*>(&sm.v[buf][row * VS + ch * 8]) = rv[i];
-    }
-  };
-
-  load_tile(0);
-  store_tile(0);
-  // Pin the Q fragments in registers here. Without this the compiler sinks their loads
-  // into the loop, and the waits it then needs inside the loop also wait for the prefetch
-  // of tile kt+1, exposing the global latency every iteration.
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-    for (int s = 0; s < SK; ++s) asm volatile("" : "+v"(qf[qb][s]));
-  __syncthreads();
-
-  for (int kt = 0; kt < ntiles; ++kt) {
-    const int cur = kt & 1;
-    const bool more = kt + 1 < ntiles;
-    if (more) load_tile(kt + 1);
-
-    // ---- S^T = K Q^T : [64 keys] x [QB*32 queries]
-    f32x16 s[2][QB];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[kb][qb][r] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < SK; ++ks) {
-      bf16x8 kf[2];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-        kf[kb] = *reinterpret_cast<const bf16x8*>(&sm.k[cur][(32 * kb + lrow) * KS + 16 * ks + lk]);
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          s[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], qf[qb][ks], s[kb][qb], 0, 0, 0);
-    }
-
-    // ---- logits in log2 units, column scale and tail mask
-    const long key0 = (long)kt * KT + 4 * c;  // + 32 kb + 8 j + i
-    if (COLSCALE) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          long key = key0 + 32 * kb + 8 * (r >> 2) + (r & 3);
-          float g = col_scale[key < Lk ? key : Lk - 1] * scale_log2;
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb) s[kb][qb][r] *= g;
-        }
-    }
-    if (!more && (Lk % KT) != 0) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          long key = key0 + 32 * kb + 8 * (r >> 2) + (r & 3);
-          if (key >= Lk) {
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) s[kb][qb][r] = -INFINITY;
-          }
-        }
-    }
-
-    // ---- online softmax, one query row per lane pair (l, l^32)
-    bf16x8 pf[QB][4];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      float mx = s[0][qb][0];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][qb][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float mxs = COLSCALE ? mx : mx * scale_log2;
-      if (__any(mxs > m_run[qb] + 8.0f)) {
-        const float m_new = fmaxf(m_run[qb], mxs);
-        const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);  // 0 on the first tile
-        m_run[qb] = m_new;
-        l_run[qb] *= alpha;
-#pragma unroll
-        for (int t = 0; t < TD; ++t)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[qb][t][r] *= alpha;
-      }
-      const float mref = m_run[qb];
-      float lsum = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        float p[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float a = COLSCALE ? (s[kb][qb][r] - mref) : __builtin_fmaf(s[kb][qb][r], scale_log2, -mref);
-          p[r] = __builtin_amdgcn_exp2f(a);
-          lsum += p[r];
-        }
-#pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) pf[qb][2 * kb + h2][e] = (bf16_t)p[8 * h2 + e];
-      }
-      l_run[qb] += lsum;
-    }
-
-    // ---- O^T += V^T P^T
-#pragma unroll
-    for (int t = 0; t < TD; ++t) {
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(&sm.v[cur][(32 * t + lrow) * VS + 16 * ks + lk]);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          o[qb][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][ks], o[qb][t], 0, 0, 0);
-      }
-    }
-
-    if (more) store_tile(cur ^ 1);
-    __syncthreads();
-  }
-
-  // ---- normalise and write O[q][head*DH + dh], 4 consecutive dh per register group
-  const int D = H * DH;
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const float l = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
-    const float inv = 1.0f / l;
-    const long q = q_wave0 + qb * 32 + lrow;
-    if (q < Lq) {
-      uint16_t* op = O + q * (long)D + head * DH + 4 * c;
-#pragma unroll
-      for (int t = 0; t < TD; ++t)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          uint2 w;
-          w.x = pack_bf16x2(o[qb][t][4 * j + 0] * inv, o[qb][t][4 * j + 1] * inv);
-          w.y = pack_bf16x2(o[qb][t][4 * j + 2] * inv, o[qb][t][4 * j + 3] * inv);
-          *reinterpret_cast<uint2*>(op + 32 * t + 8 * j) = w;
-        }
-    }
-  }
-}
+constexpr int KT = 64;  // granularity of the key padding (the smaller of the two tile sizes)
 
 // ---------------------------------------------------------------------------
-// Ping-pong variant: 8 waves, one block of 32 query rows each, two groups of four
+// Ping-pong phases: 8 waves, one block of 32 query rows each, two groups of four
 // waves (one wave of each group per SIMD). A wave alternates between a VALU phase
 // (softmax of tile j) and an MFMA phase (O += V(j) P(j), then S(j+1) = K(j+1) Q^T),
 // separated by workgroup barriers; group 1 runs one phase behind group 0, so on
@@ -509,35 +280,10 @@ int32_t launch_attn_pp(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt,
   if (nqt * H > 0x7fffffffL) return CHORUS_E_SHAPE;
   size_t smem = 2 * ((size_t)KTL * (DH + 8) + (size_t)DH * (KTL + 8)) * sizeof(uint16_t);
   auto kern = attention_pp_kernel<DH, KTL, CS>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    CHORUS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)smem));
-    attr_done = true;
-  }
+  static DynLdsOnce once;  // the raised dynamic-LDS limit is a per-device property of the kernel
+  CHK_STATUS(once.ensure(reinterpret_cast<const void*>(kern), (int)smem));
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
   hipLaunchKernelGGL(kern, dim3((unsigned)(nqt * H)), dim3(512), smem, s, Q, K, Vt, O, cs, Lq, Lk, LqPad, LkPad, H,
-                     (int)nqt, scale_log2);
-  CHORUS_LAUNCH_CHECK();
-  return CHORUS_OK;
-}
-
-template <int DH, int QB, int NW, bool CS>
-int32_t launch_attn(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, const float* cs, long Lq,
-                    long Lk, long LqPad, long LkPad, int H, hipStream_t s) {
-  constexpr int QROWS = NW * QB * 32;
-  long nqt = (Lq + QROWS - 1) / QROWS;
-  if (nqt * H > 0x7fffffffL) return CHORUS_E_SHAPE;
-  size_t smem = sizeof(AttnSmem<DH>);
-  auto kern = attention_kernel<DH, QB, NW, CS>;
-  static bool attr_done = false;  // raising the dynamic LDS limit is needed once per kernel
-  if (!attr_done) {
-    CHORUS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)smem));
-    attr_done = true;
-  }
-  const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-  hipLaunchKernelGGL(kern, dim3((unsigned)(nqt * H)), dim3(NW * 64), smem, s, Q, K, Vt, O, cs, Lq, Lk, LqPad, LkPad, H,
                      (int)nqt, scale_log2);
   CHORUS_LAUNCH_CHECK();
   return CHORUS_OK;
@@ -548,11 +294,12 @@ int32_t launch_attn(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, ui
 
 using namespace chorus;
 
-// variant: 0 = default; 1 = 8 waves x 32 rows; 2 = 4 waves x 64 rows; 3 = 8 waves, ping-pong phases
+// variant: 0 = default choice; 3 = 64-key tiles; 4 = 128-key tiles (no column scale, LkPad % 128 == 0)
 extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O,
                                     const float* col_scale, int64_t Lq, int64_t Lk, int64_t LqPad, int64_t LkPad,
                                     int32_t H, int32_t dh, int32_t variant, void* stream) {
   if (Lq < 0 || Lk < 0 || H <= 0) return CHORUS_E_ARG;
+  if (variant != 0 && variant != 3 && variant != 4) return CHORUS_E_ARG;
   if (Lq == 0) return CHORUS_OK;
   if (Lk < 1) return CHORUS_E_SHAPE;
   if (!Q || !K || !Vt || !O) return CHORUS_E_ARG;
@@ -560,32 +307,17 @@ extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const 
   if (!aligned16(Q) || !aligned16(K) || !aligned16(Vt) || !aligned16(O)) return CHORUS_E_ARG;
   hipStream_t s = (hipStream_t)stream;
   const bool cs = col_scale != nullptr;
-  // ping-pong phases (one wave per SIMD on the matrix pipe, one on the softmax); 128-key tiles
-  // when the padding allows and no column scale is needed (that kernel would spill registers)
+  // 128-key tiles when the padding allows and no column scale is needed (with it that tile size would spill
+  // registers, so it is not built)
   if (variant == 0) variant = (!cs && LkPad % 128 == 0 && Lk >= 2048) ? 4 : 3;
-#define ATTN(DHV, QBV, NWV)                                                                               \
-  (cs ? launch_attn<DHV, QBV, NWV, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)              \
-      : launch_attn<DHV, QBV, NWV, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s))
-  if (variant == 3) {
-    if (dh == 128)
-      return cs ? launch_attn_pp<128, 64, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
-                : launch_attn_pp<128, 64, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
-    return cs ? launch_attn_pp<64, 64, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
-              : launch_attn_pp<64, 64, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
+  if (variant == 4) {
+    if (cs || LkPad % 128) return CHORUS_E_SHAPE;
+    return dh == 128 ? launch_attn_pp<128, 128, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
+                     : launch_attn_pp<64, 128, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
   }
-  if (variant == 4) {  // 128-key tiles (needs LkPad % 128 == 0)
-    if (LkPad % 128) return CHORUS_E_SHAPE;
-    if (dh == 128)
-      return cs ? launch_attn_pp<128, 128, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
-                : launch_attn_pp<128, 128, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
-    return cs ? launch_attn_pp<64, 128, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
-              : launch_attn_pp<64, 128, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
-  }
-  if (dh == 128) {
-    if (variant == 1) return ATTN(128, 1, 8);
-    return ATTN(128, 2, 4);
-  }
-  if (variant == 1) return ATTN(64, 1, 8);
-  return ATTN(64, 2, 4);
-#undef ATTN
+  if (dh == 128)
+    return cs ? launch_attn_pp<128, 64, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
+              : launch_attn_pp<128, 64, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
+  return cs ? launch_attn_pp<64, 64, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
+            : launch_attn_pp<64, 64, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
 }

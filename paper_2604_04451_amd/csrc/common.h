@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "chorus.h"
 
 namespace chorus {
@@ -22,6 +24,28 @@ inline int32_t hip_fail(hipError_t e) {
   } while (0)
 
 #define CHORUS_LAUNCH_CHECK() CHORUS_HIP(hipGetLastError())
+
+#define CHK_STATUS(call)                    \
+  do {                                      \
+    int32_t st__ = (call);                  \
+    if (st__ != CHORUS_OK) return st__;     \
+  } while (0)
+
+// Raises a kernel's dynamic-LDS limit once per device. The limit is a property of the (kernel, device) pair, so the
+// record is a bit per device ordinal; setting it twice from racing threads is harmless (same value), and a device
+// ordinal beyond the mask is simply set on every call.
+struct DynLdsOnce {
+  std::atomic<uint64_t> done{0};
+  int32_t ensure(const void* kernel, int bytes) {
+    int dev = 0;
+    CHORUS_HIP(hipGetDevice(&dev));
+    const uint64_t bit = (dev >= 0 && dev < 64) ? (1ull << dev) : 0ull;
+    if (bit && (done.load(std::memory_order_acquire) & bit)) return CHORUS_OK;
+    CHORUS_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    if (bit) done.fetch_or(bit, std::memory_order_release);
+    return CHORUS_OK;
+  }
+};
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

@@ -25,8 +25,6 @@ __device__ __forceinline__ float gelu_tanh_fast(float x) {
   return x * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
-int g_gemm_variant = 0;  // 0 = default choice, 1 = never use the direct-to-LDS kernel, 2 = always when it has >= 256 tiles (comparisons)
-
 struct EpiArgs {
   void* out;
   const float* bias;
@@ -478,16 +476,12 @@ int32_t launch_gemm_dl(const uint16_t* A, const uint16_t* W, long M, int N, int 
   if (tm * tn > 0x7fffffffL) return CHORUS_E_SHAPE;
   dim3 grid((unsigned)(tm * tn)), block(512);
   const size_t smem = 2 * (256 + 256) * BK * sizeof(uint16_t);  // 128 KB
-#define GEMM_DL(E)                                                                                              \
-  {                                                                                                             \
-    auto kern = gemm_dl_kernel<E>;                                                                              \
-    static bool attr_done = false;                                                                              \
-    if (!attr_done) {                                                                                           \
-      CHORUS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                       \
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));                   \
-      attr_done = true;                                                                                         \
-    }                                                                                                           \
-    hipLaunchKernelGGL(kern, grid, block, smem, s, A, W, M, N, K, ep, (int)tm, tn);                             \
+#define GEMM_DL(E)                                                                              \
+  {                                                                                             \
+    auto kern = gemm_dl_kernel<E>;                                                              \
+    static DynLdsOnce once;                                                                     \
+    CHK_STATUS(once.ensure(reinterpret_cast<const void*>(kern), (int)smem));                    \
+    hipLaunchKernelGGL(kern, grid, block, smem, s, A, W, M, N, K, ep, (int)tm, tn);             \
   }
   switch (epi) {
     case CHORUS_EPI_BF16: GEMM_DL(CHORUS_EPI_BF16); break;
@@ -526,15 +520,11 @@ int32_t launch_gemm(const uint16_t* A, const uint16_t* W, long M, int N, int K, 
 
 using namespace chorus;
 
-extern "C" int32_t chorus_gemm_set_variant(int32_t v) {
-  g_gemm_variant = v;
-  return CHORUS_OK;
-}
-
-extern "C" int32_t chorus_gemm_bf16(const uint16_t* A, const uint16_t* W, int64_t M, int32_t N, int32_t K,
-                                    int32_t epilogue, void* out, const float* bias, const float* gate0,
-                                    const float* gate1, float scale, void* stream) {
+extern "C" int32_t chorus_gemm_bf16_kernel(const uint16_t* A, const uint16_t* W, int64_t M, int32_t N, int32_t K,
+                                           int32_t epilogue, void* out, const float* bias, const float* gate0,
+                                           const float* gate1, float scale, int32_t kernel, void* stream) {
   if (M < 0 || N <= 0 || K <= 0) return CHORUS_E_ARG;
+  if (kernel < 0 || kernel > 3) return CHORUS_E_ARG;
   if (M == 0) return CHORUS_OK;
   if (!A || !W || !out) return CHORUS_E_ARG;
   if (K % BK || N % 8) return CHORUS_E_SHAPE;
@@ -542,15 +532,24 @@ extern "C" int32_t chorus_gemm_bf16(const uint16_t* A, const uint16_t* W, int64_
     return CHORUS_E_ARG;
   EpiArgs ep{out, bias, gate0, gate1, scale};
   hipStream_t s = (hipStream_t)stream;
+  if (kernel == 1) return launch_gemm<128, 64, 64, 32>(A, W, (long)M, N, K, epilogue, ep, s);
+  if (kernel == 2) return launch_gemm<256, 128, 128, 64>(A, W, (long)M, N, K, epilogue, ep, s);
+  if (kernel == 3) return launch_gemm_dl(A, W, (long)M, N, K, epilogue, ep, s);
   // small problems get the smaller tile so that more workgroups exist; between the two large tiles the choice goes
   // by rounds of 256 workgroups: a 256 x 128 tile takes about 0.6 of the time of a 256 x 256 one
   long big_tiles = ((M + 255) / 256) * ((N + 127) / 128);
   long dl_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-  if (g_gemm_variant != 1 && dl_tiles >= 256) {
+  if (dl_tiles >= 256) {
     const double t_dl = (double)((dl_tiles + 255) / 256);
     const double t_big = 0.6 * (double)((big_tiles + 255) / 256);
-    if (g_gemm_variant == 2 || t_dl <= t_big) return launch_gemm_dl(A, W, (long)M, N, K, epilogue, ep, s);
+    if (t_dl <= t_big) return launch_gemm_dl(A, W, (long)M, N, K, epilogue, ep, s);
   }
   if (big_tiles >= 256) return launch_gemm<256, 128, 128, 64>(A, W, (long)M, N, K, epilogue, ep, s);
   return launch_gemm<128, 64, 64, 32>(A, W, (long)M, N, K, epilogue, ep, s);
+}
+
+extern "C" int32_t chorus_gemm_bf16(const uint16_t* A, const uint16_t* W, int64_t M, int32_t N, int32_t K,
+                                    int32_t epilogue, void* out, const float* bias, const float* gate0,
+                                    const float* gate1, float scale, void* stream) {
+  return chorus_gemm_bf16_kernel(A, W, M, N, K, epilogue, out, bias, gate0, gate1, scale, 0, stream);
 }

@@ -113,13 +113,16 @@ def test_v_transpose_bit_exact(L, D):
 
 # ---------------------------------------------------------------- attention
 
-def _attn_case(H, dh, Lq, Lk, variant, col_scale=None, q_std=1.0, seed=0, name=""):
+def _attn_case(H, dh, Lq, Lk, variant, col_scale=None, q_std=1.0, seed=0, name="", expect_tiles=None):
+    """One attention launch against the oracle. Keys are padded to 128 for the default choice and the 128-key
+    tile kernel (what the block does: it pads rows to 256), to 64 for the 64-key one."""
     D = H * dh
     q = synth.round_bf16(synth.normal(seed, "at.q", (Lq, D), q_std))
     k = synth.round_bf16(synth.normal(seed, "at.k", (Lk, D), q_std))
     v = synth.round_bf16(synth.normal(seed, "at.v", (Lk, D)))
     LqPad = (Lq + 255) // 256 * 256
-    LkPad = (Lk + 63) // 64 * 64
+    kpad = 64 if variant == 3 else 128
+    LkPad = (Lk + kpad - 1) // kpad * kpad
     Q = torch.zeros(H, LqPad, dh, dtype=torch.bfloat16, device=DEV)
     K = torch.zeros(H, LkPad, dh, dtype=torch.bfloat16, device=DEV)
     Q[:, :Lq] = dev_bf16(q).reshape(Lq, H, dh).transpose(0, 1)
@@ -133,24 +136,53 @@ def _attn_case(H, dh, Lq, Lk, variant, col_scale=None, q_std=1.0, seed=0, name="
                  max_abs=max(np.abs(ref).max() * 2 ** -7, 2e-3), rel_l2=5e-3)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3])
+# variant 0 is the library's own choice (128-key tiles from 2048 keys on, else 64-key tiles), 3 and 4 force the
+# 64- and the 128-key tile kernel: every shape runs through the kernel the block and the benchmark launch.
+ATTN_VARIANTS = [0, 3, 4]
+
+
+@pytest.mark.parametrize("variant", ATTN_VARIANTS)
 @pytest.mark.parametrize("H,dh,Lq,Lk", [(2, 64, 300, 300), (3, 128, 500, 333), (1, 128, 1, 1), (2, 128, 64, 64),
-                                        (2, 64, 257, 65), (12, 128, 1200, 1200), (4, 64, 256, 16)])
+                                        (2, 64, 257, 65), (12, 128, 1200, 1200), (4, 64, 256, 16),
+                                        (2, 128, 300, 2048), (2, 128, 513, 2049), (3, 64, 300, 2049),
+                                        (1, 128, 260, 2176 + 127), (1, 64, 40, 129)])
 def test_attention_plain(H, dh, Lq, Lk, variant):
     print(f"[case] attention H={H} dh={dh} Lq={Lq} Lk={Lk} variant={variant}", flush=True)
     _attn_case(H, dh, Lq, Lk, variant, name="plain")
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("variant", ATTN_VARIANTS)
 def test_attention_peaked(variant):
     """Logits with std ~4: rows dominated by few keys; catches masking / rescale mistakes that
-    near-uniform rows (output ~ mean V) would hide."""
+    near-uniform rows (output ~ mean V) would hide. Key counts with tails of 4, 16, 1 and 81 keys in the
+    last 128-key tile, above and below the 2048 keys where the default switches tile size."""
     print(f"[case] attention peaked variant={variant}", flush=True)
     _attn_case(4, 128, 700, 900, variant, q_std=2.0, seed=3, name="peaked")
     _attn_case(2, 64, 333, 2000, variant, q_std=2.0, seed=4, name="peaked64")
+    _attn_case(2, 128, 600, 2049, variant, q_std=2.0, seed=5, name="peaked 2049")
+    _attn_case(2, 64, 300, 2385, variant, q_std=2.0, seed=6, name="peaked64 2385")
+    _attn_case(1, 128, 257, 4096, variant, q_std=2.5, seed=8, name="peaked 4096 no tail")
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3])
+def test_attention_variant_argument_errors():
+    """The 128-key tile kernel is not built with a column scale; unknown variants are refused."""
+    H, dh, L = 1, 128, 128
+    Q = torch.zeros(H, 256, dh, dtype=torch.bfloat16, device=DEV)
+    K = torch.zeros(H, 128, dh, dtype=torch.bfloat16, device=DEV)
+    Vt = torch.zeros(H * dh, 128, dtype=torch.bfloat16, device=DEV)
+    Oo = torch.zeros(L, H * dh, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(P.ChorusError):
+        B.chorus_attention(Q, K, Vt, Oo, torch.ones(L, device=DEV), L, L, 4)
+    for bad in (1, 2, 5, -1):
+        with pytest.raises(P.ChorusError):
+            B.chorus_attention(Q, K, Vt, Oo, None, L, L, bad)
+    K64 = torch.zeros(H, 64, dh, dtype=torch.bfloat16, device=DEV)
+    Vt64 = torch.zeros(H * dh, 64, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(P.ChorusError):
+        B.chorus_attention(Q, K64, Vt64, Oo, None, L, 64, 4)
+
+
+@pytest.mark.parametrize("variant", [0, 3])
 @pytest.mark.parametrize("H,dh,Lq,Lt", [(4, 64, 256, 16), (12, 128, 700, 512), (2, 128, 100, 77)])
 def test_attention_tgaa_column_scale(H, dh, Lq, Lt, variant):
     print(f"[case] cross-attention TGAA H={H} dh={dh} Lq={Lq} Lt={Lt} variant={variant}", flush=True)
