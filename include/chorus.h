@@ -52,7 +52,10 @@ int32_t chorus_last_hip_error(void);
  *   ws         dev  chorus_cache_lookup_workspace_bytes(N) bytes
  * Scores are computed in fp32 with one fixed summation order per row, so equal
  * rows get equal scores; the lowest index wins ties. A zero-norm row or query
- * scores -inf. N == 0 gives index -1, score -inf, hit 0. d must be a multiple of 4.
+ * scores -inf. N == 0 gives index -1, score -inf, hit 0. d must be a multiple of 4;
+ * N at most 2^31 - 2 (the index is an int32), CHORUS_E_SHAPE beyond.
+ * Two launches: the scan leaves one (best value, index) pair per workgroup in ws, a single
+ * workgroup picks among them.
  * ------------------------------------------------------------------------ */
 typedef struct {
   int32_t index;

@@ -8,79 +8,123 @@ thread_local int32_t g_last_hip_error = 0;
 
 namespace {
 
-constexpr int kRowsPerBlock = 4;  // one wave per cache row
+constexpr int kWaves = 4;            // waves per workgroup of the scan, one cache row per wave at a time
+constexpr int kMaxScanBlocks = 4096; // beyond this many workgroups a wave walks several rows
+
+// What one workgroup of the scan leaves behind: the best r_j = <q, c_j> / |c_j| among its rows and that row's
+// index (the lowest one among equal values). The header in front of the partials holds |q|^2.
+struct LookupPartial {
+  float r;
+  int32_t idx;
+};
+constexpr size_t kLookupHeaderBytes = 256;
+
+inline long scan_blocks(long N) {
+  long g = (N + kWaves - 1) / kWaves;
+  return g < kMaxScanBlocks ? g : kMaxScanBlocks;
+}
+inline size_t lookup_scratch_bytes(long N) {
+  return kLookupHeaderBytes + align_up((size_t)(N > 0 ? scan_blocks(N) : 1) * sizeof(LookupPartial), 256);
+}
 
 // One wave per row: lanes stride over the row in float4, then a butterfly
 // reduction. The order of additions depends only on d, never on the row index,
-// so identical rows produce identical values. The kernel stores r_j = <q, c_j> / |c_j|;
+// so identical rows produce identical values. The scan compares r_j = <q, c_j> / |c_j|;
 // the query norm is a positive constant for the whole scan and is applied once, in the
-// argmax kernel (score_j = r_j / |q|), which keeps this HBM-bound loop at 8 FMAs per
-// 16 bytes read.
-__global__ __launch_bounds__(256) void lookup_scores_kernel(const float* __restrict__ cache,
-                                                            const float* __restrict__ query, float* __restrict__ scores,
-                                                            long N, int d) {
-  const int lane = threadIdx.x & 63;
-  const long row = (long)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
-  if (row >= N) return;
-  const float4* c4 = reinterpret_cast<const float4*>(cache + row * (long)d);
+// final kernel (score_j = r_j / |q|), which keeps this HBM-bound loop at 8 FMAs per
+// 16 bytes read. |q|^2 falls out of the query values every wave loads anyway (the same
+// additions in the same order in every wave); the first wave of the grid stores it.
+__global__ __launch_bounds__(kWaves * 64) void lookup_scan_kernel(const float* __restrict__ cache,
+                                                                  const float* __restrict__ query, long N, int d,
+                                                                  LookupPartial* __restrict__ partial,
+                                                                  float* __restrict__ qnorm2) {
+  __shared__ float sv[kWaves];
+  __shared__ int32_t si[kWaves];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const float4* q4 = reinterpret_cast<const float4*>(query);
   const int n4 = d >> 2;
-  float dot = 0.f, cc = 0.f;
-  int i = lane;
-  // 8 independent 16-byte loads in flight per lane
-  for (; i + 7 * 64 < n4; i += 8 * 64) {
-    float4 c[8], q[8];
+  float best = -INFINITY, qq = 0.f;
+  int32_t bi = 0x7fffffff;  // larger than any index
+  const long stride = (long)gridDim.x * kWaves;
+  for (long row = (long)blockIdx.x * kWaves + wave; row < N; row += stride) {
+    const float4* c4 = reinterpret_cast<const float4*>(cache + row * (long)d);
+    float dot = 0.f, cc = 0.f;
+    qq = 0.f;
+    int i = lane;
+    // 8 independent 16-byte loads in flight per lane
+    for (; i + 7 * 64 < n4; i += 8 * 64) {
+      float4 c[8], q[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) c[u] = ld_stream_f4(&c4[i + u * 64]);
+      for (int u = 0; u < 8; ++u) c[u] = ld_stream_f4(&c4[i + u * 64]);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) q[u] = q4[i + u * 64];
+      for (int u = 0; u < 8; ++u) q[u] = q4[i + u * 64];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      dot += c[u].x * q[u].x + c[u].y * q[u].y + c[u].z * q[u].z + c[u].w * q[u].w;
-      cc += c[u].x * c[u].x + c[u].y * c[u].y + c[u].z * c[u].z + c[u].w * c[u].w;
+      for (int u = 0; u < 8; ++u) {
+        dot += c[u].x * q[u].x + c[u].y * q[u].y + c[u].z * q[u].z + c[u].w * q[u].w;
+        cc += c[u].x * c[u].x + c[u].y * c[u].y + c[u].z * c[u].z + c[u].w * c[u].w;
+        qq += q[u].x * q[u].x + q[u].y * q[u].y + q[u].z * q[u].z + q[u].w * q[u].w;
+      }
+    }
+    for (; i < n4; i += 64) {
+      float4 c = ld_stream_f4(&c4[i]);
+      float4 q = q4[i];
+      dot += c.x * q.x + c.y * q.y + c.z * q.z + c.w * q.w;
+      cc += c.x * c.x + c.y * c.y + c.z * c.z + c.w * c.w;
+      qq += q.x * q.x + q.y * q.y + q.z * q.z + q.w * q.w;
+    }
+    dot = wave_sum(dot);
+    cc = wave_sum(cc);
+    const float nc = sqrtf(cc);
+    float r = nc > 0.f ? dot / nc : -INFINITY;
+    if (!(r == r)) r = -INFINITY;
+    if (r > best) {  // rows ascend within a wave: a strict comparison keeps the lowest index
+      best = r;
+      bi = (int32_t)row;
     }
   }
-  for (; i < n4; i += 64) {
-    float4 c = ld_stream_f4(&c4[i]);
-    float4 q = q4[i];
-    dot += c.x * q.x + c.y * q.y + c.z * q.z + c.w * q.w;
-    cc += c.x * c.x + c.y * c.y + c.z * c.z + c.w * c.w;
-  }
-  dot = wave_sum(dot);
-  cc = wave_sum(cc);
+  qq = wave_sum(qq);
   if (lane == 0) {
-    float nc = sqrtf(cc);
-    float s = nc > 0.f ? dot / nc : -INFINITY;
-    if (!(s == s)) s = -INFINITY;
-    scores[row] = s;
+    sv[wave] = best;
+    si[wave] = bi;
+    if (blockIdx.x == 0 && wave == 0) *qnorm2 = qq;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) {
+      if (sv[w] > best || (sv[w] == best && si[w] < bi)) {
+        best = sv[w];
+        bi = si[w];
+      }
+    }
+    LookupPartial p;
+    p.r = best;
+    p.idx = bi;
+    partial[blockIdx.x] = p;
   }
 }
 
-// Single workgroup: |q|, then max score with the lowest index among equal maxima.
-__global__ __launch_bounds__(1024) void lookup_argmax_kernel(const float* __restrict__ scores, long N,
-                                                             const float* __restrict__ query, int d, float tau,
-                                                             chorus_lookup_result* __restrict__ out) {
-  __shared__ float sv[16];
-  __shared__ long si[16];
-  __shared__ float sq[16];
+// Single workgroup: maximum over the workgroup partials with the lowest index among equal maxima, then the
+// division by |q| and the threshold test.
+__global__ __launch_bounds__(256) void lookup_final_kernel(const LookupPartial* __restrict__ partial, int nparts,
+                                                           const float* __restrict__ qnorm2, long N, float tau,
+                                                           chorus_lookup_result* __restrict__ out) {
+  __shared__ float sv[4];
+  __shared__ int32_t si[4];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int nw = blockDim.x >> 6;
-  float qq = 0.f;
-  for (int i = threadIdx.x; i < d; i += blockDim.x) qq += query[i] * query[i];
-  qq = wave_sum(qq);
   float best = -INFINITY;
-  long bi = N > 0 ? N : -1;  // sentinel larger than any index
-  for (long j = threadIdx.x; j < N; j += blockDim.x) {
-    float s = scores[j];
-    if (s > best || (s == best && j < bi)) {
-      best = s;
-      bi = j;
+  int32_t bi = 0x7fffffff;
+  for (int j = threadIdx.x; j < nparts; j += 256) {
+    const LookupPartial p = partial[j];
+    if (p.r > best || (p.r == best && p.idx < bi)) {
+      best = p.r;
+      bi = p.idx;
     }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
-    float ob = __shfl_xor(best, o, 64);
-    long oi = __shfl_xor(bi, o, 64);
+    const float ob = __shfl_xor(best, o, 64);
+    const int32_t oi = __shfl_xor(bi, o, 64);
     if (ob > best || (ob == best && oi < bi)) {
       best = ob;
       bi = oi;
@@ -89,13 +133,10 @@ __global__ __launch_bounds__(1024) void lookup_argmax_kernel(const float* __rest
   if (lane == 0) {
     sv[wave] = best;
     si[wave] = bi;
-    sq[wave] = qq;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    float qsum = 0.f;
-    for (int w = 0; w < nw; ++w) qsum += sq[w];
-    for (int w = 1; w < nw; ++w) {
+    for (int w = 1; w < 4; ++w) {
       if (sv[w] > best || (sv[w] == best && si[w] < bi)) {
         best = sv[w];
         bi = si[w];
@@ -107,16 +148,42 @@ __global__ __launch_bounds__(1024) void lookup_argmax_kernel(const float* __rest
       r.score = -INFINITY;
       r.hit = 0;
     } else {
-      const float nq = sqrtf(qsum);
+      const float nq = sqrtf(*qnorm2);
       float m = (nq > 0.f && best > -INFINITY) ? best / nq : -INFINITY;
       if (!(m == m)) m = -INFINITY;
       // every score -inf (zero-norm query or rows): index 0, like a first-maximum scan
-      r.index = (int32_t)((bi >= N || m == -INFINITY) ? 0 : bi);
+      r.index = (bi == 0x7fffffff || m == -INFINITY) ? 0 : bi;
       r.score = m;
       r.hit = m >= tau ? 1 : 0;
     }
     *out = r;
   }
+}
+
+// both launches of a lookup; `scratch` holds the header and the partials (lookup_scratch_bytes(N))
+int32_t launch_lookup(const float* cache_emb, long N, int d, const float* query, float tau, chorus_lookup_result* out,
+                      void* scratch, hipStream_t s) {
+  float* qnorm2 = reinterpret_cast<float*>(scratch);
+  LookupPartial* partial = reinterpret_cast<LookupPartial*>(reinterpret_cast<uint8_t*>(scratch) + kLookupHeaderBytes);
+  int nparts = 0;
+  if (N > 0) {
+    nparts = (int)scan_blocks(N);
+    hipLaunchKernelGGL(lookup_scan_kernel, dim3((unsigned)nparts), dim3(kWaves * 64), 0, s, cache_emb, query, N, d, partial,
+                       qnorm2);
+    CHORUS_LAUNCH_CHECK();
+  }
+  hipLaunchKernelGGL(lookup_final_kernel, dim3(1), dim3(256), 0, s, partial, nparts, qnorm2, N, tau, out);
+  CHORUS_LAUNCH_CHECK();
+  return CHORUS_OK;
+}
+
+int32_t check_lookup_args(const float* cache_emb, int64_t N, int32_t d, const float* query, const chorus_lookup_result* out) {
+  if (N < 0 || d <= 0 || !out || !query) return CHORUS_E_ARG;
+  if (N > 0 && !cache_emb) return CHORUS_E_ARG;
+  if ((d & 3) != 0) return CHORUS_E_SHAPE;
+  if (N > 0x7fffffffLL - 1) return CHORUS_E_SHAPE;  // the result index is an int32
+  if (!aligned16(cache_emb) || !aligned16(query)) return CHORUS_E_ARG;
+  return CHORUS_OK;
 }
 
 }  // namespace
@@ -129,26 +196,14 @@ extern "C" {
 int32_t chorus_version(void) { return 100; }
 int32_t chorus_last_hip_error(void) { return g_last_hip_error; }
 
-size_t chorus_cache_lookup_workspace_bytes(int64_t N) { return align_up((size_t)(N > 0 ? N : 1) * sizeof(float), 256); }
+size_t chorus_cache_lookup_workspace_bytes(int64_t N) { return lookup_scratch_bytes(N > 0 ? (long)N : 0); }
 
 int32_t chorus_cache_lookup(const float* cache_emb, int64_t N, int32_t d, const float* query, float tau,
                             chorus_lookup_result* out, void* ws, size_t ws_bytes, void* stream) {
-  if (N < 0 || d <= 0 || !out || !query) return CHORUS_E_ARG;
-  if (N > 0 && !cache_emb) return CHORUS_E_ARG;
-  if ((d & 3) != 0) return CHORUS_E_SHAPE;
-  if (!aligned16(cache_emb) || !aligned16(query)) return CHORUS_E_ARG;
+  CHK_STATUS(check_lookup_args(cache_emb, N, d, query, out));
   if (!ws || ws_bytes < chorus_cache_lookup_workspace_bytes(N)) return CHORUS_E_WORKSPACE;
-  if (N > (int64_t)kRowsPerBlock * 0x7fffffffLL) return CHORUS_E_SHAPE;
-  hipStream_t s = (hipStream_t)stream;
-  float* scores = (float*)ws;
-  if (N > 0) {
-    unsigned grid = (unsigned)((N + kRowsPerBlock - 1) / kRowsPerBlock);
-    hipLaunchKernelGGL(lookup_scores_kernel, dim3(grid), dim3(256), 0, s, cache_emb, query, scores, (long)N, d);
-    CHORUS_LAUNCH_CHECK();
-  }
-  hipLaunchKernelGGL(lookup_argmax_kernel, dim3(1), dim3(1024), 0, s, scores, (long)N, query, d, tau, out);
-  CHORUS_LAUNCH_CHECK();
-  return CHORUS_OK;
+  if (!aligned16(ws)) return CHORUS_E_ARG;
+  return launch_lookup(cache_emb, (long)N, d, query, tau, out, ws, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -59,6 +59,8 @@ def test_argument_validation_returns_codes():
     assert lib.chorus_cache_lookup(C.c_void_p(16), 4, 8, C.c_void_p(16), 0.5, out, null, 0, null) == B.E_WORKSPACE
     assert lib.chorus_cache_lookup(C.c_void_p(16), -1, 8, C.c_void_p(16), 0.5, out, C.c_void_p(16), 1024, null) == B.E_ARG
     assert lib.chorus_cache_lookup(C.c_void_p(8), 4, 8, C.c_void_p(16), 0.5, out, C.c_void_p(16), 1024, null) == B.E_ARG
+    # more entries than the int32 result index can name
+    assert lib.chorus_cache_lookup(C.c_void_p(16), 1 << 31, 8, C.c_void_p(16), 0.5, out, C.c_void_p(16), 1 << 20, null) == B.E_SHAPE
     # schedule
     assert lib.chorus_denoise_schedule(0.9, 0.75, -1, None, None, None, None) == B.E_ARG
     assert lib.chorus_denoise_schedule(0.9, 0.75, 0, None, None, None, None) == B.OK
@@ -90,7 +92,10 @@ def test_workspace_sizes_scale_with_rows():
     a = lib.chorus_dit_block_workspace_bytes(C.byref(sh), 13104)
     b = lib.chorus_dit_block_workspace_bytes(C.byref(sh), 32760)
     assert 0 < a < b < 3 * (1 << 30)
-    assert lib.chorus_cache_lookup_workspace_bytes(4096) >= 4096 * 4
+    # the scan leaves 8 bytes per workgroup of four rows (at most 4096 workgroups) behind a 256-byte header
+    assert lib.chorus_cache_lookup_workspace_bytes(4096) >= 256 + 1024 * 8
+    assert lib.chorus_cache_lookup_workspace_bytes(1 << 24) == lib.chorus_cache_lookup_workspace_bytes(1 << 20) >= 256 + 4096 * 8
+    assert lib.chorus_cache_lookup_workspace_bytes(0) >= 256
     assert lib.chorus_region_compact_workspace_bytes(75600) >= 4 * ((75600 + 4095) // 4096)
 
 

@@ -71,7 +71,7 @@ def test_lookup_c1_and_edges():
     assert _lookup(e, e[0], 1.0) == (0, 1.0, True)
 
 
-@pytest.mark.parametrize("N,d", [(1000, 768), (257, 4), (33, 2052), (4096, 4096)])
+@pytest.mark.parametrize("N,d", [(1000, 768), (257, 4), (33, 2052), (4096, 4096), (40003, 64)])
 def test_lookup_shapes(N, d):
     print(f"[case] lookup N={N} d={d}", flush=True)
     cache = synth.cache_embeddings(N, d, seed=1)
@@ -83,6 +83,22 @@ def test_lookup_shapes(N, d):
     # non-unit rows: cosine, not dot
     scaled = cache * synth.stream(1, "rowscale").uniform(0.1, 10.0, size=(N, 1)).astype(np.float32)
     _check_lookup(scaled, synth.cache_query(cache, seed=1, near=N // 2, trial=9))
+
+
+def test_lookup_many_rows_ties_across_workgroups():
+    """More rows than the scan has waves (a wave then walks several rows): equal rows in different workgroups and
+    in different passes of one wave still resolve to the lowest index."""
+    N, d = 70001, 32
+    print(f"[case] lookup ties N={N} d={d}", flush=True)
+    cache = synth.cache_embeddings(N, d, seed=4)
+    q = synth.cache_query(cache, seed=4, near=60000)
+    for dup in (123, 16384 + 123, 2 * 16384 + 123, 69999):
+        cache[dup] = cache[60000]
+    j, m, hit = _check_lookup(cache, cache[60000].copy())
+    assert j == 123 and hit
+    cache[123] = 0
+    j, m, hit = _check_lookup(cache, cache[60000].copy())
+    assert j == 16384 + 123
 
 
 def test_lookup_deterministic():
