@@ -68,6 +68,23 @@ int32_t chorus_cache_lookup(const float* cache_emb, int64_t N, int32_t d, const 
                             chorus_lookup_result* out, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * chorus_cache_lookup for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation. Same arguments (minus the workspace), same kernels, bit-identical result. The
+ * scan's per-workgroup partial results live in a 33 KB array in the library's own device
+ * image (one copy per GPU, held until the process ends) instead of a caller buffer. The call
+ * makes no hipMalloc / hipFree and no allocating library call; the first call on a device
+ * resolves the array's address there (make that call outside graph capture).
+ * All calls on one GPU share that array: calls that overlap in time on one GPU (two streams,
+ * two threads) race and may return each other's result; calls on one stream, or otherwise
+ * ordered, are safe, and nothing a call leaves in the array is read by the next.
+ * Limits: N at most 2^31 - 2 as for chorus_cache_lookup (the array serves every such N, the
+ * scan never uses more than 4096 workgroups); device ordinals 0..63. CHORUS_E_SHAPE beyond.
+ * ------------------------------------------------------------------------ */
+int32_t chorus_cache_lookup_static(const float* cache_emb, int64_t N, int32_t d, const float* query, float tau,
+                                   chorus_lookup_result* out, void* stream);
+
+/* ------------------------------------------------------------------------
  * The same retrieval for a batch of queued requests, with candidates: the k best entries
  * by cosine similarity for each of Q prompt embeddings. The cache is streamed once per 32
  * queries (a [N, d] x [d, Q] fp32 contraction on the matrix pipe), not once per query.

@@ -103,6 +103,7 @@ def load():
         "chorus_last_hip_error": (i32, []),
         "chorus_cache_lookup_workspace_bytes": (sz, [i64]),
         "chorus_cache_lookup": (i32, [vp, i64, i32, vp, f32, vp, vp, sz, vp]),
+        "chorus_cache_lookup_static": (i32, [vp, i64, i32, vp, f32, vp, vp]),
         "chorus_cache_insert": (i32, [vp, vp, i64, i64, i32, i64, vp, vp, vp]),
         "chorus_cache_lookup_batch_workspace_bytes": (sz, [i64, i32, i32]),
         "chorus_cache_lookup_batch": (i32, [vp, i64, i32, vp, i32, f32, i32, vp, vp, vp, vp, sz, vp]),
@@ -233,6 +234,23 @@ def chorus_cache_lookup(cache_emb, query, tau, out=None, ws=None):
         ws = _ws(need, query.device)
     _status("chorus_cache_lookup", lib.chorus_cache_lookup(_p(cache_emb) if N else C.c_void_p(0), N, d, _p(query),
                                                            float(tau), _p(out), _p(ws), ws.numel(), _stream()))
+    return out
+
+
+def chorus_cache_lookup_static(cache_emb, query, tau, out):
+    """chorus_cache_lookup without a workspace (the library's own per-GPU scratch array); `out` is required so
+    that this wrapper allocates nothing either."""
+    lib = load()
+    _chk(cache_emb, torch.float32, "cache_emb")
+    _chk(query, torch.float32, "query")
+    if out is None:
+        raise TypeError("out: required")
+    _chk(out, torch.int32, "out", (3,))
+    N, d = cache_emb.shape
+    if query.numel() != d:
+        raise TypeError("query: wrong length")
+    _status("chorus_cache_lookup_static", lib.chorus_cache_lookup_static(_p(cache_emb) if N else C.c_void_p(0), N, d,
+                                                                         _p(query), float(tau), _p(out), _stream()))
     return out
 
 

@@ -177,6 +177,30 @@ int32_t launch_lookup(const float* cache_emb, long N, int d, const float* query,
   return CHORUS_OK;
 }
 
+// Scratch of the entry point that allocates nothing: the header and the largest number of partials a scan leaves
+// (the scan caps its grid, so this serves every N). One copy per GPU, resident until the process ends.
+constexpr size_t kStaticScratchBytes = kLookupHeaderBytes + (size_t)kMaxScanBlocks * sizeof(LookupPartial);
+static __device__ __align__(256) uint8_t scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on each GPU. In host code the array's name is only a handle for
+// hipGetSymbolAddress; the address it returns for the current device is what kernels are given.
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+int32_t static_scratch(void** ptr) {
+  int dev = -1;
+  CHORUS_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return CHORUS_E_SHAPE;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {  // first call on this device (racing first calls resolve the same address)
+    CHORUS_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return CHORUS_E_HIP;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  return CHORUS_OK;
+}
+
 int32_t check_lookup_args(const float* cache_emb, int64_t N, int32_t d, const float* query, const chorus_lookup_result* out) {
   if (N < 0 || d <= 0 || !out || !query) return CHORUS_E_ARG;
   if (N > 0 && !cache_emb) return CHORUS_E_ARG;
@@ -204,6 +228,17 @@ int32_t chorus_cache_lookup(const float* cache_emb, int64_t N, int32_t d, const 
   if (!ws || ws_bytes < chorus_cache_lookup_workspace_bytes(N)) return CHORUS_E_WORKSPACE;
   if (!aligned16(ws)) return CHORUS_E_ARG;
   return launch_lookup(cache_emb, (long)N, d, query, tau, out, ws, (hipStream_t)stream);
+}
+
+int32_t chorus_cache_lookup_static(const float* cache_emb, int64_t N, int32_t d, const float* query, float tau,
+                                   chorus_lookup_result* out, void* stream) {
+  CHK_STATUS(check_lookup_args(cache_emb, N, d, query, out));
+  if (lookup_scratch_bytes(N > 0 ? (long)N : 0) > kStaticScratchBytes) return CHORUS_E_SHAPE;
+  void* ptr = nullptr;
+  CHK_STATUS(static_scratch(&ptr));
+  // nothing in the scratch has to start at zero: the scan writes the query norm and every partial the final
+  // kernel reads (it reads as many as this call's scan has workgroups), so what an earlier call left is never seen
+  return launch_lookup(cache_emb, (long)N, d, query, tau, out, ptr, (hipStream_t)stream);
 }
 
 }  // extern "C"

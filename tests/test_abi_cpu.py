@@ -61,6 +61,11 @@ def test_argument_validation_returns_codes():
     assert lib.chorus_cache_lookup(C.c_void_p(8), 4, 8, C.c_void_p(16), 0.5, out, C.c_void_p(16), 1024, null) == B.E_ARG
     # more entries than the int32 result index can name
     assert lib.chorus_cache_lookup(C.c_void_p(16), 1 << 31, 8, C.c_void_p(16), 0.5, out, C.c_void_p(16), 1 << 20, null) == B.E_SHAPE
+    # the workspace-free lookup validates the same way, before any device call
+    assert lib.chorus_cache_lookup_static(C.c_void_p(16), 4, 6, C.c_void_p(16), 0.5, out, null) == B.E_SHAPE
+    assert lib.chorus_cache_lookup_static(C.c_void_p(16), -1, 8, C.c_void_p(16), 0.5, out, null) == B.E_ARG
+    assert lib.chorus_cache_lookup_static(C.c_void_p(16), 1 << 31, 8, C.c_void_p(16), 0.5, out, null) == B.E_SHAPE
+    assert lib.chorus_cache_lookup_static(C.c_void_p(16), 4, 8, C.c_void_p(16), 0.5, None, null) == B.E_ARG
     # schedule
     assert lib.chorus_denoise_schedule(0.9, 0.75, -1, None, None, None, None) == B.E_ARG
     assert lib.chorus_denoise_schedule(0.9, 0.75, 0, None, None, None, None) == B.OK
