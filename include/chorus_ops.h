@@ -266,7 +266,12 @@ int32_t chorus_denoise_step_solver(const chorus_model_shape* model, const chorus
  * Cache update: when store_slot >= 0 and the request is a miss, the query and the latent after
  * store_after steps (1 <= store_after <= n_steps; the intermediate state a later hit with
  * K1 = store_after resumes from) are written to entry store_slot with chorus_cache_insert.
- * One cached latent per entry serves both the stage-1 copy and the stage-2 fusion.
+ * One cached latent per entry serves both the stage-1 copy and the stage-2 fusion. With latent_steps NULL the
+ * library does not know at which depth that latent was taken and resumes from it at whatever K1 Eq. 1 gives:
+ * correct only when the caller's entries were stored at that K1 (a fixed N and a plan whose K1 does not move
+ * with the score, as in the benchmark's 4-step configuration). A caller that knows the depth passes it as
+ * latent_steps = {depth}, n_latent_steps = 1 (the same memory layout): K1 is then snapped to it, and a score
+ * whose K1 falls below it runs as a miss instead of resuming from a latent at the wrong noise level.
  * Several depths per entry: with latent_steps (host [n_latent_steps], distinct, each in [1, n_steps])
  * cache_latents is [N, n_latent_steps, C, T, Hl, Wl]; a hit takes its boundaries from
  * chorus_denoise_schedule_stored and resumes from the latent stored at depth K1 (also the SL of the

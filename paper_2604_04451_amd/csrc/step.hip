@@ -368,6 +368,7 @@ int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_w
   if (st != CHORUS_OK) return st;
   if (!rq || !latent || !result || !gw) return CHORUS_E_ARG;
   if (rq->n_steps < 0 || rq->cache_N < 0 || rq->cache_d <= 0) return CHORUS_E_ARG;
+  if (rq->n_steps > 64) return CHORUS_E_SHAPE;
   if (rq->n_steps > 0 && (!rq->sigmas || !rq->t_mods || !rq->t_heads || !rq->text_ctx)) return CHORUS_E_ARG;
   if (!rq->query || (rq->cache_N > 0 && (!rq->cache_emb || !rq->cache_latents))) return CHORUS_E_ARG;
   const int S = rq->latent_steps ? rq->n_latent_steps : 1;  // latents per cache entry
@@ -406,7 +407,6 @@ int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_w
   result->hit = lr.hit;
 
   chorus_step_plan plan_buf[64];
-  if (rq->n_steps > 64) return CHORUS_E_SHAPE;
   int32_t K1 = 0, K2 = 0, depth_slot = 0;
   if (rq->latent_steps)
     st = chorus_denoise_schedule_stored(lr.score, rq->tau, rq->n_steps, rq->sched, rq->latent_steps, S, &K1, &K2,

@@ -289,3 +289,5 @@ def test_denoise_run_validates_before_any_launch():
     assert call(latent_steps=steps(1), n_latent_steps=0) == B.E_ARG
     assert call(query=0) == B.E_ARG and call(sigmas=None) == B.E_ARG and call(n_steps=-1) == B.E_ARG
     assert call(ws=None) == B.E_WORKSPACE and call(wsb=need - 1) == B.E_WORKSPACE
+    long_sig = (C.c_float * 66)(*[1.0 - i / 65 for i in range(66)])
+    assert call(n_steps=65, sigmas=long_sig) == B.E_SHAPE                    # more steps than a plan holds: no launch

@@ -17,6 +17,19 @@ from test_gpu_ops import _vt_reference
 pytestmark = pytest.mark.gpu
 
 
+import functools
+
+
+@functools.lru_cache(maxsize=2)
+def _weights(name, seed):
+    return synth.block_weights(synth.SHAPES[name], seed)
+
+
+@functools.lru_cache(maxsize=2)
+def _inputs(name, seed):
+    return synth.block_inputs(synth.SHAPES[name], seed)
+
+
 def _rows(L, n, seed):
     r = synth.stream(seed, "rows").permutation(L)[:n]
     return np.unique(np.concatenate([r, [0, L - 1, L - 2, (L // 256) * 256, (L // 256) * 256 - 1]]))
@@ -55,17 +68,27 @@ def test_self_attention_full_length_peaked(H, L):
         check(got[rows], ref, f"attention full length H={H} L={L} v{variant}", max_abs=max(np.abs(ref).max() * 2 ** -7, 2e-3), rel_l2=5e-3)
 
 
-@pytest.mark.parametrize("masked", [False, True, "bernoulli"])
+# the region sweep of the benchmark: the box of every fraction (frames x rows x columns of the 21 x 30 x 52 grid) and
+# i.i.d. masks at the two ends; `True` is the 40 % box of the headline request
+SWEEP_BOXES = {"box10": (21, 12, 13), "box25": (21, 15, 26), "box75": (21, 30, 39), "box90": (21, 27, 52)}
+
+
+@pytest.mark.parametrize("masked", [False, True, "bernoulli", "box10", "box25", "box75", "box90", "bernoulli10", "bernoulli90"])
 def test_block_full_shape_row_sampled(masked):
     bs = synth.SHAPES["wan1p3b_480p"]
     print(f"[case] block 1.3B 480p full shape masked={masked}", flush=True)
-    w = synth.block_weights(bs, 0)
-    inp = synth.block_inputs(bs, 0)
+    w = _weights("wan1p3b_480p", 0)
+    inp = _inputs("wan1p3b_480p", 0)
     g = synth.tdiff_scale(bs.Lt, 1.5, n_diff=8) if masked else None
     go = 1.5 if masked else 1.0
-    if masked == "bernoulli":
-        mask = synth.bernoulli_mask(bs.L, 0.5, seed=0)           # region sweep: i.i.d. per-token mask
+    if masked in SWEEP_BOXES:
+        bt, bh, bw = SWEEP_BOXES[masked]
+        mask = synth.box_mask(bs.grid, bt, bh, bw, 0, (30 - bh) // 2, (52 - bw) // 2)
         idx = O.region_compact(mask)
+        assert idx.size == bt * bh * bw
+    elif isinstance(masked, str):
+        mask = synth.bernoulli_mask(bs.L, {"bernoulli": 0.5, "bernoulli10": 0.1, "bernoulli90": 0.9}[masked], seed=0)
+        idx = O.region_compact(mask)                             # region sweep: i.i.d. per-token mask
     elif masked:
         mask = synth.box_mask(bs.grid, 21, 24, 26, 0, 3, 13)     # exactly 40% of the tokens
         idx = O.region_compact(mask)
@@ -90,3 +113,157 @@ def test_block_full_shape_row_sampled(masked):
     assert r <= 2e-2
     # rows outside the sample: finite and changed
     assert np.abs(got - x_in).max() > 1e-3
+
+
+def test_block_14b_720p_own_token_count_row_sampled():
+    """The 14B-shaped 720p block at its own token count: 75600 tokens (grid 21 x 45 x 80), D 5120, 40 x 128 heads,
+    F 13824, 512 text tokens, full compute. 296 query tiles x 40 heads, 590 key tiles of 128 plus an 80-key tail,
+    every GEMM in its large-tile kernel with a ragged last row tile (75600 = 295 x 256 + 80). The oracle computes the
+    keys and values of all tokens itself and then whole block rows for a seeded sample."""
+    bs = synth.SHAPES["wan14b_720p"]
+    print(f"[case] block 14B 720p full shape L={bs.L}", flush=True)
+    w = synth.block_weights(bs, 0)
+    print("[progress] weights drawn", flush=True)
+    inp = synth.block_inputs(bs, 0)
+    print("[progress] inputs drawn", flush=True)
+    shape = P.make_block_shape(bs.D, bs.H, bs.dh, bs.F, bs.Lt, bs.grid)
+    dw = P.upload_block_weights(w)
+    x = dev_f32(inp["x"])
+    g = synth.tdiff_scale(bs.Lt, 1.5, n_diff=8)
+    P.chorus_dit_block_step(shape, dw, x, bs.L, None, dev_bf16(inp["text_ctx"]), dev_f32(inp["t_mod"]), dev_f32(g), 1.5)
+    got = host(x)
+    del x, dw
+    torch.cuda.empty_cache()
+    assert np.isfinite(got).all()
+    print("[progress] device block done", flush=True)
+    rows = _rows(bs.L, 24, 13)
+    ref = O.dit_block(inp["x"], w, bs, inp["text_ctx"], inp["t_mod"], key_scale=g, gamma_o=1.5, rows=rows)
+    check(got[rows], ref, "block 14B 720p x")
+    a, r = errs(got[rows] - inp["x"][rows], ref - inp["x"][rows])
+    print(f"[parity] block 14B 720p delta: max_abs={a:.3e} rel_l2={r:.3e}", flush=True)
+    assert r <= 2e-2
+    assert np.abs(got - inp["x"]).max() > 1e-3
+
+
+# ------------------------------------------------------------------ whole requests at the full shape
+
+class _FullModel:
+    """The 480p model with n_blocks blocks on both sides, every input drawn from the seeded generators."""
+
+    def __init__(self, n_blocks, n_steps, seed=0):
+        bs = self.bs = synth.SHAPES["wan1p3b_480p"]
+        self.blocks = [synth.block_weights(bs, seed, b) for b in range(n_blocks)]
+        self.gw = synth.glue_weights(bs, seed)
+        self.text_raw = synth.round_bf16(synth.normal(seed, "text_raw", (bs.Lt, bs.text_dim), bs.text_std))
+        self.t_mods = synth.normal(seed, "t_mods", (n_steps, 6, bs.D), 0.02)
+        self.t_heads = synth.normal(seed, "t_heads", (n_steps, 2, bs.D), 0.02)
+        self.sigmas = [1.0 - i / n_steps for i in range(n_steps + 1)]
+        self.dblocks = [P.upload_block_weights(w) for w in self.blocks]
+        self.arr = B.block_array(self.dblocks)
+        self.dglue = B.upload_glue_weights(self.gw)
+        self.shape = P.make_block_shape(bs.D, bs.H, bs.dh, bs.F, bs.Lt, bs.grid)
+        self.model = B.make_model_shape(self.shape, bs.latent_shape, (2, 2), n_blocks)
+        self.d_tmods, self.d_theads = dev_f32(self.t_mods), dev_f32(self.t_heads)
+        self.d_ctx = B.chorus_text_project(dev_bf16(self.text_raw), self.dglue)
+        # a cache of four entries; the query is entry 2 itself, so the score is 1 and s = 1 in Eq. 1
+        self.cache = synth.cache_embeddings(4, bs.cache_d, seed=seed)
+        self.cache_lat = np.stack([synth.latent(bs, seed, f"cache_lat{j}") for j in range(4)])
+        self.query = self.cache[2].copy()
+        self.noise = synth.latent(bs, seed, "noise")
+        T, Hg, Wg = bs.grid
+        self.see = synth.box_mask(bs.grid, 21, 24, 26, 0, 3, 13)        # 13104 tokens = 40 %
+        self.edit = synth.box_mask(bs.grid, 21, 20, 22, 0, 5, 15)       # strictly inside
+        self.tdiff = np.zeros(bs.Lt, np.uint8)
+        self.tdiff[synth.stream(seed, "tdiff").permutation(bs.Lt)[:8]] = 1
+
+
+@pytest.mark.parametrize("stages", [(1, 3), (1, 2)])
+def test_run_full_shape_one_block_against_the_oracle(stages):
+    """chorus_denoise_run at 32760 tokens against an oracle that reads nothing from the device. With one block and a
+    two-step plan whose first step is a full reuse, the input of the computed step is the cached latent, which the
+    oracle draws from the same seeds; it then follows sampled tokens through patch embedding, the block (keys and
+    values of all tokens), the head, the sampler update and Eq. 6. (1, 3): reuse + one full step; (1, 2): reuse + one
+    region step on the 40 % box with M_edit inside M_see, TGAA 1.5 on 8 text tokens (r3 = 0 lets the plan end in
+    stage 2)."""
+    print(f"[case] run full shape one block stages={stages}", flush=True)
+    md = _FullModel(1, 2)
+    bs = md.bs
+    sched = dict(gamma_override=1.5, r3=0 if stages == (1, 2) else 1)
+    dl = dev_f32(md.noise)
+    res = B.chorus_denoise_run(md.model, md.arr, md.dglue, dl, dev_f32(md.cache), dev_f32(md.cache_lat), dev_f32(md.query),
+                               0.75, md.sigmas, md.d_tmods, md.d_theads, md.d_ctx,
+                               tdiff=torch.from_numpy(md.tdiff).to(DEV), mask_see=torch.from_numpy(md.see).to(DEV),
+                               mask_edit=torch.from_numpy(md.edit).to(DEV), sched=sched)
+    got = host(dl)
+    assert np.isfinite(got).all()
+    oj, om, ohit = O.cache_lookup(md.cache, md.query, 0.75)
+    K1, K2, plan = O.denoise_schedule(float(np.float32(res["score"])), float(np.float32(0.75)), 2, sched)
+    assert (res["index"], res["hit"], res["K1"], res["K2"]) == (oj, ohit, K1, K2) == (2, True, K1, K2)
+    assert tuple(p[0] for p in plan) == stages
+    SL = md.cache_lat[2].astype(np.float64)
+    ctx = O.text_project(md.text_raw, md.gw)
+    toks = O.patchify(SL, bs.patch)
+    dsigma = md.sigmas[2] - md.sigmas[1]
+    # the plan's amplification factors of the computed step (Eq. 4: a first stage-3 step right after the reuse still
+    # carries a decayed factor; the stage-2 step carries the override of the configuration, 1.5)
+    ks, go = np.where(md.tdiff != 0, plan[1][1], 1.0), plan[1][2]
+    if stages == (1, 3):
+        idx = np.arange(bs.L)
+        assert res["Ls"] == 0 and 1.0 < plan[1][1] < 1.5
+    else:
+        idx = O.region_compact(md.see)
+        assert res["Ls"] == idx.size == 13104 and plan[1][1] == 1.5
+    rows = _rows(idx.size, 40, 17)
+    x = O.patch_embed(O.gather_rows(toks, idx), md.gw)
+    xr = O.dit_block(x, md.blocks[0], bs, ctx, md.t_mods[1], token_idx=idx, key_scale=ks, gamma_o=go, rows=rows)
+    v = O.head(xr, md.gw, md.t_heads[1])
+    ref_rows = toks[idx[rows]] + dsigma * v
+    got_toks = O.patchify(got, bs.patch)
+    if stages == (1, 2):
+        keep = md.edit[idx[rows]] != 0
+        assert keep.any() and (~keep).any()          # the sample holds tokens of M_edit and of M_see outside it
+        ref_rows = np.where(keep[:, None], ref_rows, toks[idx[rows]])
+        Me = O.expand_token_mask(md.edit, bs.grid, bs.patch, bs.C).astype(bool)
+        np.testing.assert_array_equal(got[~Me], md.cache_lat[2][~Me])      # Eq. 6: everything outside M_edit is SL
+        upd = keep
+    else:
+        upd = np.ones(rows.size, bool)
+    check(got_toks[idx[rows]], ref_rows, f"run {stages} latent on sampled tokens")
+    a, r = errs(got_toks[idx[rows]][upd] - toks[idx[rows]][upd], ref_rows[upd] - toks[idx[rows]][upd])
+    print(f"[parity] run {stages} update on sampled tokens: max_abs={a:.3e} rel_l2={r:.3e}", flush=True)
+    assert r <= 2e-2
+
+
+def test_run_full_shape_four_steps_equals_its_steps():
+    """The benchmark's request shape (4 steps, stages [1, 2, 3, 3], 40 % box, TGAA 1.5) with two blocks at 32760
+    tokens: chorus_denoise_run gives, bit for bit, the latent that the same plan gives when it is walked with the
+    single entry points (stage-1 copy, compaction, chorus_denoise_step per computed step), whose parity is tested
+    one by one; the result is finite and the stage-2 region differs from the stage-3 result elsewhere."""
+    print("[case] run full shape four steps vs step composition", flush=True)
+    md = _FullModel(2, 4)
+    bs = md.bs
+    q = synth.cache_query(md.cache, seed=0, near=1)
+    sched = dict(gamma_override=1.5)
+    d_see = torch.from_numpy(md.see).to(DEV)
+    d_tdiff = torch.from_numpy(md.tdiff).to(DEV)
+    d_cache_lat = dev_f32(md.cache_lat)
+    dl = dev_f32(md.noise)
+    res = B.chorus_denoise_run(md.model, md.arr, md.dglue, dl, dev_f32(md.cache), d_cache_lat, dev_f32(q), 0.75, md.sigmas,
+                               md.d_tmods, md.d_theads, md.d_ctx, tdiff=d_tdiff, mask_see=d_see, mask_edit=d_see, sched=sched)
+    assert (res["index"], res["hit"], res["K1"], res["K2"], res["Ls"]) == (1, True, 1, 2, 13104)
+    K1, K2, plan = O.denoise_schedule(float(np.float32(res["score"])), float(np.float32(0.75)), 4, sched)
+    assert [p[0] for p in plan] == [1, 2, 3, 3]
+    lat = dev_f32(md.noise)
+    B.chorus_stage1_copy(lat, d_cache_lat[1])
+    idx_d, cnt = P.chorus_region_compact(d_see)
+    ks = dev_f32(np.where(md.tdiff != 0, plan[1][1], 1.0))
+    B.chorus_denoise_step(md.model, md.arr, md.dglue, lat, idx_d, int(cnt.cpu()[0]), md.d_ctx, md.d_tmods[1], md.d_theads[1],
+                          tgaa_key_scale=ks, gamma_o=plan[1][2], dsigma=md.sigmas[2] - md.sigmas[1], SL=d_cache_lat[1],
+                          mask_edit=d_see)
+    for i in (2, 3):
+        assert plan[i][1] == 1.0 and plan[i][2] == 1.0
+        B.chorus_denoise_step(md.model, md.arr, md.dglue, lat, None, bs.L, md.d_ctx, md.d_tmods[i], md.d_theads[i],
+                              dsigma=md.sigmas[i + 1] - md.sigmas[i])
+    assert torch.isfinite(dl).all()
+    assert torch.equal(dl, lat)
+    assert float((dl - d_cache_lat[1]).abs().max()) > 1e-3

@@ -22,7 +22,7 @@ def _shifted(n, shift=3.0, top=1.0):
 def _uncond(md, seed=11):
     raw = synth.round_bf16(synth.normal(seed, "text_uncond", (md.bs.Lt, md.bs.text_dim), md.bs.text_std))
     d = B.chorus_text_project(dev_bf16(raw), md.dglue)
-    return d, host_bf16(d)
+    return d, O.text_project(raw, md.gw)          # the oracle projects the prompt itself
 
 
 def _u8(a):

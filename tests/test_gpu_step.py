@@ -31,9 +31,10 @@ class Model:
         self.shape = P.make_block_shape(bs.D, bs.H, bs.dh, bs.F, bs.Lt, bs.grid)
         self.model = B.make_model_shape(self.shape, bs.latent_shape, (2, 2), n_blocks)
         self.d_tmods, self.d_theads = dev_f32(self.t_mods), dev_f32(self.t_heads)
-        # text context: the device projection, rounded to bf16, is what both sides use downstream
+        # text context: each side projects the raw prompt embedding itself -- the device with chorus_text_project
+        # (bf16 result), the oracle with its own text_project in fp64; nothing the oracle reads comes from the device
         self.d_ctx = B.chorus_text_project(dev_bf16(self.text_raw), self.dglue)
-        self.ctx = host_bf16(self.d_ctx)
+        self.ctx = O.text_project(self.text_raw, self.gw)
 
 
 def test_text_project_and_glue_ops():
@@ -41,7 +42,7 @@ def test_text_project_and_glue_ops():
     bs = synth.SHAPES["c1"]
     md = Model(bs, 1)
     ref_ctx = O.text_project(md.text_raw, md.gw)
-    check(md.ctx, ref_ctx, "text_project", max_abs=np.abs(ref_ctx).max() * 2 ** -7, rel_l2=5e-3)
+    check(host_bf16(md.d_ctx), ref_ctx, "text_project", max_abs=np.abs(ref_ctx).max() * 2 ** -7, rel_l2=5e-3)
     lat = synth.latent(bs, 0, std=1.0)
     mask = synth.exact_count_mask(bs.L, 100, seed=3)
     idx = O.region_compact(mask)

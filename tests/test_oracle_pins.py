@@ -443,6 +443,88 @@ def test_patchify_roundtrip_and_layout():
     np.testing.assert_array_equal(O.unpatchify(tok, shp, patch), lat)
 
 
+# -------------------------------------------------- model input / output stand-ins
+
+def _loop_linear(x, w, b):
+    """y[i][o] = sum_k x[i][k] * w[o][k] + b[o], written out."""
+    return [[sum(float(xi[k]) * float(w[o][k]) for k in range(len(xi))) + float(b[o]) for o in range(len(w))] for xi in x]
+
+
+def _loop_gelu_tanh(v):
+    return 0.5 * v * (1.0 + math.tanh(math.sqrt(2.0 / math.pi) * (v + 0.044715 * v ** 3)))
+
+
+def test_patch_embed_text_project_head_written_out():
+    """The model's input and output layers are stand-ins the paper does not define (Sec. 2.1 names the parts of a
+    DiT only), so the only pin available is the definition written out as Python loops on a tiny case: the patch
+    embedding (a linear map of the (c, dy, dx) cell), the text projection (linear, tanh-GELU, linear, in that
+    order) and the head (LayerNorm without affine, times (1 + scale), plus shift, then linear; row 0 of the table
+    is the shift, row 1 the scale). Biases and both modulation rows are non-zero and distinct, so a dropped bias,
+    swapped layers, a swapped (shift, scale) pair or a missing "1 +" each fail."""
+    rng = synth.stream(21, "glue-pin")
+    D, P, Lt, Td, L = 6, 4, 3, 5, 4
+    gw = {
+        "w_patch": rng.normal(size=(D, P)), "b_patch": rng.normal(size=D),
+        "w_text1": rng.normal(size=(D, Td)), "b_text1": rng.normal(size=D),
+        "w_text2": rng.normal(size=(D, D)), "b_text2": rng.normal(size=D),
+        "w_head": rng.normal(size=(P, D)), "b_head": rng.normal(size=P),
+        "head_table": rng.normal(size=(2, D)),
+    }
+    # patch embedding
+    patches = rng.normal(size=(L, P))
+    np.testing.assert_allclose(O.patch_embed(patches, gw), _loop_linear(patches, gw["w_patch"], gw["b_patch"]), rtol=1e-12, atol=1e-12)
+    # text projection
+    text = rng.normal(size=(Lt, Td))
+    hid = [[_loop_gelu_tanh(v) for v in row] for row in _loop_linear(text, gw["w_text1"], gw["b_text1"])]
+    np.testing.assert_allclose(O.text_project(text, gw), _loop_linear(hid, gw["w_text2"], gw["b_text2"]), rtol=1e-12, atol=1e-12)
+    # head
+    x = rng.normal(size=(L, D)) * 2.0 + 0.5
+    t_head = rng.normal(size=(2, D))
+    mod = []
+    for row in x:
+        mu = sum(float(v) for v in row) / D
+        var = sum((float(v) - mu) ** 2 for v in row) / D
+        mod.append([(float(row[i]) - mu) / math.sqrt(var + 1e-6) * (1.0 + float(gw["head_table"][1][i]) + float(t_head[1][i]))
+                    + float(gw["head_table"][0][i]) + float(t_head[0][i]) for i in range(D)])
+    ref = np.array(_loop_linear(mod, gw["w_head"], gw["b_head"]))
+    np.testing.assert_allclose(O.head(x, gw, t_head), ref, rtol=1e-12, atol=1e-12)
+    # the planted mistakes are all visible at this size
+    swapped = dict(gw, head_table=gw["head_table"][::-1].copy())
+    assert np.abs(O.head(x, swapped, t_head[::-1]) - ref).max() > 1e-2
+    # torch as a third opinion on the head's normalisation
+    tx = torch.tensor(x, dtype=T64)
+    tref = TF.linear(TF.layer_norm(tx, (D,), eps=1e-6) * (1.0 + torch.tensor(gw["head_table"][1] + t_head[1]))
+                     + torch.tensor(gw["head_table"][0] + t_head[0]), torch.tensor(gw["w_head"]), torch.tensor(gw["b_head"]))
+    np.testing.assert_allclose(O.head(x, gw, t_head), tref.numpy(), rtol=1e-12, atol=1e-12)
+
+
+def test_step_euler_update_written_out():
+    """One stage-3 step of a model without blocks is patchify -> embed -> head -> x + dsigma * v -> unpatchify:
+    checked cell by cell with the written-out layers above, so the token / feature order of the update is pinned."""
+    rng = synth.stream(22, "step-pin")
+    bs = synth.BlockShape("pin", D=8, H=1, dh=8, F=8, Lt=2, text_dim=4, grid=(2, 2, 2), C=2)
+    gw = synth.glue_weights(bs, 3, std=0.3)
+    gw["b_patch"] = rng.normal(size=bs.D)
+    gw["b_head"] = rng.normal(size=bs.patch_dim)
+    lat = rng.normal(size=bs.latent_shape)
+    t_head = rng.normal(size=(2, bs.D)) * 0.3
+    out = O.denoise_step(lat, [], gw, bs, np.zeros((bs.Lt, bs.D)), np.zeros((6, bs.D)), t_head, -0.5)
+    C, T, Hl, Wl = bs.latent_shape
+    for t in range(T):
+        for hg in range(Hl // 2):
+            for wg in range(Wl // 2):
+                cell = [lat[c, t, 2 * hg + dy, 2 * wg + dx] for c in range(C) for dy in range(2) for dx in range(2)]
+                xrow = _loop_linear([cell], gw["w_patch"], gw["b_patch"])
+                v = O.head(np.array(xrow), gw, t_head)[0]
+                f = 0
+                for c in range(C):
+                    for dy in range(2):
+                        for dx in range(2):
+                            want = lat[c, t, 2 * hg + dy, 2 * wg + dx] - 0.5 * v[f]
+                            assert abs(out[c, t, 2 * hg + dy, 2 * wg + dx] - want) < 1e-12
+                            f += 1
+
+
 # ------------------------------------------------------------- step / schedule
 
 def _tiny_model(seed=0):
