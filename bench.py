@@ -2,10 +2,12 @@
 """Benchmark of the Chorus hot path on one MI355X.
 
 One "step" = one whole request of the 4-step Chorus schedule on the Wan2.1-1.3B-
-shaped 480p model (30 blocks): cache lookup over 4096 x 4096-d embeddings, schedule,
-stage-1 full reuse of the matched latent, one stage-2 step on a contiguous 40% box of
-the tokens with TGAA amplification 1.5, blend with the cached latent, two stage-3
-full steps. Inputs are synthetic, seeded, and resident in HBM before the clock starts.
+shaped 480p model (30 blocks): projection of the prompt embedding to the model width,
+the timestep modulation rows of the four noise levels, cache lookup over 4096 x 4096-d
+embeddings, schedule, stage-1 full reuse of the matched latent, one stage-2 step on a
+contiguous 40% box of the tokens with TGAA amplification 1.5, blend with the cached
+latent, two stage-3 full steps. Inputs are synthetic, seeded, and resident in HBM
+before the clock starts.
 
 Prints ONE JSON line. `value` is milliseconds per request. `roofline` is for the
 dominant kernel (self-attention): algorithmic FLOPs (4 Ls^2 D per launch) over the
@@ -29,12 +31,13 @@ if ROOT not in sys.path:
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 # Bytes that leave / enter L2 per self-attention launch of the default workload (stage-2
-# launches at 13104 tokens and stage-3 launches at 32760 tokens, weighted 30:60), from the
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/bench_wan1p3b_480p_pmc_traffic.txt (FETCH_SIZE scaled by 1.992, the factor a plain
-# 8.39 MB copy kernel of the same run shows; WRITE_SIZE by 1.000). Counters cannot be read
-# inside this process, so the figure is only reported for that exact workload.
+# launches at 13104 tokens and stage-3 launches at 32760 tokens, weighted 30:60). Hardware
+# counters cannot be read inside this process: the figure is the one the two rocprofv3 --pmc
+# runs (FETCH_SIZE, then WRITE_SIZE) of this same command gave when the summary named below
+# was written (FETCH_SIZE scaled by 1.992, the factor a plain 8.39 MB copy kernel of the same
+# run shows; WRITE_SIZE by 1.000); it is reported for that exact workload only, with its source.
 SELF_ATTN_TRAFFIC_BYTES_DEFAULT = 7.69e8
+SELF_ATTN_TRAFFIC_SOURCE = "profiles/bench_wan1p3b_480p_pmc_traffic.txt"
 
 
 def block_flops(Ls, D, F, Lt):
@@ -116,10 +119,20 @@ def main():
 
     # ---- request inputs
     text_raw = randn((Lt, bs.text_dim), bs.text_std, torch.bfloat16)
-    ctx = B.chorus_text_project(text_raw, glue)            # once per request in serving; outside the clock
-    t_mods = randn((n_steps, 6, D), 0.02)
-    t_heads = randn((n_steps, 2, D), 0.02)
+    freq_dim = 256
+    tt = {
+        "w_t1": randn((D, freq_dim), 0.02, torch.bfloat16), "b_t1": randn((D,), 0.02),
+        "w_t2": randn((D, D), 0.02, torch.bfloat16), "b_t2": randn((D,), 0.02),
+        "w_tp": randn((6 * D, D), 0.02, torch.bfloat16), "b_tp": randn((6 * D,), 0.02),
+    }
+    tw = B.DeviceTime.__new__(B.DeviceTime)
+    tw.tensors, tw.freq_dim, tw.D = tt, freq_dim, D
+    tw.cstruct = B.TimeWeights(*[tt[n].data_ptr() for n in ("w_t1", "b_t1", "w_t2", "b_t2", "w_tp", "b_tp")])
+    ctx = torch.empty(Lt, D, dtype=torch.bfloat16, device=dev)
+    t_mods = torch.empty(n_steps, 6, D, device=dev)
+    t_heads = torch.empty(n_steps, 2, D, device=dev)
     sigmas = [1.0 - i / n_steps for i in range(n_steps + 1)]
+    timesteps = [1000.0 * sg for sg in sigmas[:n_steps]]       # the model's timestep value at each noise level
     noise = randn(bs.latent_shape, 1.0)
     cache_np = synth.cache_embeddings(N, bs.cache_d, seed=0)
     near = (N * 5) // 8
@@ -136,6 +149,8 @@ def main():
         boxes = {0.1: (12, 13), 0.25: (15, 26), 0.4: (24, 26), 0.5: (30, 26), 0.75: (30, 39), 0.9: (27, 52)}
         if (Hg, Wg) == (30, 52) and args.region in boxes:
             bh, bw = boxes[args.region]
+        elif (Hg, Wg) == (45, 80) and args.region == 0.5:
+            bh, bw = 45, 40                                 # the 720p workload's 50 % box
         else:
             bh = max(1, int(round(Hg * args.region ** 0.5)))
             bw = max(1, int(round(Wg * args.region * Hg / bh))) if bh else 1
@@ -146,18 +161,28 @@ def main():
     tdiff = torch.ones(Lt, dtype=torch.uint8, device=dev)   # amplification on all text tokens
     sched = dict(gamma_override=1.5)
     latent = torch.empty_like(noise)
+    lib = P.load()
     ws = torch.empty(B.chorus_denoise_run_workspace_bytes(model, N), dtype=torch.uint8, device=dev)
+    ws_text = torch.empty(max(lib.chorus_text_project_workspace_bytes(Lt, D), 256), dtype=torch.uint8, device=dev)
+    ws_time = torch.empty(max(lib.chorus_time_mod_workspace_bytes(D, freq_dim), 256), dtype=torch.uint8, device=dev)
 
     def request(tau=0.75):
+        """Everything a request computes, from the raw prompt embedding and the initial noise to the final latent."""
         B.chorus_stage1_copy(latent, noise)
-        return B.chorus_denoise_run(model, arr, glue, latent, cache_emb, cache_lat, query, tau, sigmas, t_mods, t_heads,
-                                    ctx, tdiff=tdiff, mask_see=mask, mask_edit=mask, sched=sched, ws=ws)
+        B.chorus_text_project(text_raw, glue, ctx, ws_text)
+        for i in range(n_steps):
+            B.chorus_time_mod(timesteps[i], tw, t_mods[i], t_heads[i], ws_time)
+        return B.chorus_denoise_run(model, arr, glue, latent, cache_emb, cache_lat.unsqueeze(1), query, tau, sigmas, t_mods, t_heads,
+                                    ctx, tdiff=tdiff, mask_see=mask, mask_edit=mask, sched=sched, ws=ws,
+                                    latent_steps=[1])       # every entry holds the latent after one step
 
-    for _ in range(args.warmup):
+    # warm-up; the first pass runs with the profiler on so that its event pool exists before the clock starts
+    B.prof_reset()
+    B.prof_enable([B.PROF_SELF_ATTN])
+    for _ in range(max(args.warmup, 1)):
         res = request()
     torch.cuda.synchronize()
     B.prof_reset()
-    B.prof_enable([B.PROF_SELF_ATTN])
     t0 = time.perf_counter()
     for _ in range(args.steps):
         res = request()
@@ -168,8 +193,14 @@ def main():
     B.prof_reset()
     ms = (t1 - t0) * 1e3 / max(args.steps, 1)
     assert res["hit"] and res["index"] == near and (res["K1"], res["K2"]) == (1, 2) and res["Ls"] == Ls, res
+    # the result of the last timed request: finite everywhere, the cached latent bit for bit outside the region
+    # (Eq. 6 ... then two full steps move every token), and different from the initial noise
+    assert bool(torch.isfinite(latent).all()), "non-finite latent"
+    assert float((latent - noise).abs().max()) > 1e-3 and float((latent - cache_lat[near]).abs().max()) > 1e-3
 
     # ---- roofline of the dominant kernel: self-attention, 4 Ls^2 D FLOPs per launch
+    default_workload = (args.workload == "wan1p3b_480p" and args.blocks is None and args.cache_entries is None
+                        and args.region == 0.4 and not args.bernoulli)
     per_req_attn_flops = n_blocks * (4.0 * Ls * Ls * D + 2 * 4.0 * L * L * D)
     attn_tflops = per_req_attn_flops * args.steps / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else 0.0
     plan_flops = n_blocks * (block_flops(Ls, D, F, Lt) + 2 * block_flops(L, D, F, Lt))
@@ -180,16 +211,19 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{bs.name}: 4-step Chorus schedule, {n_blocks} blocks, L={L}, D={D}, H={bs.H}x{bs.dh}, "
                                f"F={F}, Lt={Lt}, cache {N}x{bs.cache_d}, stage-2 "
-                               f"{'bernoulli' if args.bernoulli else 'box'} mask {Ls}/{L} tokens, TGAA 1.5",
+                               f"{'bernoulli' if args.bernoulli else 'box'} mask {Ls}/{L} tokens, TGAA 1.5; "
+                               f"text projection and timestep modulation inside the request",
                    "stages": [1, 2, 3, 3], "blocks": n_blocks, "tokens": L, "stage2_tokens": Ls},
         "request_tflops": round(plan_flops / (ms * 1e-3) / 1e12, 2),
         "self_attn_tflops": round(attn_tflops, 2),
         "self_attn_ms_per_launch": round(attn_ms / max(attn_n, 1), 4),
         "roofline": {"bound": "mfma", "achieved": round(attn_tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(attn_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "traffic": (SELF_ATTN_TRAFFIC_BYTES_DEFAULT if (args.workload == "wan1p3b_480p" and args.blocks is None
-                                                                      and args.region == 0.4 and not args.bernoulli) else None),
-                     "algorithmic_bytes": (30 * 4 * 2.0 * Ls * D + 60 * 4 * 2.0 * L * D) / 90.0,
+                     "traffic": (SELF_ATTN_TRAFFIC_BYTES_DEFAULT if default_workload else None),
+                     "traffic_source": (SELF_ATTN_TRAFFIC_SOURCE if default_workload else None),
+                     # Q, K, V read once and O written once per launch, averaged over the request's launches
+                     # (one per block at the stage-2 token count, two per block at the full count)
+                     "algorithmic_bytes": (4 * 2.0 * Ls * D + 2 * 4 * 2.0 * L * D) / 3.0,
                      "kernel": "attention_pp_kernel<128,128,false> (self-attention)", "launches": attn_n},
     }
     # what a bare MFMA loop sustains on this device right now (the part is power-managed: the rate depends on the
@@ -220,37 +254,53 @@ def main():
         out["plain_4_step_ms"] = round((time.perf_counter() - t0) * 1e3, 3)
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(bs, plan_flops)
+        out["cpu_baseline"] = cpu_baseline(bs, n_blocks, L, Ls)
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(bs, plan_flops):
-    """The numpy fp64 oracle, as it stands, on a bounded sample: one block of the same
-    widths on a 1024-token grid; scaled to the request by algorithmic FLOPs."""
+def cpu_baseline(bs, n_blocks, L, Ls):
+    """The numpy fp64 oracle, as it stands, timed on one block of the same widths at the two largest of the token
+    counts 2048, 4096, 8192 that fit in about 20 s of host time (TGAA 1.5 as in the stage-2 step). A block costs
+    a L + b L^2 (per-token work and self-attention); the two timings fix a and b, and the request is
+    n_blocks * (cost(Ls) + 2 cost(L)): an extrapolation, labelled as such."""
+    import dataclasses
     import synth
     from oracle import chorus_oracle as O
-    import dataclasses
-    small = dataclasses.replace(bs, grid=(4, 16, 16)) if bs.L > 1024 else bs
-    w = synth.block_weights(small, 0)
-    inp = synth.block_inputs(small, 0)
-    t0 = time.perf_counter()
-    reps = 0
-    while True:
-        O.dit_block(inp["x"], w, small, inp["text_ctx"], inp["t_mod"], key_scale=np.full(small.Lt, 1.5), gamma_o=1.5)
-        reps += 1
-        if time.perf_counter() - t0 > 10.0 or reps >= 20:
+    w = synth.block_weights(bs, 0)
+    times = []
+    # grow the sample while the host keeps up: 2048 tokens, then 4096, then 8192 if the first two took under 8 s
+    for grid in ([bs.grid] if bs.L <= 4096 else [(2, 32, 32), (4, 32, 32), (8, 32, 32)]):
+        if len(times) == 2 and sum(t for _, t in times) > 8.0:
             break
-    dt = (time.perf_counter() - t0) / reps
-    fl = block_flops(small.L, small.D, small.F, small.Lt)
+        small = dataclasses.replace(bs, grid=grid)
+        inp = synth.block_inputs(small, 0)
+        t0 = time.perf_counter()
+        O.dit_block(inp["x"], w, small, inp["text_ctx"], inp["t_mod"], key_scale=np.full(small.Lt, 1.5), gamma_o=1.5)
+        times.append((small.L, time.perf_counter() - t0))
+    times = times[-2:]
+    if len(times) == 2:
+        (l1, t1), (l2, t2) = times
+        b = (t2 / l2 - t1 / l1) / (l2 - l1)
+        a = t1 / l1 - b * l1
+        b = max(b, 0.0)
+    else:
+        (l1, t1), = times
+        a, b = t1 / l1, 0.0
+    cost = lambda n: a * n + b * n * n
+    total = n_blocks * (cost(Ls) + 2 * cost(L))
     try:
         import threadpoolctl
-        cores = max(p["num_threads"] for p in threadpoolctl.threadpool_info()) if threadpoolctl.threadpool_info() else 1
+        info = threadpoolctl.threadpool_info()
+        cores = max(p["num_threads"] for p in info) if info else 1
     except Exception:
         cores = os.cpu_count() or 1
-    return {"value": round(dt * plan_flops / fl * 1e3, 1), "unit": "ms per 4-step denoise (extrapolated by FLOPs)",
+    fl = block_flops(times[-1][0], bs.D, bs.F, bs.Lt)
+    return {"value": round(total * 1e3, 1), "unit": "ms per 4-step denoise (extrapolated from two measured block sizes)",
             "cores": int(cores), "kind": "oracle",
-            "sample": f"one block, {small.L} tokens, same widths: {dt * 1e3:.1f} ms measured = "
-                      f"{fl / dt / 1e9:.1f} GFLOP/s fp64; scaled by {plan_flops / fl:.0f}x to the request's FLOPs"}
+            "sample": "one block of the same widths, measured at " + " and ".join(f"{l} tokens: {t:.2f} s" for l, t in times)
+                      + f" ({fl / times[-1][1] / 1e9:.0f} GFLOP/s fp64 at the larger; self-attention is "
+                      + f"{4.0 * times[-1][0] ** 2 * bs.D / fl:.0%} of its FLOPs, {b * times[-1][0] ** 2 / max(times[-1][1], 1e-9):.0%} of its time); "
+                      + f"block cost a*L + b*L^2 fitted to the two, request = {n_blocks} x (cost({Ls}) + 2 cost({L}))"}
 
 
 if __name__ == "__main__":

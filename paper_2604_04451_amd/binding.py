@@ -577,14 +577,15 @@ def make_model_shape(bshape: BlockShape, latent_shape, patch_hw=(2, 2), n_blocks
     return ModelShape(bshape, Cc, T, Hl, Wl, patch_hw[0], patch_hw[1], n_blocks)
 
 
-def chorus_text_project(text, glue: DeviceGlue, ctx=None):
+def chorus_text_project(text, glue: DeviceGlue, ctx=None, ws=None):
     lib = load()
     _chk(text, torch.bfloat16, "text")
     Lt, td = text.shape
     D = glue.tensors["w_text1"].shape[0]
     if ctx is None:
         ctx = torch.empty(Lt, D, dtype=torch.bfloat16, device=text.device)
-    ws = _ws(lib.chorus_text_project_workspace_bytes(Lt, D), text.device)
+    if ws is None:
+        ws = _ws(lib.chorus_text_project_workspace_bytes(Lt, D), text.device)
     t = glue.tensors
     _status("chorus_text_project", lib.chorus_text_project(_p(text), Lt, td, D, _p(t["w_text1"]), _p(t["b_text1"]),
                                                            _p(t["w_text2"]), _p(t["b_text2"]), _p(ctx), _p(ws),
@@ -901,7 +902,7 @@ class DeviceTime:
         self.cstruct = TimeWeights(*[self.tensors[n].data_ptr() for n in ("w_t1", "b_t1", "w_t2", "b_t2", "w_tp", "b_tp")])
 
 
-def chorus_time_mod(t, tw: DeviceTime, t_mod=None, t_head=None):
+def chorus_time_mod(t, tw: DeviceTime, t_mod=None, t_head=None, ws=None):
     """(t_mod [6, D], t_head [2, D]) of one timestep value."""
     lib = load()
     dev = tw.tensors["w_t1"].device
@@ -912,7 +913,8 @@ def chorus_time_mod(t, tw: DeviceTime, t_mod=None, t_head=None):
         t_head = torch.empty(2, D, dtype=torch.float32, device=dev)
     _chk(t_mod, torch.float32, "t_mod", (6, D))
     _chk(t_head, torch.float32, "t_head", (2, D))
-    ws = _ws(lib.chorus_time_mod_workspace_bytes(D, tw.freq_dim), dev)
+    if ws is None:
+        ws = _ws(lib.chorus_time_mod_workspace_bytes(D, tw.freq_dim), dev)
     _status("chorus_time_mod", lib.chorus_time_mod(float(t), tw.freq_dim, D, C.byref(tw.cstruct), _p(t_mod), _p(t_head),
                                                    _p(ws), ws.numel(), _stream()))
     return t_mod, t_head

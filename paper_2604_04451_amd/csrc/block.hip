@@ -9,12 +9,17 @@
 namespace chorus {
 namespace {
 
+// Benchmark profiler (the library's only process-wide state; off by default, not thread-safe). Events come from a
+// pool that survives chorus_prof_reset, so a warm-up pass with the profiler on creates them and the timed passes
+// only record.
 struct ProfRec {
   int cls;
-  hipEvent_t a, b;
+  int ev;  // index of the start event in the pool; the stop event follows it
 };
 unsigned g_prof_mask = 0;  // bit c set: kernel class c is timed
 std::vector<ProfRec> g_prof;
+std::vector<hipEvent_t> g_prof_pool;
+size_t g_prof_pool_used = 0;
 
 struct ProfScope {
   hipStream_t s;
@@ -22,18 +27,20 @@ struct ProfScope {
   bool live;
   ProfScope(int cls, hipStream_t st) : s(st), live(false) {
     if (!(g_prof_mask & (1u << cls))) return;
-    rec.cls = cls;
-    if (hipEventCreate(&rec.a) != hipSuccess) return;
-    if (hipEventCreate(&rec.b) != hipSuccess) {
-      hipEventDestroy(rec.a);
-      return;
+    while (g_prof_pool.size() < g_prof_pool_used + 2) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) return;
+      g_prof_pool.push_back(e);
     }
-    hipEventRecord(rec.a, s);
+    rec.cls = cls;
+    rec.ev = (int)g_prof_pool_used;
+    g_prof_pool_used += 2;
+    hipEventRecord(g_prof_pool[rec.ev], s);
     live = true;
   }
   ~ProfScope() {
     if (!live) return;
-    hipEventRecord(rec.b, s);
+    hipEventRecord(g_prof_pool[rec.ev + 1], s);
     g_prof.push_back(rec);
   }
 };
@@ -115,11 +122,8 @@ int32_t chorus_prof_enable(int32_t class_mask) {
 }
 
 int32_t chorus_prof_reset(void) {
-  for (auto& r : g_prof) {
-    hipEventDestroy(r.a);
-    hipEventDestroy(r.b);
-  }
-  g_prof.clear();
+  g_prof.clear();  // the events stay in the pool for the next pass
+  g_prof_pool_used = 0;
   return CHORUS_OK;
 }
 
@@ -129,9 +133,9 @@ int32_t chorus_prof_read(int32_t kernel_class, double* total_ms, int32_t* launch
   int n = 0;
   for (auto& r : g_prof) {
     if (r.cls != kernel_class) continue;
-    CHORUS_HIP(hipEventSynchronize(r.b));
+    CHORUS_HIP(hipEventSynchronize(g_prof_pool[r.ev + 1]));
     float ms = 0.f;
-    CHORUS_HIP(hipEventElapsedTime(&ms, r.a, r.b));
+    CHORUS_HIP(hipEventElapsedTime(&ms, g_prof_pool[r.ev], g_prof_pool[r.ev + 1]));
     tot += ms;
     ++n;
   }
