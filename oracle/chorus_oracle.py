@@ -27,6 +27,8 @@ What the paper fixes and what it leaves open
 * Cache update (Sec. 3.1): `cache_insert`; several stored depths per entry enter the schedule as
   `stored_steps` (K1 snaps to a stored depth). `cache_lookup_topk` is the batched retrieval with
   candidates; its column 0 is `cache_lookup`.
+* Low-precision storage of the cached embeddings (bf16 / FP8 E4M3) with an exact re-rank:
+  `cache_lowprec_encode`, `cache_lookup_lowprec`; its result is `cache_lookup`'s by construction.
 * Timestep injection (Sec. 2.1, Fig. 2): `time_mod`, Wan2.1-shaped like the block.
 * The sampler (Sec. 4.1: DPM++ with default settings, no formulas given): the published
   DPM-Solver++ multistep update of order <= 2 in data-prediction form on the rectified-flow
@@ -71,6 +73,103 @@ def cache_lookup(cache_emb, query, tau):
     j = int(np.argmax(s))  # numpy returns the first maximum
     m = float(s[j])
     return j, m, bool(m >= tau)
+
+
+# --------------------------------------------------------------------------
+# Low-precision embedding storage with an exact re-rank (cache maintenance around the
+# retrieval of Sec. 3.1 "Full Reuse"; the paper's cache backend is a vector store, appendix).
+# The result is DEFINED to be `cache_lookup`'s: the low-precision copy only decides which rows
+# are re-scored from the fp32 rows. Encodings are written from the published formats
+# (bfloat16: 1 sign, 8 exponent, 7 fraction bits, fp32's exponent range; OCP FP8 E4M3:
+# 1 sign, 4 exponent bits with bias 7, 3 fraction bits, subnormals, largest finite 448, no
+# infinities), both with round-to-nearest-even.
+# --------------------------------------------------------------------------
+
+def bf16_encode(x):
+    """float32 values -> bf16 bit patterns (uint16), round to nearest, ties to even."""
+    bits = np.ascontiguousarray(x, np.float32).view(np.uint32).astype(np.uint64)
+    lsb = (bits >> np.uint64(16)) & np.uint64(1)
+    return ((bits + np.uint64(0x7FFF) + lsb) >> np.uint64(16)).astype(np.uint16)
+
+
+def bf16_decode(code):
+    return (np.asarray(code, np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32).astype(F64)
+
+
+def fp8_e4m3_decode(code):
+    """OCP FP8 E4M3 bit patterns -> values: (-1)^s 2^(e-7) (1 + f/8) for e > 0, (-1)^s 2^-6 (f/8) for e = 0."""
+    c = np.asarray(code, np.uint8).astype(np.int64)
+    sgn = np.where(c & 0x80, -1.0, 1.0)
+    e = (c >> 3) & 0xF
+    f = c & 0x7
+    mag = np.where(e > 0, np.ldexp(1.0 + f / 8.0, e - 7), np.ldexp(f / 8.0, -6))
+    return sgn * mag
+
+
+def fp8_e4m3_encode(y):
+    """Finite values -> OCP FP8 E4M3 bit patterns: the nearest representable magnitude (ties to the even
+    code), magnitudes beyond 448 saturate to 448. Written as a search over the 127 finite magnitudes."""
+    y = np.asarray(y, F64)
+    mags = fp8_e4m3_decode(np.arange(127, dtype=np.uint8))          # codes 0x00..0x7E, ascending
+    a = np.minimum(np.abs(y), 448.0)
+    hi = np.searchsorted(mags, a, side="left").clip(0, 126)         # first magnitude >= a
+    lo = np.maximum(hi - 1, 0)
+    d_hi, d_lo = mags[hi] - a, a - mags[lo]
+    pick_lo = (d_lo < d_hi) | ((d_lo == d_hi) & (lo % 2 == 0))
+    code = np.where(pick_lo, lo, hi).astype(np.uint8)
+    return np.where(np.signbit(y), code | np.uint8(0x80), code).astype(np.uint8)
+
+
+LOWPREC_FORMATS = ("bf16", "fp8")
+
+
+def cache_lowprec_encode(cache_emb, fmt):
+    """The low-precision copy of the cached prompt embeddings. bf16: every element rounded. fp8: every row is
+    first scaled so that its largest magnitude maps to 448 (inv = 448 / max|c| and y = c * inv, both single fp32
+    operations, the precision in which the integer code is decided), then rounded; an all-zero row encodes as zeros.
+    The scale is not kept: cosine similarity does not depend on it."""
+    c = np.ascontiguousarray(cache_emb, np.float32)
+    if fmt == "bf16":
+        return bf16_encode(c)
+    assert fmt == "fp8"
+    amax = np.abs(c).max(axis=1, keepdims=True) if c.shape[0] else np.zeros((0, 1), np.float32)
+    with np.errstate(divide="ignore"):
+        inv = np.where(amax > 0, np.float32(448.0) / amax, np.float32(0.0)).astype(np.float32)
+    return fp8_e4m3_encode((c * inv).astype(np.float32))
+
+
+def cache_lowprec_decode(codes, fmt):
+    return bf16_decode(codes) if fmt == "bf16" else fp8_e4m3_decode(codes)
+
+
+def lowprec_margin(fmt, d):
+    """Twice the largest change of a cosine score when a row c is replaced by its low-precision copy c^:
+    |cos(q, c^) - cos(q, c)| <= angle(c, c^) <= asin(|c^ - c| / |c|). bf16 keeps 8 significant bits: every element
+    moves by at most 2^-8 of itself. FP8 E4M3 keeps 4 (2^-4 of itself) down to 2^-6, below that the step is 2^-9
+    (at most 2^-10 off), and the scaled row's norm is at least 448."""
+    delta = 2.0 ** -8 if fmt == "bf16" else 2.0 ** -4 + math.sqrt(d) * 2.0 ** -10 / 448.0
+    return 2.0 * math.asin(delta)
+
+
+def cache_lookup_lowprec(cache_emb, codes, fmt, query, tau, margin=None):
+    """Two-stage retrieval: score every row from its low-precision copy, keep the rows within `margin` of the best
+    approximate score, re-score those from the fp32 rows and take the best (lowest index among equal scores).
+    With margin >= lowprec_margin the true best row is always among the candidates, so (index, score, hit) are
+    `cache_lookup`'s. Returns (index, score, hit, number of re-scored rows)."""
+    c = np.asarray(cache_emb, F64)
+    if c.shape[0] == 0:
+        return -1, -math.inf, False, 0
+    if margin is None:
+        margin = lowprec_margin(fmt, c.shape[1])
+    approx = cosine_scores(cache_lowprec_decode(codes, fmt), query)
+    best = approx.max()
+    if not np.isfinite(best):                     # zero-norm query or all rows zero: every exact score is -inf too
+        return 0, -math.inf, False, 0
+    cand = np.nonzero(approx >= best - margin)[0]
+    exact = cosine_scores(c[cand], query)
+    k = int(np.argmax(exact))
+    m = float(exact[k])
+    return int(cand[k]), m, bool(m >= tau), int(cand.size)
 
 
 # --------------------------------------------------------------------------

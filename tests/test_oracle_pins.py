@@ -1001,3 +1001,109 @@ def test_time_mod_vs_torch_and_closed_forms():
                                atol=1e-12)
     # different timesteps give different modulation
     assert np.abs(O.time_mod(420.0, tw, bs.D, 16)[0] - t_mod).max() > 1e-4
+
+
+# ---------------------------------------------- low-precision embedding storage with exact re-rank
+
+def _nearest_even_brute(x, values):
+    """Nearest of the sorted representable `values` to x, ties to the one whose position is even."""
+    best, bi = None, None
+    for i, v in enumerate(values):
+        d = abs(v - x)
+        if best is None or d < best or (d == best and i % 2 == 0 and bi % 2 == 1):
+            best, bi = d, i
+    return bi
+
+
+def test_fp8_e4m3_format_and_rounding():
+    """The FP8 E4M3 table against the format's published corner values, the encoder against a brute-force nearest
+    search and against torch's conversion; decode(encode(v)) = v on every representable value."""
+    mags = O.fp8_e4m3_decode(np.arange(127, dtype=np.uint8))
+    assert mags[0] == 0.0 and mags[1] == 2.0 ** -9 and mags[7] == 7 * 2.0 ** -9          # subnormals
+    assert mags[8] == 2.0 ** -6 and mags[0x38] == 1.0 and mags[0x7E] == 448.0            # smallest normal, one, largest
+    assert (np.diff(mags) > 0).all()
+    np.testing.assert_array_equal(O.fp8_e4m3_decode(np.arange(128, 255, dtype=np.uint8)), -mags)
+    np.testing.assert_array_equal(O.fp8_e4m3_encode(mags), np.arange(127, dtype=np.uint8))
+    np.testing.assert_array_equal(O.fp8_e4m3_encode(-mags[1:]), np.arange(129, 255, dtype=np.uint8))
+    rng = synth.stream(31, "fp8")
+    xs = np.concatenate([rng.normal(size=300) * 10.0 ** rng.uniform(-4, 2.6, size=300),
+                         (mags[:-1] + mags[1:]) / 2, [448.0, 460.0, 1e9, 2.0 ** -10, 2.0 ** -11, 0.0]])
+    enc = O.fp8_e4m3_encode(xs)
+    for x, e in zip(xs, enc):
+        want = _nearest_even_brute(min(abs(x), 448.0), list(mags))
+        assert (e & 0x7F) == want and bool(e & 0x80) == bool(np.signbit(x)), (x, e, want)
+    if hasattr(torch, "float8_e4m3fn"):
+        y = np.clip(xs, -448, 448).astype(np.float32)
+        t8 = torch.from_numpy(y).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        np.testing.assert_array_equal(O.fp8_e4m3_encode(y), t8)
+
+
+def test_bf16_rounding_vs_brute_force_and_torch():
+    rng = synth.stream(32, "bf16")
+    x = (rng.normal(size=2000) * 10.0 ** rng.uniform(-6, 6, size=2000)).astype(np.float32)
+    enc = O.bf16_encode(x)
+    np.testing.assert_array_equal(enc, torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+    # brute force on a few: the two neighbouring bf16 values around x, nearest wins, ties to the even code
+    for v, e in list(zip(x, enc))[:200]:
+        trunc = int(np.float32(v).view(np.uint32)) >> 16
+        lo, hi = O.bf16_decode(np.uint16(trunc)), O.bf16_decode(np.uint16(trunc + 1))
+        dl, dh = abs(float(v) - lo), abs(hi - float(v))
+        want = trunc if dl < dh or (dl == dh and trunc % 2 == 0) else trunc + 1
+        assert e == want
+    exact_tie = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8], np.float32)          # halfway cases
+    np.testing.assert_array_equal(O.bf16_decode(O.bf16_encode(exact_tie)), [1.0, 1.0 + 2.0 ** -6])
+
+
+def _same_lookup(a, b):
+    """Index and hit exactly; the score up to the rounding order of the matrix product (a dot product taken inside a
+    product over a few rows and inside one over all rows may differ in the last bit)."""
+    return a[0] == b[0] and a[2] == b[2] and (a[1] == b[1] or abs(a[1] - b[1]) <= 1e-14)
+
+
+@pytest.mark.parametrize("fmt", O.LOWPREC_FORMATS)
+def test_lowprec_lookup_is_the_exact_lookup(fmt):
+    """The two-stage retrieval returns cache_lookup's result on clustered caches, on near-duplicate rows that the
+    low-precision copy cannot tell apart (or ranks the wrong way round), with duplicates, zero rows and a zero
+    query; the score change stays inside the bound the margin is derived from."""
+    for seed, (N, d) in enumerate([(64, 32), (300, 256), (257, 768)]):
+        cache = synth.cache_embeddings(N, d, seed=seed)
+        codes = O.cache_lowprec_encode(cache, fmt)
+        assert codes.shape == cache.shape and codes.dtype == (np.uint16 if fmt == "bf16" else np.uint8)
+        half = O.lowprec_margin(fmt, d) / 2
+        for trial, near in enumerate((N // 2, None, 0, N - 1)):
+            q = synth.cache_query(cache, seed=seed, near=near, trial=trial)
+            exact = O.cosine_scores(cache, q)
+            approx = O.cosine_scores(O.cache_lowprec_decode(codes, fmt), q)
+            assert np.abs(approx - exact).max() <= half
+            j, m, hit, n = O.cache_lookup_lowprec(cache, codes, fmt, q, 0.75)
+            assert _same_lookup((j, m, hit), O.cache_lookup(cache, q, 0.75)) and 1 <= n <= N
+    # adversarial: rows that differ from the query's source by less than the storage resolution
+    cache = synth.cache_embeddings(40, 64, seed=9)
+    q = cache[7].copy()
+    for k, eps in enumerate((1e-4, 3e-4, 1e-3)):
+        cache[20 + k] = cache[7] + eps * synth.normal(9, f"adv{k}", (64,))
+    cache[33] = cache[7]                                   # an exact duplicate at a higher index
+    codes = O.cache_lowprec_encode(cache, fmt)
+    approx = O.cosine_scores(O.cache_lowprec_decode(codes, fmt), q)
+    j, m, hit, n = O.cache_lookup_lowprec(cache, codes, fmt, q, 0.75)
+    assert _same_lookup((j, m, hit), O.cache_lookup(cache, q, 0.75)) and (j, hit) == (7, True) and n >= 5
+    assert O.cache_lookup_lowprec(cache, codes, fmt, q, 0.75, margin=0.0)[3] >= 1
+    # the approximate ranking alone would not do: with these rows some other entry ties or beats row 7
+    assert (approx[[20, 21, 22, 33]] >= approx[7] - 1e-12).any()
+    # zero rows, zero query, empty cache
+    cache[3] = 0
+    codes = O.cache_lowprec_encode(cache, fmt)
+    assert not codes[3].any()
+    assert _same_lookup(O.cache_lookup_lowprec(cache, codes, fmt, q, 0.75)[:3], O.cache_lookup(cache, q, 0.75))
+    assert O.cache_lookup_lowprec(cache, codes, fmt, np.zeros(64), 0.75)[:3] == O.cache_lookup(cache, np.zeros(64), 0.75)
+    assert O.cache_lookup_lowprec(np.zeros((0, 64)), np.zeros((0, 64), np.uint8), fmt, q, 0.75) == (-1, -math.inf, False, 0)
+
+
+def test_fp8_row_scaling():
+    """Each row uses the whole FP8 range (its largest magnitude encodes as 448) whatever its norm, and rows that
+    differ only by a positive factor encode alike up to the fp32 rounding of the scale."""
+    cache = synth.cache_embeddings(16, 128, seed=4)
+    codes = O.cache_lowprec_encode(cache, "fp8")
+    assert ((codes & 0x7F).max(axis=1) == 0x7E).all()
+    scaled = (cache * np.float32(1024.0)).astype(np.float32)          # a power of two: exactly the same codes
+    np.testing.assert_array_equal(O.cache_lowprec_encode(scaled, "fp8"), codes)
