@@ -85,6 +85,41 @@ int32_t chorus_cache_lookup_static(const float* cache_emb, int64_t N, int32_t d,
                                    chorus_lookup_result* out, void* stream);
 
 /* ------------------------------------------------------------------------
+ * The same retrieval over a low-precision copy of the cached embeddings (cache maintenance
+ * around Sec. 3.1 "Full Reuse"; the appendix's cache backend): the scan reads bf16 rows (half
+ * the bytes of the fp32 scan) or FP8 E4M3 rows (a quarter); every row whose approximate score
+ * lies within a margin of the best approximate score is then re-scored from its fp32 row, and
+ * the best of those is returned. The margin is twice the most a cosine can move when a row is
+ * replaced by its low-precision copy (bf16: every element within 2^-8 of itself; FP8: 2^-4,
+ * and 2^-10 of the scaled row's largest magnitude / 448 below 2^-6), so the true best row is
+ * always re-scored: index, score and hit are chorus_cache_lookup's, bit for bit.
+ *   chorus_cache_lowprec_bytes   device bytes of the copy of N rows (N d elements of 2 or 1 bytes)
+ *   chorus_cache_lowprec_store   encodes n_rows fp32 rows (emb dev [n_rows, d]) into out dev
+ *                                [n_rows, d]; call it on the whole cache once and on an entry's
+ *                                row after chorus_cache_insert. bf16: round to nearest even.
+ *                                FP8: the row times 448 / max|row| (two fp32 operations), rounded
+ *                                to nearest even; the scale is not kept (a cosine does not
+ *                                depend on it); an all-zero row encodes as zeros.
+ *   chorus_cache_lookup_lowprec  cache_emb dev [N, d] fp32 (read only for the re-scored rows),
+ *                                cache_lp dev [N, d] codes, n_rescored dev int32 or NULL (the
+ *                                number of rows re-scored), ws dev of
+ *                                chorus_cache_lookup_lowprec_workspace_bytes(N) bytes.
+ * d a multiple of 16; N at most 2^31 - 2. Three launches: the low-precision scan, the re-rank
+ * (in the scan's launch shape: when every row is a candidate, as with FP8 on a query far from
+ * every entry, it costs one fp32 scan; usually one wave has work) and a single-workgroup pick.
+ * Errors: CHORUS_E_ARG (null / misaligned pointer, unknown format), CHORUS_E_SHAPE,
+ * CHORUS_E_WORKSPACE, CHORUS_E_HIP.
+ * ------------------------------------------------------------------------ */
+#define CHORUS_LP_BF16 0
+#define CHORUS_LP_FP8 1
+size_t chorus_cache_lowprec_bytes(int64_t N, int32_t d, int32_t format);
+int32_t chorus_cache_lowprec_store(const float* emb, int64_t n_rows, int32_t d, int32_t format, void* out, void* stream);
+size_t chorus_cache_lookup_lowprec_workspace_bytes(int64_t N);
+int32_t chorus_cache_lookup_lowprec(const float* cache_emb, const void* cache_lp, int32_t format, int64_t N, int32_t d,
+                                    const float* query, float tau, chorus_lookup_result* out, int32_t* n_rescored, void* ws,
+                                    size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * The same retrieval for a batch of queued requests, with candidates: the k best entries
  * by cosine similarity for each of Q prompt embeddings. The cache is streamed once per 32
  * queries (a [N, d] x [d, Q] fp32 contraction on the matrix pipe), not once per query.

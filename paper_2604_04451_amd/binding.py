@@ -104,6 +104,10 @@ def load():
         "chorus_cache_lookup_workspace_bytes": (sz, [i64]),
         "chorus_cache_lookup": (i32, [vp, i64, i32, vp, f32, vp, vp, sz, vp]),
         "chorus_cache_lookup_static": (i32, [vp, i64, i32, vp, f32, vp, vp]),
+        "chorus_cache_lowprec_bytes": (sz, [i64, i32, i32]),
+        "chorus_cache_lowprec_store": (i32, [vp, i64, i32, i32, vp, vp]),
+        "chorus_cache_lookup_lowprec_workspace_bytes": (sz, [i64]),
+        "chorus_cache_lookup_lowprec": (i32, [vp, vp, i32, i64, i32, vp, f32, vp, vp, vp, sz, vp]),
         "chorus_cache_insert": (i32, [vp, vp, i64, i64, i32, i64, vp, vp, vp]),
         "chorus_cache_lookup_batch_workspace_bytes": (sz, [i64, i32, i32]),
         "chorus_cache_lookup_batch": (i32, [vp, i64, i32, vp, i32, f32, i32, vp, vp, vp, vp, sz, vp]),
@@ -252,6 +256,44 @@ def chorus_cache_lookup_static(cache_emb, query, tau, out):
     _status("chorus_cache_lookup_static", lib.chorus_cache_lookup_static(_p(cache_emb) if N else C.c_void_p(0), N, d,
                                                                          _p(query), float(tau), _p(out), _stream()))
     return out
+
+
+LP_BF16, LP_FP8 = 0, 1
+
+
+def chorus_cache_lowprec_store(emb, fmt, out=None):
+    """Low-precision copy of fp32 rows [n, d]: a uint16 (bf16 bits) or uint8 (FP8 E4M3 codes) device tensor [n, d]."""
+    lib = load()
+    _chk(emb, torch.float32, "emb")
+    n, d = emb.shape
+    if out is None:
+        out = torch.empty(n, d, dtype=torch.int16 if fmt == LP_BF16 else torch.uint8, device=emb.device)
+    _status("chorus_cache_lowprec_store", lib.chorus_cache_lowprec_store(_p(emb) if n else C.c_void_p(0), n, d, int(fmt),
+                                                                         _p(out) if n else C.c_void_p(0), _stream()))
+    return out
+
+
+def chorus_cache_lookup_lowprec(cache_emb, cache_lp, fmt, query, tau, out=None, n_rescored=None, ws=None):
+    """Returns (result words [3] int32 as chorus_cache_lookup, n_rescored [1] int32), both on the device."""
+    lib = load()
+    _chk(cache_emb, torch.float32, "cache_emb")
+    _chk(query, torch.float32, "query")
+    N, d = cache_emb.shape
+    if tuple(cache_lp.shape) != (N, d) or cache_lp.element_size() != (2 if fmt == LP_BF16 else 1) or not cache_lp.is_cuda:
+        raise TypeError("cache_lp: wrong shape or element size")
+    if query.numel() != d:
+        raise TypeError("query: wrong length")
+    if out is None:
+        out = torch.empty(3, dtype=torch.int32, device=query.device)
+    if n_rescored is None:
+        n_rescored = torch.empty(1, dtype=torch.int32, device=query.device)
+    if ws is None:
+        ws = _ws(lib.chorus_cache_lookup_lowprec_workspace_bytes(N), query.device)
+    _status("chorus_cache_lookup_lowprec",
+            lib.chorus_cache_lookup_lowprec(_p(cache_emb) if N else C.c_void_p(0), _p(cache_lp) if N else C.c_void_p(0),
+                                            int(fmt), N, d, _p(query), float(tau), _p(out), _p(n_rescored), _p(ws),
+                                            ws.numel(), _stream()))
+    return out, n_rescored
 
 
 def chorus_cache_lookup_batch(cache_emb, queries, tau, k=1, ws=None):

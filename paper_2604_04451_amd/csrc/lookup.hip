@@ -1,6 +1,7 @@
 // Stage-1 retrieval: top-1 cosine similarity over the prompt-embedding cache
 // (Sec. 3.1 "Full Reuse"). HBM-bound: the [N, d] fp32 cache is streamed once.
 #include "common.h"
+#include "lookup_row.h"
 
 namespace chorus {
 
@@ -47,46 +48,18 @@ __global__ __launch_bounds__(kWaves * 64) void lookup_scan_kernel(const float* _
   int32_t bi = 0x7fffffff;  // larger than any index
   const long stride = (long)gridDim.x * kWaves;
   for (long row = (long)blockIdx.x * kWaves + wave; row < N; row += stride) {
-    const float4* c4 = reinterpret_cast<const float4*>(cache + row * (long)d);
-    float dot = 0.f, cc = 0.f;
-    qq = 0.f;
-    int i = lane;
-    // 8 independent 16-byte loads in flight per lane
-    for (; i + 7 * 64 < n4; i += 8 * 64) {
-      float4 c[8], q[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) c[u] = ld_stream_f4(&c4[i + u * 64]);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) q[u] = q4[i + u * 64];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        dot += c[u].x * q[u].x + c[u].y * q[u].y + c[u].z * q[u].z + c[u].w * q[u].w;
-        cc += c[u].x * c[u].x + c[u].y * c[u].y + c[u].z * c[u].z + c[u].w * c[u].w;
-        qq += q[u].x * q[u].x + q[u].y * q[u].y + q[u].z * q[u].z + q[u].w * q[u].w;
-      }
-    }
-    for (; i < n4; i += 64) {
-      float4 c = ld_stream_f4(&c4[i]);
-      float4 q = q4[i];
-      dot += c.x * q.x + c.y * q.y + c.z * q.z + c.w * q.w;
-      cc += c.x * c.x + c.y * c.y + c.z * c.z + c.w * c.w;
-      qq += q.x * q.x + q.y * q.y + q.z * q.z + q.w * q.w;
-    }
-    dot = wave_sum(dot);
-    cc = wave_sum(cc);
-    const float nc = sqrtf(cc);
-    float r = nc > 0.f ? dot / nc : -INFINITY;
-    if (!(r == r)) r = -INFINITY;
+    float dot, cc;
+    fp32_row_products(reinterpret_cast<const float4*>(cache + row * (long)d), q4, n4, lane, dot, cc, qq);
+    const float r = row_ratio(dot, cc);
     if (r > best) {  // rows ascend within a wave: a strict comparison keeps the lowest index
       best = r;
       bi = (int32_t)row;
     }
   }
-  qq = wave_sum(qq);
   if (lane == 0) {
     sv[wave] = best;
     si[wave] = bi;
-    if (blockIdx.x == 0 && wave == 0) *qnorm2 = qq;
+    if (blockIdx.x == 0 && wave == 0) *qnorm2 = qq;  // wave 0 of workgroup 0 always has a row
   }
   __syncthreads();
   if (threadIdx.x == 0) {

@@ -68,6 +68,19 @@ def main():
         wsb = torch.empty(B.load().chorus_cache_lookup_batch_workspace_bytes(N, d, Q), dtype=torch.uint8, device=DEV)
         med, best = timeit(lambda i: B.chorus_cache_lookup_batch(caches[i % 10], qs, 0.75, 8, wsb), n)
         report(f"cache_lookup_batch Q={Q} k=8 (2 launches)", N * d * 4 + Q * d * 4, med, best)
+    # the scan over a low-precision copy with the exact re-rank (3 launches): a query near an entry (one row is
+    # re-scored) and one far from every entry (bf16: a handful; FP8: its proven margin keeps every row, the re-rank
+    # then is a whole fp32 scan)
+    for fmt, name, eb in ((B.LP_BF16, "bf16", 2), (B.LP_FP8, "fp8", 1)):
+        lps = [B.chorus_cache_lowprec_store(c, fmt) for c in caches]
+        wsl = torch.empty(B.load().chorus_cache_lookup_lowprec_workspace_bytes(N), dtype=torch.uint8, device=DEV)
+        nres = torch.empty(1, dtype=torch.int32, device=DEV)
+        for qname, qq in (("near an entry", [c[123] + 0.3 * torch.randn(d, device=DEV, generator=g) for c in caches]),
+                          ("far from all", [torch.randn(d, device=DEV, generator=g) for _ in caches])):
+            med, best = timeit(lambda i: B.chorus_cache_lookup_lowprec(caches[i % 10], lps[i % 10], fmt, qq[i % 10], 0.75, out, nres, wsl), n)
+            k = int(nres.cpu()[0])
+            report(f"cache_lookup_lowprec {name}, query {qname} ({k} re-scored)", N * d * eb + k * d * 4 + d * 4, med, best)
+        del lps
     del caches
 
     # ---- latent-sized kernels: 24 triples of 8.4 MB

@@ -66,6 +66,16 @@ def test_argument_validation_returns_codes():
     assert lib.chorus_cache_lookup_static(C.c_void_p(16), -1, 8, C.c_void_p(16), 0.5, out, null) == B.E_ARG
     assert lib.chorus_cache_lookup_static(C.c_void_p(16), 1 << 31, 8, C.c_void_p(16), 0.5, out, null) == B.E_SHAPE
     assert lib.chorus_cache_lookup_static(C.c_void_p(16), 4, 8, C.c_void_p(16), 0.5, None, null) == B.E_ARG
+    # low-precision storage: sizes, unknown format, width not a multiple of 16, missing workspace
+    assert lib.chorus_cache_lowprec_bytes(10, 64, B.LP_BF16) == 1280 and lib.chorus_cache_lowprec_bytes(10, 64, B.LP_FP8) == 640
+    assert lib.chorus_cache_lowprec_bytes(10, 64, 7) == 0
+    assert lib.chorus_cache_lowprec_store(C.c_void_p(16), 4, 64, 7, C.c_void_p(16), null) == B.E_ARG
+    assert lib.chorus_cache_lowprec_store(C.c_void_p(16), 4, 24, B.LP_FP8, C.c_void_p(16), null) == B.E_SHAPE
+    assert lib.chorus_cache_lowprec_store(C.c_void_p(16), 0, 64, B.LP_FP8, null, null) == B.OK
+    assert lib.chorus_cache_lookup_lowprec(C.c_void_p(16), C.c_void_p(16), B.LP_BF16, 4, 64, C.c_void_p(16), 0.5, out, null, null, 0, null) == B.E_WORKSPACE
+    assert lib.chorus_cache_lookup_lowprec(C.c_void_p(16), C.c_void_p(16), 3, 4, 64, C.c_void_p(16), 0.5, out, null, C.c_void_p(16), 1 << 20, null) == B.E_ARG
+    assert lib.chorus_cache_lookup_lowprec(C.c_void_p(16), C.c_void_p(16), B.LP_FP8, 4, 40, C.c_void_p(16), 0.5, out, null, C.c_void_p(16), 1 << 20, null) == B.E_SHAPE
+    assert lib.chorus_cache_lookup_lowprec_workspace_bytes(4096) >= 4096 * 4
     # schedule
     assert lib.chorus_denoise_schedule(0.9, 0.75, -1, None, None, None, None) == B.E_ARG
     assert lib.chorus_denoise_schedule(0.9, 0.75, 0, None, None, None, None) == B.OK
