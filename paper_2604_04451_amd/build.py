@@ -52,5 +52,39 @@ def build(verbose: bool = True, jobs: int = 8) -> str:
     return LIB
 
 
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+             "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
+def build_sanitized_driver(driver_cpp: str, jobs: int = 8) -> str:
+    """The library's sources with AddressSanitizer and UndefinedBehaviorSanitizer on the HOST code (the device code
+    is compiled as usual and never runs), linked with a host driver program into an executable under _build/san.
+    Returns its path. Used by the CPU tests to run the host-only entry points and every argument-validation path
+    under the sanitizers."""
+    san = os.path.join(OBJ, "san")
+    os.makedirs(san, exist_ok=True)
+
+    def comp(src_path: str) -> str:
+        obj = os.path.join(san, os.path.splitext(os.path.basename(src_path))[0] + ".o")
+        cmd = [HIPCC, *FLAGS, *SAN_FLAGS, "-c", src_path, "-o", obj]
+        if src_path.endswith(".cpp"):
+            cmd.insert(1, "-x")
+            cmd.insert(2, "hip")
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc (sanitized) failed on {src_path}:\n{r.stdout}\n{r.stderr}")
+        return obj
+
+    paths = [os.path.join(CSRC, f) for f in sources()] + [driver_cpp]
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(comp, paths))
+    exe = os.path.join(san, "sanitize_driver")
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-o", exe, *objs],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link (sanitized) failed:\n{r.stdout}\n{r.stderr}")
+    return exe
+
+
 if __name__ == "__main__":
     build()

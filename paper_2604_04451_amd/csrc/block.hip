@@ -65,7 +65,7 @@ inline long pad_text(long Lt) { return (long)align_up((size_t)Lt, 64); }
 BlockWs carve(const chorus_block_shape& sh, long Ls, void* base) {
   const size_t D = sh.D, F = sh.F, Lt = sh.Lt;
   const size_t Lpad = pad_rows(Ls), LtPad = pad_text(Lt);
-  uint8_t* p = (uint8_t*)base;
+  const BytePtr p(base);
   size_t off = 0;
   auto take = [&](size_t elems) {
     uint16_t* r = (uint16_t*)(p + off);

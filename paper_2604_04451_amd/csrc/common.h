@@ -50,6 +50,14 @@ struct DynLdsOnce {
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Base address of a workspace that is being carved into regions. The base is null when only the total size is
+// wanted, and offsetting a null pointer is undefined, so the addresses are formed in integer arithmetic.
+struct BytePtr {
+  uintptr_t addr;
+  explicit BytePtr(void* p) : addr(reinterpret_cast<uintptr_t>(p)) {}
+  uint8_t* operator+(size_t off) const { return reinterpret_cast<uint8_t*>(addr + off); }
+};
+
 typedef __bf16 bf16_t;
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;

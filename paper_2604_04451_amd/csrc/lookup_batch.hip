@@ -288,7 +288,7 @@ BatchWs carve_batch(long N, int d, int Qc, void* base) {
   const BatchPlan p = plan_batch(N, d);
   const int QP = Qc > 16 ? 32 : 16;
   const long rows = p.tiles > 0 ? (long)p.tiles * kBR : kBR;  // padded to whole row tiles
-  uint8_t* b = (uint8_t*)base;
+  const BytePtr b(base);
   size_t off = 0;
   auto take = [&](size_t bytes) {
     void* r = b + off;

@@ -35,7 +35,7 @@ struct LpWs {
   size_t bytes;
 };
 LpWs carve_lp(long N, void* base) {
-  uint8_t* p = (uint8_t*)base;
+  const BytePtr p(base);
   LpWs w;
   size_t off = 0;
   w.qnorm2 = (float*)(p + off);

@@ -18,7 +18,7 @@ struct StepWs {
 
 StepWs carve_step(const chorus_model_shape& m, long Ls, void* base) {
   StepWs w;
-  uint8_t* p = (uint8_t*)base;
+  const BytePtr p(base);
   size_t off = 0;
   const long rows = Ls > 0 ? Ls : 1;
   w.x = (float*)(p + off);
@@ -111,7 +111,7 @@ struct SolverWs {
 
 SolverWs carve_solver(const chorus_model_shape& m, long Ls, int cfg, void* base) {
   SolverWs w;
-  uint8_t* p = (uint8_t*)base;
+  const BytePtr p(base);
   size_t off = 0;
   const long rows = Ls > 0 ? Ls : 1;
   const int P = m.C * m.ph * m.pw;
@@ -307,7 +307,7 @@ struct RunWs {
 
 RunWs carve_run(const chorus_model_shape& m, int64_t N, void* base) {
   RunWs w;
-  uint8_t* p = (uint8_t*)base;
+  const BytePtr p(base);
   size_t off = 0;
   const int64_t Ltok = (int64_t)m.T * (m.Hl / m.ph) * (m.Wl / m.pw);
   auto take = [&](size_t bytes) {
