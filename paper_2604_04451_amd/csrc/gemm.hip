@@ -133,57 +133,6 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16 (&acc)[TM][TN], const
   }
 }
 
-// bf16 epilogue through LDS: the wave's 128 x 64 tile is converted (bias, optional GELU) and
-// written to a private LDS region as [m][n] in two halves of 64 rows, then read back with
-// 8 lanes per row of 128 bytes, so every global store instruction writes 8 full 128-byte
-// lines instead of 32 scattered 8-byte pieces. `cw` is this wave's region of 64 x 68 elements;
-// the caller guarantees that no wave still reads the main-loop LDS it overlays.
-constexpr int EPI_LDS_STRIDE = 64 + 4;
-constexpr int EPI_LDS_WAVE = 64 * EPI_LDS_STRIDE;  // elements per wave
-
-template <int EPI>
-__device__ __forceinline__ void gemm_epilogue_bf16_lds(const f32x16 (&acc)[4][2], const EpiArgs& ep, uint16_t* cw,
-                                                       long m_wave0, int n_wave0, long M, int N, int lane) {
-  const int lrow = lane & 31, c4 = (lane >> 5) * 4;
-  const int rrow = lane >> 3, rch = (lane & 7) * 8;
-#pragma unroll
-  for (int half = 0; half < 2; ++half) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int nl = 32 * j + 8 * g + c4;  // column inside the wave tile
-        const int n = n_wave0 + nl;
-        float4 bias = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (ep.bias && n < N) bias = *reinterpret_cast<const float4*>(ep.bias + n);
-#pragma unroll
-        for (int i2 = 0; i2 < 2; ++i2) {
-          const f32x16& a = acc[2 * half + i2][j];
-          float v0 = a[4 * g + 0] + bias.x, v1 = a[4 * g + 1] + bias.y, v2 = a[4 * g + 2] + bias.z,
-                v3 = a[4 * g + 3] + bias.w;
-          if (EPI == CHORUS_EPI_GELU_BF16) {
-            v0 = gelu_tanh_fast(v0); v1 = gelu_tanh_fast(v1); v2 = gelu_tanh_fast(v2); v3 = gelu_tanh_fast(v3);
-          }
-          uint2 w;
-          w.x = pack_bf16x2(v0, v1);
-          w.y = pack_bf16x2(v2, v3);
-          *reinterpret_cast<uint2*>(cw + (32 * i2 + lrow) * EPI_LDS_STRIDE + nl) = w;
-        }
-      }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");  // LDS ops of one wave stay in order
-#pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int row = 8 * it + rrow;
-      const long m = m_wave0 + 64 * half + row;
-      const int n = n_wave0 + rch;
-      const u32x4 v = *reinterpret_cast<const u32x4*>(cw + row * EPI_LDS_STRIDE + rch);
-      if (m < M && n < N) *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(ep.out) + m * N + n) = v;
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-  }
-}
-
 // fp32 residual epilogue through LDS for a 128 x 64 wave tile: 32 rows at a time are written to a private LDS
 // region as [32][64] floats (row stride 68 floats, so the 16-byte writes of 16 lanes fall in distinct banks), then
 // read back with 16 lanes per row, so every global load / store instruction moves four full 256-byte row segments
@@ -342,24 +291,155 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t* __res
 }
 
 // ---------------------------------------------------------------------------
-// Large-problem kernel: 256 x 256 x 64 tiles, 8 waves (2 x 4, each 128 x 64), operands
-// streamed global -> LDS directly (global_load_lds_dwordx4, no register staging, no
-// LDS store instructions), two LDS stages, one barrier per k-step: after the barrier
-// that publishes tile kt, the loads of tile kt+1 are issued into the other stage and
-// stay in flight during the 32 MFMAs per wave of tile kt.
+// Large-problem kernel: 256 x 256 x 64 tiles, four waves (one per SIMD), each wave a 128 x 128 quadrant as 8 x 8
+// accumulators of v_mfma_f32_16x16x32_bf16 (256 accumulator registers). Per unit of work a 16x16x32 MFMA reads and
+// writes half the accumulator registers of a 32x32x16 one (k = 32 per instruction instead of 16), which is what the
+// power-managed part rewards; a 16-byte LDS fragment (16 rows x 8 k per quarter wave) feeds eight MFMAs.
 //
-// A direct load writes the 64 lanes' 16-byte pieces to consecutive LDS addresses,
-// i.e. 8 unpadded rows of 128 bytes. Bank conflicts are avoided by an XOR swizzle
-// instead of padding: the 16-byte chunk c of row r lives at chunk position
-// c ^ ((r >> 1) & 7); the loading lane for position p of row r fetches global chunk
-// p ^ ((r >> 1) & 7). Sixteen consecutive rows read at one logical chunk then cover
-// all 64 banks exactly once.
+// Both operands stream global -> LDS directly (global_load_lds_dwordx4: no register staging, no LDS store
+// instructions) into two 64 KB stages. A direct load writes the 64 lanes' 16-byte pieces to consecutive LDS
+// addresses, i.e. 8 unpadded rows of 128 bytes. Bank conflicts are avoided by an XOR swizzle instead of padding: the
+// 16-byte chunk c of row r lives at chunk position c ^ ((r >> 1) & 7); the loading lane for position p of row r
+// fetches global chunk p ^ ((r >> 1) & 7). (A 16-byte-per-lane LDS read is served 16 lanes a cycle: the four-lane
+// groups of one half wave whose group index has the same bit parity, groups 0, 3, 5, 6 together and 1, 2, 4, 7. With
+// lane = 16 * chunk + row those are rows 0-3 and 12-15 of one chunk with rows 4-11 of its neighbour, which this
+// swizzle spreads over all 64 banks: measured, no conflict cycles.)
+//
+// Operand layout of v_mfma_f32_16x16x32_bf16: lane l supplies row (or column) l % 16 and the 8 k-values
+// 8 (l / 16) .. + 8; it receives column l % 16 and rows 4 (l / 16) .. + 4 of the 16 x 16 result. The weight fragment is
+// the row operand and the activation fragment the column operand, so a lane holds one output row m and four
+// consecutive output columns n.
+//
+// One loop iteration per k-step, hand-laid for a single wave per SIMD (nothing else hides a gap between two MFMAs):
+// half-step 0 (64 MFMAs) with the LDS reads of half-step 1's fragments and the second half of the next step's loads;
+// the first 32 MFMAs of half-step 1; vmcnt(0) + barrier; the last 32 MFMAs with the LDS reads of the next step's
+// first fragments and the first half of the loads of the step after next (their stage is free behind the barrier).
+// The MFMAs are volatile assembly, in place on their accumulators: left to the register allocator every result gets
+// a new home, at the price of several hundred accumulator moves per k-step.
 // ---------------------------------------------------------------------------
+
+// bf16 (optionally GELU) epilogue of the 16x16 layout: 32 output rows at a time go through a private LDS region as
+// [32][128] bf16 (row stride 136), then leave as full 256-byte row segments.
+constexpr int E16_BF_STRIDE = 128 + 8;
+constexpr int E16_BF_WAVE = 32 * E16_BF_STRIDE;  // elements per wave
 template <int EPI>
-__global__ __launch_bounds__(512, 2) void gemm_dl_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
-                                                         long M, int N, int K, EpiArgs ep, int tiles_m, int tiles_n) {
-  constexpr int BM = 256, BN = 256, WM = 128, WN = 64;
-  constexpr int TM = WM / 32, TN = WN / 32;
+__device__ __forceinline__ void gemm16_epilogue_bf16(const f32x4 (&acc)[8][8], const EpiArgs& ep, uint16_t* cw, long m_wave0,
+                                                     int n_wave0, long M, int N, int lane) {
+  const int lj = lane & 15, lg = lane >> 4;
+  const int rrow = lane >> 4, rcol = (lane & 15) * 8;  // read-back: 4 rows per instruction, 16 lanes x 16 bytes per row
+  float4 bias[8];
+#pragma unroll
+  for (int nb = 0; nb < 8; ++nb) {
+    const int n = n_wave0 + 16 * nb + 4 * lg;
+    bias[nb] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (ep.bias && n < N) bias[nb] = *reinterpret_cast<const float4*>(ep.bias + n);
+  }
+#pragma unroll
+  for (int mp = 0; mp < 4; ++mp) {  // pairs of 16-row blocks
+#pragma unroll
+    for (int mh = 0; mh < 2; ++mh)
+#pragma unroll
+      for (int nb = 0; nb < 8; ++nb) {
+        const f32x4& a = acc[nb][2 * mp + mh];
+        float v0 = a[0] + bias[nb].x, v1 = a[1] + bias[nb].y, v2 = a[2] + bias[nb].z, v3 = a[3] + bias[nb].w;
+        if (EPI == CHORUS_EPI_GELU_BF16) {
+          v0 = gelu_tanh_fast(v0); v1 = gelu_tanh_fast(v1); v2 = gelu_tanh_fast(v2); v3 = gelu_tanh_fast(v3);
+        }
+        uint2 w;
+        w.x = pack_bf16x2(v0, v1);
+        w.y = pack_bf16x2(v2, v3);
+        *reinterpret_cast<uint2*>(cw + (16 * mh + lj) * E16_BF_STRIDE + 16 * nb + 4 * lg) = w;
+      }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int row = 4 * it + rrow;
+      const long m = m_wave0 + 32 * mp + row;
+      const int n = n_wave0 + rcol;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(cw + row * E16_BF_STRIDE + rcol);
+      if (m < M && n < N) *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(ep.out) + m * N + n) = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// fp32 gated-residual epilogue of the 16x16 layout: 16 output rows at a time through a private LDS region as
+// [16][128] fp32 (row stride 132), read back with 32 lanes per row; the residual rows are requested before the LDS
+// round trip. out[m][n] += gate[n] * scale * (acc + bias[n]).
+constexpr int E16_F32_STRIDE = 128 + 4;
+constexpr int E16_F32_WAVE = 16 * E16_F32_STRIDE;  // floats per wave
+__device__ __forceinline__ void gemm16_epilogue_resid(const f32x4 (&acc)[8][8], const EpiArgs& ep, float* cw, long m_wave0,
+                                                      int n_wave0, long M, int N, int lane) {
+  const int lj = lane & 15, lg = lane >> 4;
+  const int rrow = lane >> 5, rcol = (lane & 31) * 4;  // read-back: 2 rows per instruction, 32 lanes x 16 bytes per row
+  const int n = n_wave0 + rcol;
+  const bool n_ok = n < N;
+  f32x4 bias = {0.f, 0.f, 0.f, 0.f}, gate = {1.f, 1.f, 1.f, 1.f};
+  if (n_ok) {
+    if (ep.bias) bias = *reinterpret_cast<const f32x4*>(ep.bias + n);
+    if (ep.gate0 || ep.gate1) {
+      gate = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (ep.gate0) gate += *reinterpret_cast<const f32x4*>(ep.gate0 + n);
+      if (ep.gate1) gate += *reinterpret_cast<const f32x4*>(ep.gate1 + n);
+    }
+    gate *= ep.scale;
+  }
+  float* out = reinterpret_cast<float*>(ep.out);
+#pragma unroll
+  for (int mb = 0; mb < 8; ++mb) {
+    f32x4 cur[8];
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      long m = m_wave0 + 16 * mb + 2 * it + rrow;
+      if (m > M - 1) m = M - 1;  // rows past the end read the last row (never stored)
+      cur[it] = *reinterpret_cast<const f32x4*>(out + m * N + (n_ok ? n : 0));
+    }
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb) *reinterpret_cast<f32x4*>(cw + lj * E16_F32_STRIDE + 16 * nb + 4 * lg) = acc[nb][mb];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(cw + (2 * it + rrow) * E16_F32_STRIDE + rcol);
+      const long m = m_wave0 + 16 * mb + 2 * it + rrow;
+      if (n_ok && m < M) *reinterpret_cast<f32x4*>(out + m * N + n) = cur[it] + gate * (v + bias);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// Epilogue of the 4-wave 16x16 kernels: wave (wm, wn) holds rows m0 + 128 wm .. +128, columns n0 + 128 wn .. +128.
+template <int EPI>
+__device__ __forceinline__ void gemm16_finish(f32x4 (&acc)[8][8], const EpiArgs& ep, uint8_t* smem_raw, int wave, int wm, int wn,
+                                              long m0, int n0, long M, int N, int lane) {
+  uint16_t* smem = reinterpret_cast<uint16_t*>(smem_raw);
+  const int lj = lane & 15, lg = lane >> 4;
+  if constexpr (EPI == CHORUS_EPI_BF16 || EPI == CHORUS_EPI_GELU_BF16) {
+    gemm16_epilogue_bf16<EPI>(acc, ep, smem + wave * E16_BF_WAVE, m0 + wm * 128, n0 + wn * 128, M, N, lane);
+  } else if constexpr (EPI == CHORUS_EPI_RESID) {
+    gemm16_epilogue_resid(acc, ep, reinterpret_cast<float*>(smem_raw) + wave * E16_F32_WAVE, m0 + wm * 128, n0 + wn * 128, M, N, lane);
+  } else {
+    // plain fp32: a lane stores its four consecutive columns of every block
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb) {
+      const int n = n0 + wn * 128 + 16 * nb + 4 * lg;
+      if (n >= N) continue;
+      f32x4 bias = {0.f, 0.f, 0.f, 0.f};
+      if (ep.bias) bias = *reinterpret_cast<const f32x4*>(ep.bias + n);
+#pragma unroll
+      for (int mb = 0; mb < 8; ++mb) {
+        const long m = m0 + wm * 128 + 16 * mb + lj;
+        if (m < M) *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(ep.out) + m * N + n) = acc[nb][mb] + bias;
+      }
+    }
+  }
+}
+
+template <int EPI>
+__global__ __launch_bounds__(256, 1) void gemm_w16_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
+                                                          long M, int N, int K, EpiArgs ep, int tiles_m, int tiles_n) {
+  constexpr int BM = 256, BN = 256;
   constexpr int GM = 8;
   constexpr int STAGE = (BM + BN) * BK;  // elements per stage
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem_raw[];
@@ -378,17 +458,17 @@ __global__ __launch_bounds__(512, 2) void gemm_dl_kernel(const uint16_t* __restr
   const int n0 = tn_idx * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 2, wn = wave & 3;
-  const int lrow = lane & 31;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int lj = lane & 15, lg = lane >> 4;
 
-  // ---- loader: wave w, slot i covers tile rows 8*(4w+i) .. +8 of A and of W; lane -> (row, position)
+  // ---- loader: wave w, slot i (0..7) covers tile rows 8*(8w+i) .. +8 of A and of W; lane -> (row, position)
   const int lr = lane >> 3, lp = lane & 7;
-  const uint16_t* ga[4];
-  const uint16_t* gb[4];
+  const uint16_t* ga[8];
+  const uint16_t* gb[8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = 8 * (4 * wave + i) + lr;           // row inside the 256-row tile
-    const int ch = lp ^ ((r >> 1) & 7);              // global chunk that belongs at position lp
+  for (int i = 0; i < 8; ++i) {
+    const int r = 8 * (8 * wave + i) + lr;
+    const int ch = lp ^ ((r >> 1) & 7);  // global chunk that belongs at position lp
     long ra = m0 + r;
     if (ra > M - 1) ra = M - 1;
     int rb = n0 + r;
@@ -396,101 +476,126 @@ __global__ __launch_bounds__(512, 2) void gemm_dl_kernel(const uint16_t* __restr
     ga[i] = A + ra * (long)K + ch * 8;
     gb[i] = W + (long)rb * K + ch * 8;
   }
-  auto issue = [&](int kt, int stage) {
+  auto issue = [&](int kt, int stage, int t0, int t1) {  // loads t0 .. t1-1 of the 16 per k-step (even: A rows, odd: W rows)
     uint16_t* sa = smem + stage * STAGE;
     uint16_t* sb = sa + BM * BK;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int rows0 = 8 * (4 * wave + i);
-      __builtin_amdgcn_global_load_lds(ga[i] + (long)kt * BK, sa + rows0 * BK, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(gb[i] + (long)kt * BK, sb + rows0 * BK, 16, 0, 0);
+    for (int t = t0; t < t1; ++t) {
+      const int i = t >> 1;
+      const int rows0 = 8 * (8 * wave + i);
+      if (t & 1)
+        __builtin_amdgcn_global_load_lds(gb[i] + (long)kt * BK, sb + rows0 * BK, 16, 0, 0);
+      else
+        __builtin_amdgcn_global_load_lds(ga[i] + (long)kt * BK, sa + rows0 * BK, 16, 0, 0);
     }
   };
 
-  // ---- operand read offsets (elements): row base + swizzled chunk for each k-substep
-  const int sw = (lrow >> 1) & 7;
-  int koff[BK / 16];
+  // ---- fragment read offsets (elements): row l % 16 of a 16-row block, 16-byte chunk 4 h + l / 16, swizzled by the row
+  const int sw = (lj >> 1) & 7;
+  int koff[2];
 #pragma unroll
-  for (int ks = 0; ks < BK / 16; ++ks) koff[ks] = ((2 * ks + (lane >> 5)) ^ sw) * 8;
-  const int a_row0 = (wm * WM + lrow) * BK;
-  const int b_row0 = BM * BK + (wn * WN + lrow) * BK;
+  for (int h = 0; h < 2; ++h) koff[h] = ((4 * h + lg) ^ sw) * 8;
+  const int a_row0 = (wm * 128 + lj) * BK;
+  const int b_row0 = BM * BK + (wn * 128 + lj) * BK;
 
-  f32x16 acc[TM][TN];
+  f32x4 acc[8][8];  // [n block][m block]
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int nb = 0; nb < 8; ++nb)
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    for (int mb = 0; mb < 8; ++mb) acc[nb][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  bf16x8 af[2][8], bfr[2][8];
+  // fragment f of a half-step: 0-7 the activation blocks (m), 8-15 the weight blocks (n)
+  auto read_frag = [&](const uint16_t* st, int h, int set, int f) {
+    if (f < 8)
+      af[set][f] = *reinterpret_cast<const bf16x8*>(st + a_row0 + f * 16 * BK + koff[h]);
+    else
+      bfr[set][f - 8] = *reinterpret_cast<const bf16x8*>(st + b_row0 + (f - 8) * 16 * BK + koff[h]);
+  };
+  // MFMAs g0 .. g1-1 of the 64 of a half-step, weight block major: g = 8 nb + mb. In place on the accumulator
+  // registers (left to itself the register allocator gives every result a new home and pays with hundreds of
+  // accumulator moves per k-step); being volatile they also keep their place between the loads written around them.
+  auto mfmas = [&](int set, int g0, int g1) {
+#pragma unroll
+    for (int g = g0; g < g1; ++g)
+      asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[g >> 3][g & 7]) : "v"(bfr[set][g >> 3]), "v"(af[set][g & 7]));
+  };
+  // order in which the fragments of a half-step are fetched: what its first MFMAs need comes first
+  constexpr int kFragOrder[16] = {8, 0, 1, 2, 3, 4, 5, 6, 7, 9, 10, 11, 12, 13, 14, 15};
+
+  // Schedule of one k-step (128 MFMAs a wave). The barrier sits after MFMA 96: by then every wave holds all its
+  // fragments of the current stage in registers and its own pieces of the next stage have landed. Behind it the stage
+  // just consumed is free, so the loads of the step after next start there (kEarly of them in the 32 MFMAs up to the
+  // end of the step, the rest in the first MFMAs of the next step) and have most of a k-step to arrive; the fragment
+  // reads of the next step's first half share those 32 MFMAs.
+  constexpr int kEarly = 8;
   const int KTN = K / BK;
-  issue(0, 0);
-  for (int kt = 0; kt < KTN; ++kt) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's pieces of tile kt are in LDS
-    lds_barrier();                       // ... and everybody's; all waves are done with the other stage
-    __builtin_amdgcn_sched_barrier(0);
-    issue(kt + 1 < KTN ? kt + 1 : kt, (kt + 1) & 1);  // branch-free: the last step re-fetches its own tile into the idle stage
-    const uint16_t* st = smem + (kt & 1) * STAGE;
-    // Operand fragments are double-buffered in registers: the LDS reads of k-substep ks+1 are
-    // issued ahead of the 8 MFMAs of substep ks, so a fragment is requested ~256 cycles before use.
-    bf16x8 af[2][TM], bfr[2][TN];
-    auto read_frags = [&](int ks, int set) {
+  auto clampk = [&](int k) { return k < KTN ? k : KTN - 1; };  // past the end: re-fetch the last tile into an idle stage
+  issue(0, 0, 0, 16);
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  lds_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+  issue(clampk(1), 1, 0, kEarly);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[set][j] = *reinterpret_cast<const bf16x8*>(st + b_row0 + j * 32 * BK + koff[ks]);
-#pragma unroll
-      for (int i = 0; i < TM; ++i) af[set][i] = *reinterpret_cast<const bf16x8*>(st + a_row0 + i * 32 * BK + koff[ks]);
-    };
-    read_frags(0, 0);
-    __builtin_amdgcn_sched_group_barrier(0x020, 8, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      if (ks + 1 < BK / 16) read_frags(ks + 1, (ks + 1) & 1);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][j], af[ks & 1][i], acc[i][j], 0, 0, 0);
-      if (ks + 1 < BK / 16) __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);  // all reads of ks+1 first
-      __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);                           // then the MFMAs of ks
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the redundant last prefetch before the workgroup may exit
+  for (int f = 0; f < 16; ++f) read_frag(smem, 0, 0, kFragOrder[f]);
+  __builtin_amdgcn_sched_barrier(0);
 
-  if constexpr (EPI == CHORUS_EPI_BF16 || EPI == CHORUS_EPI_GELU_BF16) {
-    lds_barrier();  // the staging regions overlay the operand stages
-    gemm_epilogue_bf16_lds<EPI>(acc, ep, smem + wave * EPI_LDS_WAVE, m0 + wm * WM, n0 + wn * WN, M, N, lane);
-  } else if constexpr (EPI == CHORUS_EPI_RESID) {
-    lds_barrier();
-    gemm_epilogue_resid_lds(acc, ep, reinterpret_cast<float*>(smem_raw) + wave * EPI_F32_WAVE, m0 + wm * WM, n0 + wn * WN, M, N,
-                            lane);
-  } else {
-    gemm_epilogue<EPI, TM, TN>(acc, ep, m0 + wm * WM + lrow, n0 + wn * WN + (lane >> 5) * 4, M, N);
+  for (int kt = 0; kt < KTN; ++kt) {
+    const uint16_t* st = smem + (kt & 1) * STAGE;
+    const uint16_t* stn = smem + ((kt + 1) & 1) * STAGE;
+    const int k1 = clampk(kt + 1), k2 = clampk(kt + 2);
+    // ---- half-step 0: 64 MFMAs; every four of them one fragment read of half-step 1 and, at first, one load
+#pragma unroll
+    for (int f = 0; f < 16; ++f) {
+      read_frag(st, 1, 1, kFragOrder[f]);
+      if (kEarly + f < 16) issue(k1, (kt + 1) & 1, kEarly + f, kEarly + f + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfmas(0, 4 * f, 4 * f + 4);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // ---- first 32 MFMAs of half-step 1
+    mfmas(1, 0, 32);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's pieces of step kt+1 are in LDS
+    lds_barrier();                       // every wave has all its fragments of this stage in registers
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- last 32 MFMAs of half-step 1, every two of them one fragment read of the next step's first half
+#pragma unroll
+    for (int f = 0; f < 16; ++f) {
+      read_frag(stn, 0, 0, kFragOrder[f]);
+      if (f < kEarly) issue(k2, kt & 1, f, f + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfmas(1, 32 + 2 * f, 32 + 2 * f + 2);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
+
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the look-ahead loads of the last step have landed
+  lds_barrier();  // the staging regions of the epilogue overlay the operand stages
+  gemm16_finish<EPI>(acc, ep, smem_raw, wave, wm, wn, m0, n0, M, N, lane);
 }
 
-int32_t launch_gemm_dl(const uint16_t* A, const uint16_t* W, long M, int N, int K, int epi, EpiArgs ep, hipStream_t s) {
+int32_t launch_gemm_w16(const uint16_t* A, const uint16_t* W, long M, int N, int K, int epi, EpiArgs ep, hipStream_t s) {
   long tm = (M + 255) / 256;
   int tn = (N + 255) / 256;
   if (tm * tn > 0x7fffffffL) return CHORUS_E_SHAPE;
-  dim3 grid((unsigned)(tm * tn)), block(512);
+  dim3 grid((unsigned)(tm * tn)), block(256);
   const size_t smem = 2 * (256 + 256) * BK * sizeof(uint16_t);  // 128 KB
-#define GEMM_DL(E)                                                                              \
+#define GEMM_W16(E)                                                                             \
   {                                                                                             \
-    auto kern = gemm_dl_kernel<E>;                                                              \
+    auto kern = gemm_w16_kernel<E>;                                                             \
     static DynLdsOnce once;                                                                     \
     CHK_STATUS(once.ensure(reinterpret_cast<const void*>(kern), (int)smem));                    \
     hipLaunchKernelGGL(kern, grid, block, smem, s, A, W, M, N, K, ep, (int)tm, tn);             \
   }
   switch (epi) {
-    case CHORUS_EPI_BF16: GEMM_DL(CHORUS_EPI_BF16); break;
-    case CHORUS_EPI_GELU_BF16: GEMM_DL(CHORUS_EPI_GELU_BF16); break;
-    case CHORUS_EPI_F32: GEMM_DL(CHORUS_EPI_F32); break;
-    case CHORUS_EPI_RESID: GEMM_DL(CHORUS_EPI_RESID); break;
+    case CHORUS_EPI_BF16: GEMM_W16(CHORUS_EPI_BF16); break;
+    case CHORUS_EPI_GELU_BF16: GEMM_W16(CHORUS_EPI_GELU_BF16); break;
+    case CHORUS_EPI_F32: GEMM_W16(CHORUS_EPI_F32); break;
+    case CHORUS_EPI_RESID: GEMM_W16(CHORUS_EPI_RESID); break;
     default: return CHORUS_E_ARG;
   }
-#undef GEMM_DL
+#undef GEMM_W16
   CHORUS_LAUNCH_CHECK();
   return CHORUS_OK;
 }
@@ -534,17 +639,18 @@ extern "C" int32_t chorus_gemm_bf16_kernel(const uint16_t* A, const uint16_t* W,
   hipStream_t s = (hipStream_t)stream;
   if (kernel == 1) return launch_gemm<128, 64, 64, 32>(A, W, (long)M, N, K, epilogue, ep, s);
   if (kernel == 2) return launch_gemm<256, 128, 128, 64>(A, W, (long)M, N, K, epilogue, ep, s);
-  if (kernel == 3) return launch_gemm_dl(A, W, (long)M, N, K, epilogue, ep, s);
-  // small problems get the smaller tile so that more workgroups exist; between the two large tiles the choice goes
-  // by rounds of 256 workgroups: a 256 x 128 tile takes about 0.6 of the time of a 256 x 256 one
-  long big_tiles = ((M + 255) / 256) * ((N + 127) / 128);
-  long dl_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-  if (dl_tiles >= 256) {
-    const double t_dl = (double)((dl_tiles + 255) / 256);
-    const double t_big = 0.6 * (double)((big_tiles + 255) / 256);
-    if (t_dl <= t_big) return launch_gemm_dl(A, W, (long)M, N, K, epilogue, ep, s);
-  }
-  if (big_tiles >= 256) return launch_gemm<256, 128, 128, 64>(A, W, (long)M, N, K, epilogue, ep, s);
+  if (kernel == 3) return launch_gemm_w16(A, W, (long)M, N, K, epilogue, ep, s);
+  // Automatic choice: the estimated time of each tile shape, in microseconds, from fits to measurements on this chip
+  // at K = 1536 and K = 8960 (a constant for prologue and epilogue plus a cost per element of K). The two large tiles
+  // run one workgroup per compute unit, so they go in rounds of 256 workgroups; the small tile keeps several
+  // workgroups per unit in flight, so its time grows with the tile count past the first 256.
+  const double k = (double)K;
+  const double t256 = (double)((((M + 255) / 256) * ((N + 255) / 256) + 255) / 256) * (16.0 + 0.0233 * k);
+  const double t128 = (double)((((M + 255) / 256) * ((N + 127) / 128) + 255) / 256) * (5.0 + 0.0173 * k);
+  const long small_tiles = ((M + 127) / 128) * ((N + 63) / 64);
+  const double t64 = (5.6 + 0.0084 * k) + (small_tiles > 256 ? (double)(small_tiles - 256) / 256.0 * (0.8 + 0.0057 * k) : 0.0);
+  if (t256 <= t128 && t256 <= t64) return launch_gemm_w16(A, W, (long)M, N, K, epilogue, ep, s);
+  if (t128 <= t64) return launch_gemm<256, 128, 128, 64>(A, W, (long)M, N, K, epilogue, ep, s);
   return launch_gemm<128, 64, 64, 32>(A, W, (long)M, N, K, epilogue, ep, s);
 }
 

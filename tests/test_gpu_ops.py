@@ -20,7 +20,9 @@ pytestmark = pytest.mark.gpu
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (100, 768, 256), (257, 1536, 1536), (1000, 64, 1536),
                                    (4099, 4608, 1536), (3000, 1536, 8960), (513, 1024, 64), (70, 8, 128)])
 def test_gemm_epilogues(M, N, K):
-    print(f"[case] gemm M={M} N={N} K={K}", flush=True)
+    """Every tile kernel (1: 128 x 64, 2: 256 x 128, 3: 256 x 256 direct to LDS) and the automatic choice (0), each on
+    every shape: tiles with ragged rows and columns, a single row, fewer columns than a tile has, K of one and of
+    many steps; the four epilogues."""
     A = synth.round_bf16(synth.normal(M, "g.A", (M, K)))
     W = synth.round_bf16(synth.normal(M, "g.W", (N, K), 0.05))
     bias = synth.normal(M, "g.b", (N,), 0.5)
@@ -28,22 +30,25 @@ def test_gemm_epilogues(M, N, K):
     g1 = synth.normal(M, "g.g1", (N,), 0.5)
     resid = synth.normal(M, "g.r", (M, N))
     ref = O.linear(A, W, bias)
-    dA, dW, db = dev_bf16(A), dev_bf16(W), dev_f32(bias)
-    out = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
-    B.chorus_gemm_bf16(dA, dW, B.EPI_BF16, out, db)
-    check(host_bf16(out), ref, "gemm bf16", max_abs=np.abs(ref).max() * 2 ** -8, rel_l2=3e-3)
-    B.chorus_gemm_bf16(dA, dW, B.EPI_GELU_BF16, out, db)
+    ref0 = O.linear(A, W, np.zeros(N))
     gref = O.gelu_tanh(ref)
-    check(host_bf16(out), gref, "gemm gelu", max_abs=max(np.abs(gref).max() * 2 ** -8, 1e-3), rel_l2=3e-3)
-    o32 = torch.empty(M, N, dtype=torch.float32, device=DEV)
-    B.chorus_gemm_bf16(dA, dW, B.EPI_F32, o32, None)
-    check(host(o32), O.linear(A, W, np.zeros(N)), "gemm f32", max_abs=1e-3, rel_l2=1e-5)
-    r = dev_f32(resid)
-    B.chorus_gemm_bf16(dA, dW, B.EPI_RESID, r, db, dev_f32(g0), dev_f32(g1), 1.0)
-    check(host(r), resid + (g0.astype(np.float64) + g1) * ref, "gemm resid gated", max_abs=1e-3, rel_l2=1e-5)
-    r = dev_f32(resid)
-    B.chorus_gemm_bf16(dA, dW, B.EPI_RESID, r, db, None, None, 1.5)
-    check(host(r), resid + 1.5 * ref, "gemm resid scale", max_abs=1e-3, rel_l2=1e-5)
+    dA, dW, db = dev_bf16(A), dev_bf16(W), dev_f32(bias)
+    for kern in (0, 1, 2, 3):
+        print(f"[case] gemm M={M} N={N} K={K} kernel={kern}", flush=True)
+        out = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+        B.chorus_gemm_bf16(dA, dW, B.EPI_BF16, out, db, kernel=kern)
+        check(host_bf16(out), ref, f"gemm bf16 k{kern}", max_abs=np.abs(ref).max() * 2 ** -8, rel_l2=3e-3)
+        B.chorus_gemm_bf16(dA, dW, B.EPI_GELU_BF16, out, db, kernel=kern)
+        check(host_bf16(out), gref, f"gemm gelu k{kern}", max_abs=max(np.abs(gref).max() * 2 ** -8, 1e-3), rel_l2=3e-3)
+        o32 = torch.empty(M, N, dtype=torch.float32, device=DEV)
+        B.chorus_gemm_bf16(dA, dW, B.EPI_F32, o32, None, kernel=kern)
+        check(host(o32), ref0, f"gemm f32 k{kern}", max_abs=1e-3, rel_l2=1e-5)
+        r = dev_f32(resid)
+        B.chorus_gemm_bf16(dA, dW, B.EPI_RESID, r, db, dev_f32(g0), dev_f32(g1), 1.0, kernel=kern)
+        check(host(r), resid + (g0.astype(np.float64) + g1) * ref, f"gemm resid gated k{kern}", max_abs=1e-3, rel_l2=1e-5)
+        r = dev_f32(resid)
+        B.chorus_gemm_bf16(dA, dW, B.EPI_RESID, r, db, None, None, 1.5, kernel=kern)
+        check(host(r), resid + 1.5 * ref, f"gemm resid scale k{kern}", max_abs=1e-3, rel_l2=1e-5)
 
 
 # ------------------------------------------------------------- LN + modulate
