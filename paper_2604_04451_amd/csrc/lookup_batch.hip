@@ -9,7 +9,8 @@
 namespace chorus {
 namespace {
 
-constexpr int kBR = 128;      // cache rows per workgroup, 32 per wave
+constexpr int kRB = 1;        // 16-row blocks per wave
+constexpr int kBR = 64 * kRB;  // cache rows per workgroup, 16 kRB per wave
 constexpr int kBK = 64;       // floats of every row per step (256 bytes: two full cache lines)
 constexpr int kLS = kBK + 4;  // LDS row stride in floats (16-byte aligned, staggers the banks)
 
@@ -23,11 +24,11 @@ inline BatchPlan plan_batch(long N, int d) {
   BatchPlan p;
   p.tiles = (int)((N + kBR - 1) / kBR);
   const int nchunks = (d + kBK - 1) / kBK;
-  // enough workgroups to fill 256 CUs twice; partial sums of the slices are added in a fixed order afterwards
-  int want = p.tiles > 0 ? (512 + p.tiles - 1) / p.tiles : 1;
+  // enough workgroups to put four on each of 256 CUs; partial sums of the slices are added in a fixed order afterwards
+  int want = p.tiles > 0 ? (1024 + p.tiles - 1) / p.tiles : 1;
   if (want < 1) want = 1;
   if (want > nchunks) want = nchunks;
-  if (want > 64) want = 64;
+  if (want > 16) want = 16;  // every slice writes and re-reads its own partial sums
   p.chunks_per_slice = (nchunks + want - 1) / want;
   p.KS = (nchunks + p.chunks_per_slice - 1) / p.chunks_per_slice;
   return p;
@@ -53,16 +54,16 @@ __global__ __launch_bounds__(256) void lookup_batch_scores_kernel(const float* _
 
   // loader role: 16 threads per row segment of 256 bytes
   const int lcol = tid & 15, lrow = tid >> 4;
-  f32x4 ra[8], rb[QB];
-  auto load_chunk = [&](int c) {
+  f32x4 ra[2][4 * kRB], rb[2][QB];  // two chunks in flight
+  auto load_chunk = [&](int st, int c) {
     const int k = c * kBK + 4 * lcol;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < 4 * kRB; ++i) {
       const long r = row0 + lrow + 16 * i;
       const bool ok = r < N && k < d;
       const float* p = cache + (ok ? r : 0) * (long)d + (ok ? k : 0);
       f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
-      ra[i] = ok ? v : f32x4{0.f, 0.f, 0.f, 0.f};
+      ra[st][i] = ok ? v : f32x4{0.f, 0.f, 0.f, 0.f};
     }
 #pragma unroll
     for (int i = 0; i < QB; ++i) {
@@ -70,40 +71,41 @@ __global__ __launch_bounds__(256) void lookup_batch_scores_kernel(const float* _
       const bool ok = q < Q && k < d;
       const float* p = queries + (long)(ok ? q : 0) * d + (ok ? k : 0);
       f32x4 v = *reinterpret_cast<const f32x4*>(p);
-      rb[i] = ok ? v : f32x4{0.f, 0.f, 0.f, 0.f};
+      rb[st][i] = ok ? v : f32x4{0.f, 0.f, 0.f, 0.f};
     }
   };
-  auto store_chunk = [&]() {
+  auto store_chunk = [&](int st) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) *reinterpret_cast<f32x4*>(&sA[(lrow + 16 * i) * kLS + 4 * lcol]) = ra[i];
+    for (int i = 0; i < 4 * kRB; ++i) *reinterpret_cast<f32x4*>(&sA[(lrow + 16 * i) * kLS + 4 * lcol]) = ra[st][i];
 #pragma unroll
-    for (int i = 0; i < QB; ++i) *reinterpret_cast<f32x4*>(&sB[(lrow + 16 * i) * kLS + 4 * lcol]) = rb[i];
+    for (int i = 0; i < QB; ++i) *reinterpret_cast<f32x4*>(&sB[(lrow + 16 * i) * kLS + 4 * lcol]) = rb[st][i];
   };
 
   // compute role: a wave owns 32 rows = two 16-row blocks; lane = (row or query l % 16, k quarter l / 16)
   const int l16 = lane & 15, kq = lane >> 4;
-  f32x4 acc[2][QB];
+  f32x4 acc[kRB][QB];
 #pragma unroll
-  for (int r = 0; r < 2; ++r)
+  for (int r = 0; r < kRB; ++r)
 #pragma unroll
     for (int q = 0; q < QB; ++q) acc[r][q] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float cc[2] = {0.f, 0.f};
+  float cc[kRB] = {};
 
-  if (c0 < c1) load_chunk(c0);
-  for (int c = c0; c < c1; ++c) {
+  // chunk c + 1 is already in flight when chunk c is stored, and chunk c + 2 is requested right after: two chunks
+  // (64 KB per workgroup) are on their way during the MFMAs. Past the slice the loads are masked to zeros.
+  auto step = [&](int st, int c) {
     __syncthreads();  // the previous step's reads are done
-    store_chunk();
+    store_chunk(st);
     __syncthreads();
-    if (c + 1 < c1) load_chunk(c + 1);  // in flight during the MFMAs
+    if (c + 2 < c1) load_chunk(st, c + 2);
 #pragma unroll
     for (int j = 0; j < kBK / 16; ++j) {
-      f32x4 a[2], b[QB];
+      f32x4 a[kRB], b[QB];
 #pragma unroll
-      for (int r = 0; r < 2; ++r) a[r] = *reinterpret_cast<const f32x4*>(&sA[(32 * wave + 16 * r + l16) * kLS + 16 * j + 4 * kq]);
+      for (int r = 0; r < kRB; ++r) a[r] = *reinterpret_cast<const f32x4*>(&sA[(16 * kRB * wave + 16 * r + l16) * kLS + 16 * j + 4 * kq]);
 #pragma unroll
       for (int q = 0; q < QB; ++q) b[q] = *reinterpret_cast<const f32x4*>(&sB[(16 * q + l16) * kLS + 16 * j + 4 * kq]);
 #pragma unroll
-      for (int r = 0; r < 2; ++r) {
+      for (int r = 0; r < kRB; ++r) {
         cc[r] += a[r][0] * a[r][0] + a[r][1] * a[r][1] + a[r][2] * a[r][2] + a[r][3] * a[r][3];
 #pragma unroll
         for (int e = 0; e < 4; ++e)
@@ -111,100 +113,196 @@ __global__ __launch_bounds__(256) void lookup_batch_scores_kernel(const float* _
           for (int q = 0; q < QB; ++q) acc[r][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r][e], b[q][e], acc[r][q], 0, 0, 0);
       }
     }
+  };
+  if (c0 < c1) load_chunk(0, c0);
+  if (c0 + 1 < c1) load_chunk(1, c0 + 1);
+  for (int c = c0; c < c1; c += 2) {
+    step(0, c);
+    if (c + 1 < c1) step(1, c + 1);
   }
   // row norms: the four k quarters of a row sit in lanes l16, l16 + 16, l16 + 32, l16 + 48
 #pragma unroll
-  for (int r = 0; r < 2; ++r) {
+  for (int r = 0; r < kRB; ++r) {
     cc[r] += __shfl_xor(cc[r], 16, 64);
     cc[r] += __shfl_xor(cc[r], 32, 64);
-    const long row = row0 + 32 * wave + 16 * r + l16;
+    const long row = row0 + 16 * kRB * wave + 16 * r + l16;
     if (kq == 0) part_cc[(long)ks * Npad + row] = cc[r];
   }
   // accumulator elements 0..3 of lane (l16, kq): rows 4 kq .. 4 kq + 3 of the block, query l16 (rows past N hold zeros)
 #pragma unroll
-  for (int r = 0; r < 2; ++r)
+  for (int r = 0; r < kRB; ++r)
 #pragma unroll
     for (int q = 0; q < QB; ++q) {
-      const long row = row0 + 32 * wave + 16 * r + 4 * kq;
+      const long row = row0 + 16 * kRB * wave + 16 * r + 4 * kq;
       *reinterpret_cast<f32x4*>(&part_dot[((long)ks * QP + 16 * q + l16) * Npad + row]) = acc[r][q];
     }
 }
 
-// One workgroup per query: final scores = (partial dots summed in slice order) / (|c_row| |q|), -inf for zero norms
-// and NaN; then k rounds, each picking the best entry that comes after the previous winner in the order
-// (score descending, index ascending). REG: the scores of a thread live in registers (N <= 8 * 1024), else they
-// are re-read from `scores`.
-template <bool REG>
-__global__ __launch_bounds__(1024) void lookup_topk_kernel(const float* __restrict__ part_dot,
-                                                           const float* __restrict__ part_cc,
-                                                           const float* __restrict__ queries, float* __restrict__ scores,
-                                                           long N, long Npad, int d, int QP, int KS, int k, float tau,
-                                                           int32_t* __restrict__ out_idx, float* __restrict__ out_score,
-                                                           int32_t* __restrict__ out_hit) {
-  constexpr int R = 8;
-  __shared__ float sv[2][16];
-  __shared__ int si[2][16];  // N < 2^31 entries per call
-  __shared__ float sq[16];
-  const int q = blockIdx.x;
+// dot[u], cc[u] (u < RU) += the partial sums of entry j + STRIDE u over the KS slices, in ascending slice order
+// whatever the grouping: G slices x RU entries x 2 loads are in flight at a time.
+template <int RU, int G, int RMAX, int STRIDE>
+__device__ __forceinline__ void sum_slices(const float* __restrict__ part_dot, const float* __restrict__ part_cc, int KS,
+                                           int QP, int q, long Npad, long j, long N, float (&dot)[RMAX], float (&cc)[RMAX]) {
+  for (int ks0 = 0; ks0 < KS; ks0 += G) {
+    float pd[G][RU], pc[G][RU];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const int ks = ks0 + g < KS ? ks0 + g : KS - 1;
+#pragma unroll
+      for (int u = 0; u < RU; ++u) {
+        const long ju = j + (long)STRIDE * u;
+        const long jj = ju < N ? ju : N - 1;
+        pd[g][u] = part_dot[((long)ks * QP + q) * Npad + jj];
+        pc[g][u] = part_cc[(long)ks * Npad + jj];
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int u = 0; u < RU; ++u) {
+        const bool live = ks0 + g < KS;
+        dot[u] += live ? pd[g][u] : 0.f;
+        cc[u] += live ? pc[g][u] : 0.f;
+      }
+  }
+}
+
+constexpr int kWaveK = 64;  // up to this k the selection runs without a barrier per position
+
+// Final scores of all queries: score[q][j] = (partial dots summed in slice order) / (|c_j| |q|), -inf for zero norms
+// and NaN. Grid (row blocks of 1024, queries): spread over the chip, because one workgroup per query would pull its
+// KS slices (half a megabyte at 4096 entries) through a single compute unit.
+__global__ __launch_bounds__(256) void lookup_batch_final_kernel(const float* __restrict__ part_dot,
+                                                                 const float* __restrict__ part_cc,
+                                                                 const float* __restrict__ queries,
+                                                                 float* __restrict__ scores, long N, long Npad, int d,
+                                                                 int QP, int KS) {
+  constexpr int R = 4;
+  __shared__ float sq[4];
+  const int q = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  // |q|
   float qq = 0.f;
-  for (int i = tid; i < d; i += 1024) {
+  for (int i = tid; i < d; i += 256) {
     const float v = queries[(long)q * d + i];
     qq += v * v;
   }
   qq = wave_sum(qq);
   if (lane == 0) sq[wave] = qq;
   __syncthreads();
-  float qn = 0.f;
-  for (int w = 0; w < 16; ++w) qn += sq[w];
-  qn = sqrtf(qn);
-  // final scores
-  float* sc = scores + (long)q * Npad;
+  const float qn = sqrtf(sq[0] + sq[1] + sq[2] + sq[3]);
+  const long j0 = (long)blockIdx.x * (256 * R) + tid;
+  float dot[R], cc[R];
+#pragma unroll
+  for (int u = 0; u < R; ++u) dot[u] = cc[u] = 0.f;
+  sum_slices<R, 8, R, 256>(part_dot, part_cc, KS, QP, q, Npad, j0, N, dot, cc);
+#pragma unroll
+  for (int u = 0; u < R; ++u) {
+    const long j = j0 + 256L * u;
+    const float den = sqrtf(cc[u]) * qn;
+    float v = den > 0.f ? dot[u] / den : -INFINITY;
+    if (!(v == v)) v = -INFINITY;
+    if (j < N) scores[(long)q * Npad + j] = v;
+  }
+}
+
+// One workgroup per query: k rounds over its final scores, each picking the best entry that comes after the
+// previous winner in the order (score descending, index ascending). REG: the scores of a thread live in registers
+// (N <= 8 * 1024), else they are re-read from `scores`.
+template <bool REG>
+__global__ __launch_bounds__(1024) void lookup_topk_kernel(const float* __restrict__ scores, long N, long Npad, int k,
+                                                           float tau, int32_t* __restrict__ out_idx,
+                                                           float* __restrict__ out_score, int32_t* __restrict__ out_hit) {
+  constexpr int R = 8;
+  __shared__ float sv[2][16];
+  __shared__ int si[2][16];  // N < 2^31 entries per call
+  __shared__ float cv[16][kWaveK];  // small k: the kWaveK best of every wave, best first
+  __shared__ int ci[16][kWaveK];
+  const int q = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const float* sc = scores + (long)q * Npad;
   float mine[R];
 #pragma unroll
-  for (int u = 0; u < R; ++u) mine[u] = -INFINITY;
-  for (long j0 = 0; j0 < N; j0 += 1024 * R) {
-    // all loads of a slice group are issued before any is used (addresses clamped, results masked afterwards)
-    float dot[R], cc[R];
-#pragma unroll
-    for (int u = 0; u < R; ++u) dot[u] = cc[u] = 0.f;
-    for (int ks0 = 0; ks0 < KS; ks0 += 4) {
-      float pd[4][R], pc[4][R];
-#pragma unroll
-      for (int s4 = 0; s4 < 4; ++s4) {
-        const int ks = ks0 + s4 < KS ? ks0 + s4 : KS - 1;
-#pragma unroll
-        for (int u = 0; u < R; ++u) {
-          const long j = j0 + tid + 1024L * u;
-          const long jj = j < N ? j : N - 1;
-          pd[s4][u] = part_dot[((long)ks * QP + q) * Npad + jj];
-          pc[s4][u] = part_cc[(long)ks * Npad + jj];
-        }
-      }
-#pragma unroll
-      for (int s4 = 0; s4 < 4; ++s4)
-#pragma unroll
-        for (int u = 0; u < R; ++u) {
-          const bool live = ks0 + s4 < KS;  // slices are added in ascending order whatever the grouping
-          dot[u] += live ? pd[s4][u] : 0.f;
-          cc[u] += live ? pc[s4][u] : 0.f;
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < R; ++u) {
-      const long j = j0 + tid + 1024L * u;
-      const float den = sqrtf(cc[u]) * qn;
-      float v = den > 0.f ? dot[u] / den : -INFINITY;
-      if (!(v == v)) v = -INFINITY;
-      if (j < N) {
-        if (REG) mine[u] = v;
-        else sc[j] = v;
-      }
-    }
+  for (int u = 0; u < R; ++u) {
+    const long j = tid + 1024L * u;
+    mine[u] = (REG && j < N) ? sc[j] : -INFINITY;
   }
-  if (!REG) __syncthreads();
   unsigned taken = 0;  // REG: bit u set = this thread's entry u has been output
+  if (k <= kWaveK) {
+    // Small k without a workgroup barrier per position: every wave first lists the k best of ITS entries (rounds of
+    // in-wave exchanges only), then the first wave merges the 16 sorted lists. The k best overall are among them.
+    float ps_w = INFINITY;
+    int pj_w = -1;
+    for (int r = 0; r < k; ++r) {
+      float best = -INFINITY;
+      int bi = -1;
+      if (REG) {
+#pragma unroll
+        for (int u = 0; u < R; ++u) {
+          const int j = tid + 1024 * u;
+          if (j < N && !(taken & (1u << u)) && (bi < 0 || mine[u] > best)) {
+            best = mine[u];
+            bi = j;
+          }
+        }
+      } else {
+        for (long j = tid; j < N; j += 1024) {
+          const float v = sc[j];
+          const bool eligible = r == 0 || v < ps_w || (v == ps_w && j > pj_w);
+          if (eligible && (bi < 0 || v > best)) {
+            best = v;
+            bi = (int)j;
+          }
+        }
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        const float ob = __shfl_xor(best, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        if (oi >= 0 && (bi < 0 || ob > best || (ob == best && oi < bi))) {
+          best = ob;
+          bi = oi;
+        }
+      }
+      if (lane == 0) {
+        cv[wave][r] = best;
+        ci[wave][r] = bi;
+      }
+      ps_w = best;
+      pj_w = bi;
+      if (REG && bi >= 0 && (bi & 1023) == tid) taken |= 1u << (unsigned)(bi >> 10);
+      if (bi < 0) {  // this wave's entries are used up: the rest of its list is empty
+        for (int rr = r + 1 + lane; rr < k; rr += 64) ci[wave][rr] = -1;
+        break;
+      }
+    }
+    __syncthreads();
+    if (wave == 0) {
+      int head = 0;  // lanes 0..15: position in the list of wave `lane`
+      for (int r = 0; r < k; ++r) {
+        int i = (lane < 16 && head < k) ? ci[lane][head] : -1;
+        float b = i >= 0 ? cv[lane][head] : -INFINITY;
+        const int mine_i = i;
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) {
+          const float ob = __shfl_xor(b, o, 64);
+          const int oi = __shfl_xor(i, o, 64);
+          if (oi >= 0 && (i < 0 || ob > b || (ob == b && oi < i))) {
+            b = ob;
+            i = oi;
+          }
+        }
+        b = __shfl(b, 0, 64);
+        i = __shfl(i, 0, 64);
+        if (lane == 0) {
+          out_idx[(long)q * k + r] = i;
+          out_score[(long)q * k + r] = i >= 0 ? b : -INFINITY;
+          if (r == 0) out_hit[q] = (i >= 0 && b >= tau) ? 1 : 0;
+        }
+        if (i >= 0 && mine_i == i) ++head;  // the winner's list moves on
+      }
+    }
+    return;
+  }
   float ps = INFINITY;
   int pj = -1;
   for (int r = 0; r < k; ++r) {
@@ -342,12 +440,17 @@ int32_t chorus_cache_lookup_batch(const float* cache_emb, int64_t N, int32_t d, 
       CHORUS_LAUNCH_CHECK();
     }
     const long Npad = (long)p.tiles * kBR;
+    if (N > 0) {
+      hipLaunchKernelGGL(lookup_batch_final_kernel, dim3((unsigned)((N + 1023) / 1024), (unsigned)Qc), dim3(256), 0, s,
+                         w.part_dot, w.part_cc, qs, w.scores, (long)N, Npad, d, QP, p.KS);
+      CHORUS_LAUNCH_CHECK();
+    }
     if (N <= 8 * 1024)
-      hipLaunchKernelGGL(lookup_topk_kernel<true>, dim3(Qc), dim3(1024), 0, s, w.part_dot, w.part_cc, qs, w.scores, (long)N,
-                         Npad, d, QP, p.KS, k, tau, out_index + (long)q0 * k, out_score + (long)q0 * k, out_hit + q0);
+      hipLaunchKernelGGL(lookup_topk_kernel<true>, dim3(Qc), dim3(1024), 0, s, w.scores, (long)N, Npad, k, tau,
+                         out_index + (long)q0 * k, out_score + (long)q0 * k, out_hit + q0);
     else
-      hipLaunchKernelGGL(lookup_topk_kernel<false>, dim3(Qc), dim3(1024), 0, s, w.part_dot, w.part_cc, qs, w.scores, (long)N,
-                         Npad, d, QP, p.KS, k, tau, out_index + (long)q0 * k, out_score + (long)q0 * k, out_hit + q0);
+      hipLaunchKernelGGL(lookup_topk_kernel<false>, dim3(Qc), dim3(1024), 0, s, w.scores, (long)N, Npad, k, tau,
+                         out_index + (long)q0 * k, out_score + (long)q0 * k, out_hit + q0);
     CHORUS_LAUNCH_CHECK();
   }
   return CHORUS_OK;

@@ -266,7 +266,7 @@ def test_lookup_batch_edges():
 
 
 @pytest.mark.parametrize("N,d,Q,k", [(1000, 768, 5, 4), (257, 4, 16, 8), (33, 2052, 17, 2), (4096, 4096, 32, 8),
-                                     (4096, 4096, 1, 1), (70000, 256, 32, 16)])
+                                     (4096, 4096, 1, 1), (70000, 256, 32, 16), (3000, 128, 3, 100), (9000, 64, 2, 70)])
 def test_lookup_batch_shapes(N, d, Q, k):
     print(f"[case] lookup_batch N={N} d={d} Q={Q} k={k}", flush=True)
     cache = synth.cache_embeddings(N, d, seed=1)
