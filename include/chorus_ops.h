@@ -112,6 +112,15 @@ int32_t chorus_head_update(float* latent, const float* x, int64_t Ls, const int3
                            const chorus_glue_weights* gw, const float* t_head, float dsigma, int32_t D, int32_t C,
                            int32_t T, int32_t Hl, int32_t Wl, int32_t ph, int32_t pw, void* ws, size_t ws_bytes,
                            void* stream);
+/* chorus_head_update with Eq. 6 applied to the selected tokens in the same pass: a selected token n with
+ * mask_edit[n] == 0 receives SL (device fp32, the latent's shape) instead of the update. With SL and mask_edit NULL it
+ * is chorus_head_update. A caller whose latent already equals SL outside the selection (after a stage-1 copy or an
+ * earlier region step) needs no separate chorus_region_blend then. latent and SL must not overlap.
+ * CHORUS_E_ARG when only one of SL / mask_edit is given; otherwise as chorus_head_update. */
+int32_t chorus_head_update_region(float* latent, const float* x, int64_t Ls, const int32_t* token_idx,
+                                  const chorus_glue_weights* gw, const float* t_head, float dsigma, const float* SL,
+                                  const uint8_t* mask_edit, int32_t D, int32_t C, int32_t T, int32_t Hl, int32_t Wl,
+                                  int32_t ph, int32_t pw, void* ws, size_t ws_bytes, void* stream);
 /* ------------------------------------------------------------------------
  * The sampler (Sec. 4.1: the DPM++ solver with default settings; the paper gives no
  * formulas): DPM-Solver++ in data-prediction form, multistep, order <= 2, on the

@@ -153,6 +153,8 @@ def _bind_ops(lib):
         "chorus_glue_workspace_bytes": (sz, [i32, i32, i64]),
         "chorus_patch_embed": (i32, [vp, i32, i32, i32, i32, i32, i32, vp, i64, GW, i32, vp, vp, sz, vp]),
         "chorus_head_update": (i32, [vp, vp, i64, vp, GW, vp, f32, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]),
+        "chorus_head_update_region": (i32, [vp, vp, i64, vp, GW, vp, f32, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, sz,
+                                            vp]),
         "chorus_text_project_workspace_bytes": (sz, [i32, i32]),
         "chorus_text_project": (i32, [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]),
         "chorus_denoise_step_workspace_bytes": (sz, [MS, i64]),
@@ -664,6 +666,28 @@ def chorus_head_update(latent, x, Ls, token_idx, glue: DeviceGlue, t_head, dsigm
     _status("chorus_head_update", lib.chorus_head_update(_p(latent), _p(x), Ls, _p(token_idx), C.byref(glue.cstruct),
                                                          _p(t_head), float(dsigma), D, Cc, T, Hl, Wl, patch_hw[0],
                                                          patch_hw[1], _p(ws), ws.numel(), _stream()))
+    return latent
+
+
+def chorus_head_update_region(latent, x, Ls, token_idx, glue: DeviceGlue, t_head, dsigma, SL=None, mask_edit=None,
+                              patch_hw=(2, 2), ws=None):
+    """chorus_head_update with Eq. 6 on the selected tokens in the same pass (SL, mask_edit both given or both None)."""
+    lib = load()
+    _chk(latent, torch.float32, "latent")
+    _chk(x, torch.float32, "x")
+    _chk(token_idx, torch.int32, "token_idx")
+    D = x.shape[1]
+    _chk(t_head, torch.float32, "t_head", (2, D))
+    _chk(SL, torch.float32, "SL", tuple(latent.shape))
+    _chk(mask_edit, torch.uint8, "mask_edit")
+    Cc, T, Hl, Wl = latent.shape
+    P = Cc * patch_hw[0] * patch_hw[1]
+    if ws is None:
+        ws = _ws(lib.chorus_glue_workspace_bytes(D, P, Ls), latent.device)
+    _status("chorus_head_update_region",
+            lib.chorus_head_update_region(_p(latent), _p(x), Ls, _p(token_idx), C.byref(glue.cstruct), _p(t_head),
+                                          float(dsigma), _p(SL), _p(mask_edit), D, Cc, T, Hl, Wl, patch_hw[0], patch_hw[1],
+                                          _p(ws), ws.numel(), _stream()))
     return latent
 
 

@@ -38,9 +38,13 @@ __global__ __launch_bounds__(256) void patch_gather_kernel(const float* __restri
     }
 }
 
+// Euler update of one (selected token, channel) cell per thread, with Eq. 6 on the selected tokens when a mask is
+// given: a selected token outside M_edit receives the source latent instead of the update.
 __global__ __launch_bounds__(256) void unpatch_euler_kernel(float* __restrict__ latent, const float* __restrict__ v,
                                                             const int* __restrict__ token_idx, long Ls, int C, int T,
-                                                            int Hl, int Wl, int ph, int pw, float dsigma) {
+                                                            int Hl, int Wl, int ph, int pw, float dsigma,
+                                                            const float* __restrict__ SL,
+                                                            const uint8_t* __restrict__ mask_edit) {
   long g = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (g >= Ls * C) return;
   long i = g / C;
@@ -49,7 +53,13 @@ __global__ __launch_bounds__(256) void unpatch_euler_kernel(float* __restrict__ 
   long n = token_idx ? (long)token_idx[i] : i;
   int wg = (int)(n % Wg), hg = (int)((n / Wg) % Hg), t = (int)(n / ((long)Wg * Hg));
   const int cell = ph * pw;
-  float* dst = latent + (((long)ch * T + t) * Hl + (long)hg * ph) * Wl + (long)wg * pw;
+  const long base = (((long)ch * T + t) * Hl + (long)hg * ph) * Wl + (long)wg * pw;
+  float* dst = latent + base;
+  if (mask_edit && mask_edit[n] == 0) {
+    for (int dy = 0; dy < ph; ++dy)
+      for (int dx = 0; dx < pw; ++dx) dst[(long)dy * Wl + dx] = SL[base + (long)dy * Wl + dx];
+    return;
+  }
   const float* vi = v + i * (long)(C * cell) + ch * cell;
   for (int dy = 0; dy < ph; ++dy)
     for (int dx = 0; dx < pw; ++dx) dst[(long)dy * Wl + dx] += dsigma * vi[dy * pw + dx];
@@ -139,11 +149,12 @@ int32_t chorus_patch_embed(const float* latent, int32_t C, int32_t T, int32_t Hl
   return CHORUS_OK;
 }
 
-int32_t chorus_head_update(float* latent, const float* x, int64_t Ls, const int32_t* token_idx,
-                           const chorus_glue_weights* gw, const float* t_head, float dsigma, int32_t D, int32_t C,
-                           int32_t T, int32_t Hl, int32_t Wl, int32_t ph, int32_t pw, void* ws, size_t ws_bytes,
-                           void* stream) {
+int32_t chorus_head_update_region(float* latent, const float* x, int64_t Ls, const int32_t* token_idx,
+                                  const chorus_glue_weights* gw, const float* t_head, float dsigma, const float* SL,
+                                  const uint8_t* mask_edit, int32_t D, int32_t C, int32_t T, int32_t Hl, int32_t Wl,
+                                  int32_t ph, int32_t pw, void* ws, size_t ws_bytes, void* stream) {
   if (Ls < 0 || C <= 0 || T <= 0 || Hl <= 0 || Wl <= 0 || ph <= 0 || pw <= 0 || D <= 0) return CHORUS_E_ARG;
+  if ((SL != nullptr) != (mask_edit != nullptr)) return CHORUS_E_ARG;
   if (Ls == 0) return CHORUS_OK;
   if (!latent || !x || !gw || !t_head || !gw->w_head || !gw->head_table) return CHORUS_E_ARG;
   const int P = C * ph * pw;
@@ -157,9 +168,17 @@ int32_t chorus_head_update(float* latent, const float* x, int64_t Ls, const int3
   CHK(chorus_gemm_bf16(h, gw->w_head, Ls, P, D, CHORUS_EPI_F32, v, gw->b_head, nullptr, nullptr, 1.f, stream));
   long n = Ls * C;
   hipLaunchKernelGGL(unpatch_euler_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, latent, v, token_idx,
-                     (long)Ls, C, T, Hl, Wl, ph, pw, dsigma);
+                     (long)Ls, C, T, Hl, Wl, ph, pw, dsigma, SL, mask_edit);
   CHORUS_LAUNCH_CHECK();
   return CHORUS_OK;
+}
+
+int32_t chorus_head_update(float* latent, const float* x, int64_t Ls, const int32_t* token_idx,
+                           const chorus_glue_weights* gw, const float* t_head, float dsigma, int32_t D, int32_t C,
+                           int32_t T, int32_t Hl, int32_t Wl, int32_t ph, int32_t pw, void* ws, size_t ws_bytes,
+                           void* stream) {
+  return chorus_head_update_region(latent, x, Ls, token_idx, gw, t_head, dsigma, nullptr, nullptr, D, C, T, Hl, Wl, ph, pw,
+                                   ws, ws_bytes, stream);
 }
 
 int32_t chorus_sampler_coefficients(const float* sigmas, int32_t n_steps, int32_t i, int32_t order,

@@ -59,8 +59,8 @@ namespace {
 int32_t denoise_step_impl(const chorus_model_shape* model, const chorus_block_weights* blocks, const chorus_glue_weights* gw,
                           float* latent, const int32_t* token_idx, int64_t Ls, const uint16_t* text_ctx,
                           const uint8_t* text_kv, const float* t_mod, const float* t_head, const float* tgaa_key_scale,
-                          float gamma_o, float dsigma, const float* SL, const uint8_t* mask_edit, void* ws, size_t ws_bytes,
-                          void* stream) {
+                          float gamma_o, float dsigma, const float* SL, const uint8_t* mask_edit, bool outside_is_source,
+                          void* ws, size_t ws_bytes, void* stream) {
   int32_t st = check_model(model);
   if (st != CHORUS_OK) return st;
   const chorus_model_shape& m = *model;
@@ -86,11 +86,14 @@ int32_t denoise_step_impl(const chorus_model_shape* model, const chorus_block_we
                                    w.block, w.block_bytes, stream);
       if (st != CHORUS_OK) return st;
     }
-    st = chorus_head_update(latent, w.x, Ls, token_idx, gw, t_head, dsigma, m.block.D, m.C, m.T, m.Hl, m.Wl, m.ph,
-                            m.pw, w.glue, w.glue_bytes, stream);
+    // Eq. 6 inside the update pass when the latent outside the selection already is the source latent
+    const bool fused = mask_edit && outside_is_source;
+    st = chorus_head_update_region(latent, w.x, Ls, token_idx, gw, t_head, dsigma, fused ? SL : nullptr,
+                                   fused ? mask_edit : nullptr, m.block.D, m.C, m.T, m.Hl, m.Wl, m.ph, m.pw, w.glue,
+                                   w.glue_bytes, stream);
     if (st != CHORUS_OK) return st;
   }
-  if (mask_edit) {
+  if (mask_edit && !outside_is_source) {
     st = chorus_region_blend(latent, latent, SL, mask_edit, m.C, m.T, m.Hl, m.Wl, m.ph, m.pw, stream);
     if (st != CHORUS_OK) return st;
   }
@@ -203,7 +206,7 @@ int32_t chorus_denoise_step(const chorus_model_shape* model, const chorus_block_
                             const uint8_t* mask_edit, void* ws, size_t ws_bytes, void* stream) {
   if (!text_ctx) return CHORUS_E_ARG;
   return denoise_step_impl(model, blocks, gw, latent, token_idx, Ls, text_ctx, nullptr, t_mod, t_head, tgaa_key_scale,
-                           gamma_o, dsigma, SL, mask_edit, ws, ws_bytes, stream);
+                           gamma_o, dsigma, SL, mask_edit, false, ws, ws_bytes, stream);
 }
 
 int32_t chorus_denoise_step_kv(const chorus_model_shape* model, const chorus_block_weights* blocks,
@@ -213,7 +216,7 @@ int32_t chorus_denoise_step_kv(const chorus_model_shape* model, const chorus_blo
                                const uint8_t* mask_edit, void* ws, size_t ws_bytes, void* stream) {
   if (!text_kv) return CHORUS_E_ARG;
   return denoise_step_impl(model, blocks, gw, latent, token_idx, Ls, nullptr, (const uint8_t*)text_kv, t_mod, t_head,
-                           tgaa_key_scale, gamma_o, dsigma, SL, mask_edit, ws, ws_bytes, stream);
+                           tgaa_key_scale, gamma_o, dsigma, SL, mask_edit, false, ws, ws_bytes, stream);
 }
 
 size_t chorus_model_text_kv_bytes(const chorus_model_shape* model) {
@@ -485,11 +488,12 @@ int32_t chorus_denoise_run(const chorus_model_shape* model, const chorus_block_w
         history = 2;
       }
     } else if (p.stage == 2) {
+      // as above: after a reused step or an earlier stage-2 step Eq. 6 only has to touch the selected tokens
       st = denoise_step_impl(model, blocks, gw, latent, w.idx, Ls, rq->text_ctx, m.n_blocks > 0 ? (const uint8_t*)w.text_kv : nullptr,
-                             t_mod, t_head, ks, p.gamma_o, dsigma, SL, rq->mask_edit, w.step, w.step_bytes, stream);
+                             t_mod, t_head, ks, p.gamma_o, dsigma, SL, rq->mask_edit, i > 0, w.step, w.step_bytes, stream);
     } else {
       st = denoise_step_impl(model, blocks, gw, latent, nullptr, Ltok, rq->text_ctx, m.n_blocks > 0 ? (const uint8_t*)w.text_kv : nullptr,
-                             t_mod, t_head, ks, p.gamma_o, dsigma, nullptr, nullptr, w.step, w.step_bytes, stream);
+                             t_mod, t_head, ks, p.gamma_o, dsigma, nullptr, nullptr, false, w.step, w.step_bytes, stream);
     }
     if (st != CHORUS_OK) return st;
     // cache update after a miss: keep the prompt embedding and this intermediate latent for later requests

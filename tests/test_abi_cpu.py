@@ -210,6 +210,21 @@ def test_solver_entry_points_validate():
     assert lib.chorus_denoise_run_workspace_bytes(C.byref(ms), 4) >= b
 
 
+def test_head_update_region_validates():
+    lib = P.load()
+    null, p16 = C.c_void_p(0), C.c_void_p(16)
+    gw = B.GlueWeights(16, 16, 16, 16, 16)
+    args = lambda **k: [p16, p16, k.get("Ls", 4), null, C.byref(gw), p16, -0.25, k.get("SL", null), k.get("mask", null), 64, 16,
+                        1, 4, 4, 2, 2, k.get("ws", p16), k.get("ws_bytes", 1 << 30), null]
+    assert lib.chorus_head_update_region(*args(SL=C.c_void_p(48))) == B.E_ARG      # SL without mask
+    assert lib.chorus_head_update_region(*args(mask=C.c_void_p(48))) == B.E_ARG    # mask without SL
+    assert lib.chorus_head_update_region(*args(ws=null)) == B.E_WORKSPACE
+    assert lib.chorus_head_update_region(*args(ws_bytes=8)) == B.E_WORKSPACE
+    assert lib.chorus_head_update_region(*args(Ls=-1)) == B.E_ARG
+    assert lib.chorus_head_update_region(*args(Ls=0)) == B.OK
+    assert lib.chorus_head_update_region(*args(Ls=0, SL=C.c_void_p(48), mask=C.c_void_p(64))) == B.OK
+
+
 def test_mfma_ceiling_validates():
     lib = P.load()
     out = C.c_double(0)

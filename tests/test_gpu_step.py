@@ -60,6 +60,25 @@ def test_text_project_and_glue_ops():
     check(host(dl), ref_l, "head_update", max_abs=2e-3, rel_l2=1e-3)
     untouched = ~O.expand_token_mask(mask, bs.grid, bs.patch, bs.C).astype(bool)
     np.testing.assert_array_equal(host(dl)[untouched], lat[untouched])
+    # Eq. 6 inside the update pass: the selected tokens outside M_edit receive SL, the others the update: bit for bit
+    # what the update followed by the blend gives when the latent outside the selection already is SL
+    SL = synth.latent(bs, 0, "SL", std=1.0)
+    edit = (mask != 0) & (synth.exact_count_mask(bs.L, bs.L // 2, seed=5) != 0)
+    assert edit.any() and (edit != (mask != 0)).any()
+    start = np.where(O.expand_token_mask(mask, bs.grid, bs.patch, bs.C).astype(bool), lat, SL)   # SL outside the selection
+    d_edit = torch.from_numpy(edit.astype(np.uint8)).to(DEV)
+    two = dev_f32(start)
+    B.chorus_head_update(two, dev_f32(xin), idx.size, didx, md.dglue, md.d_theads[0], -0.25)
+    B.chorus_region_blend(two, two, dev_f32(SL), d_edit, patch_hw=bs.patch[1:])
+    one = dev_f32(start)
+    B.chorus_head_update_region(one, dev_f32(xin), idx.size, didx, md.dglue, md.d_theads[0], -0.25, dev_f32(SL), d_edit)
+    np.testing.assert_array_equal(host(one), host(two))
+    toks = O.patchify(start.astype(np.float64), bs.patch)
+    toks[idx] += -0.25 * O.head(xin, md.gw, md.t_heads[0])
+    ref_f = O.region_blend(O.unpatchify(toks, lat.shape, bs.patch), SL, edit, bs.grid, bs.patch)
+    check(host(one), ref_f, "head_update_region", max_abs=2e-3, rel_l2=1e-3)
+    keep = O.expand_token_mask(edit.astype(np.uint8), bs.grid, bs.patch, bs.C).astype(bool)
+    np.testing.assert_array_equal(host(one)[~keep], SL[~keep])
 
 
 @pytest.mark.parametrize("name,n_blocks,stress", [("c1", 2, True), ("wan1p3b_small", 2, False)])
