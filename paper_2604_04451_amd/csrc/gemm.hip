@@ -571,6 +571,9 @@ __global__ __launch_bounds__(256, 1) void gemm_w16_kernel(const uint16_t* __rest
   }
 
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the look-ahead loads of the last step have landed
+  // The compiler does not know the assembly above for MFMAs and so keeps no distance between the last of them and the
+  // first instruction that reads an accumulator: cover the longest such distance explicitly.
+  asm volatile("s_nop 15\n\ts_nop 15");
   lds_barrier();  // the staging regions of the epilogue overlay the operand stages
   gemm16_finish<EPI>(acc, ep, smem_raw, wave, wm, wn, m0, n0, M, N, lane);
 }
