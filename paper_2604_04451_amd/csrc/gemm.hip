@@ -388,23 +388,30 @@ __device__ __forceinline__ void gemm16_epilogue_resid(const f32x4 (&acc)[8][8], 
     gate *= ep.scale;
   }
   float* out = reinterpret_cast<float*>(ep.out);
-#pragma unroll
-  for (int mb = 0; mb < 8; ++mb) {
-    f32x4 cur[8];
+  // The residual rows of block mb + 1 are requested before the results of block mb are stored: memory operations
+  // retire in order, so a load issued behind a block's stores could only be consumed once those stores had drained.
+  f32x4 cur[2][8];
+  auto fetch = [&](int mb, f32x4 (&dst)[8]) {
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
       long m = m_wave0 + 16 * mb + 2 * it + rrow;
       if (m > M - 1) m = M - 1;  // rows past the end read the last row (never stored)
-      cur[it] = *reinterpret_cast<const f32x4*>(out + m * N + (n_ok ? n : 0));
+      dst[it] = *reinterpret_cast<const f32x4*>(out + m * N + (n_ok ? n : 0));
     }
+  };
+  fetch(0, cur[0]);
+#pragma unroll
+  for (int mb = 0; mb < 8; ++mb) {
 #pragma unroll
     for (int nb = 0; nb < 8; ++nb) *reinterpret_cast<f32x4*>(cw + lj * E16_F32_STRIDE + 16 * nb + 4 * lg) = acc[nb][mb];
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    if (mb + 1 < 8) fetch(mb + 1, cur[(mb + 1) & 1]);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
       const f32x4 v = *reinterpret_cast<const f32x4*>(cw + (2 * it + rrow) * E16_F32_STRIDE + rcol);
       const long m = m_wave0 + 16 * mb + 2 * it + rrow;
-      if (n_ok && m < M) *reinterpret_cast<f32x4*>(out + m * N + n) = cur[it] + gate * (v + bias);
+      if (n_ok && m < M) *reinterpret_cast<f32x4*>(out + m * N + n) = cur[mb & 1][it] + gate * (v + bias);
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
     __builtin_amdgcn_sched_barrier(0);
