@@ -79,8 +79,9 @@ int32_t chorus_v_transpose(const uint16_t* in, int64_t ld, uint16_t* out, int64_
  *   col_scale dev [Lk] fp32 or NULL
  * dh in {64,128}; LkPad % 64 == 0, LkPad >= Lk >= 1; rows/cols beyond Lq/Lk are padding
  * (finite values).
- * variant: 0 = the default choice (128-key tiles for col_scale == NULL, LkPad % 128 == 0 and Lk >= 2048, else
- * 64-key tiles); 3 = 64-key tiles; 4 = 128-key tiles, CHORUS_E_SHAPE with a col_scale or LkPad % 128 != 0.
+ * variant: 0 = the default choice (128-key tiles on 16x16x32 MFMAs for col_scale == NULL, LkPad % 128 == 0 and
+ * Lk >= 2048, else 64-key tiles); 3 = 64-key tiles; 4 = 128-key tiles on 32x32x16 MFMAs; 5 = 128-key tiles on
+ * 16x16x32 MFMAs; 4 and 5 give CHORUS_E_SHAPE with a col_scale or LkPad % 128 != 0.
  * Any other value: CHORUS_E_ARG. */
 int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O,
                          const float* col_scale, int64_t Lq, int64_t Lk, int64_t LqPad, int64_t LkPad, int32_t H,

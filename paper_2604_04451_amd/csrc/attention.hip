@@ -273,6 +273,314 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------
+// The same ping-pong kernel on v_mfma_f32_16x16x32_bf16, 128-key tiles, no column scale. Per flop this shape writes
+// half the accumulator registers of the 32x32x16 one and a result block is accumulated by four MFMAs in a row (the
+// whole head dimension or the whole key tile), which is what the power-managed part rewards.
+//
+// A wave still owns 32 query rows, as two blocks of 16 (rb). Lane l: query row l % 16 of each block, and of every
+// 16 x 16 result block the four rows 4 g .. 4 g + 3, g = l / 16.
+//   S^T block kb (16 keys x 16 query rows, kb = 0..7 of a 128-key tile): the K fragment's row r is key
+//   32 (kb / 2) + 16 (r / 8) + 8 (kb % 2) + r % 8 of the tile, so the lane holds keys 32 (kb / 2) + 16 (g / 2) +
+//   8 (kb % 2) + 4 (g % 2) + i. For a 32-key step of O^T += V^T P^T (blocks kb = 2 c, 2 c + 1) these eight keys are
+//   {4 (g % 2) .. + 3, 8 + 4 (g % 2) .. + 3} of the 16-key group 2 c + g / 2: exactly the eight consecutive
+//   positions 8 g .. 8 g + 7 of the step in the stored V^T order (see chorus_v_transpose), so the V operand is one
+//   16-byte LDS read and the lane's probabilities are its B operand as they stand.
+// LDS rows are padded by 32 bytes: with 16 rows x 4 chunks per fragment read that stride is free of bank conflicts.
+// ---------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
+    const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vt,
+    uint16_t* __restrict__ O, long Lq, long Lk, long LqPad, long LkPad, int H, int n_qtiles, float scale_log2) {
+  constexpr int NT = 512;
+  constexpr int KTL = 128;
+  constexpr int KS = DH + 16, VS = KTL + 16;  // padded LDS row strides (elements)
+  constexpr int KB = KTL / 16;                 // 16-key blocks of S^T per tile
+  constexpr int NC = KTL / 32;                 // 32-key MFMA steps of P V per tile
+  constexpr int KC = DH / 32;                  // 32-wide steps over the head dimension
+  constexpr int DB = DH / 16;                  // 16-row blocks of O^T
+  constexpr int K_LD = KTL * (DH / 8) / NT;
+  constexpr int V_LD = DH * (KTL / 8) / NT;
+  constexpr int QROWS = 8 * 32;
+
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+  uint16_t* smk = reinterpret_cast<uint16_t*>(smem_raw);   // [2][KTL][KS]
+  uint16_t* smv = smk + 2 * KTL * KS;                      // [2][DH][VS]
+
+  const int tile_id = xcd_remap(blockIdx.x, H * n_qtiles);
+  const int head = tile_id / n_qtiles;
+  const int qt = tile_id - head * n_qtiles;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int group = wave >> 2;
+  const int lq = lane & 15, g = lane >> 4;
+  const long q_wave0 = (long)qt * QROWS + wave * 32;
+
+  const uint16_t* Kh = K + (long)head * LkPad * DH;
+  const uint16_t* Vh = Vt + (long)head * DH * LkPad;
+
+  bf16x8 qf[2][KC];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    long q = q_wave0 + 16 * rb + lq;
+    if (q > Lq - 1) q = Lq - 1;
+    const uint16_t* qp = Q + ((long)head * LqPad + q) * DH + 8 * g;
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) qf[rb][kc] = *reinterpret_cast<const bf16x8*>(qp + 32 * kc);
+  }
+
+  f32x4 o[DB][2];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) o[db][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run[2] = {-INFINITY, -INFINITY};
+#ifdef PP16_LMFMA
+  f32x4 lacc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+  bf16x8 ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (bf16_t)1.0f;
+#else
+  float l_run[2] = {0.f, 0.f};
+#endif
+
+  const int ntiles = (int)((Lk + KTL - 1) / KTL);
+  u32x4 rk[K_LD], rv[V_LD];
+
+  auto load_k = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < K_LD; ++i)
+      rk[i] = *reinterpret_cast<const u32x4*>(Kh + (long)kt * KTL * DH + (tid + NT * i) * 8);
+  };
+  auto load_v = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < V_LD; ++i) {
+      int id = tid + NT * i, row = id / (KTL / 8), ch = id % (KTL / 8);
+      rv[i] = *reinterpret_cast<const u32x4*>(Vh + (long)row * LkPad + (long)kt * KTL + ch * 8);
+    }
+  };
+  auto store_k = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < K_LD; ++i) {
+      int id = tid + NT * i, row = id / (DH / 8), ch = id % (DH / 8);
+      *reinterpret_cast<u32x4*>(&smk[(buf * KTL + row) * KS + ch * 8]) = rk[i];
+    }
+  };
+  auto store_v = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < V_LD; ++i) {
+      int id = tid + NT * i, row = id / (KTL / 8), ch = id % (KTL / 8);
+      *reinterpret_cast<u32x4*>(&smv[(buf * DH + row) * VS + ch * 8]) = rv[i];
+    }
+  };
+  // LDS row of the K tile that fragment row lane % 16 of block kb stands for
+  const int krow0 = 16 * (lq >> 3) + (lq & 7);
+  f32x4 s[KB][2];
+  auto compute_s = [&](int buf) {
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+      bf16x8 kf[KC];
+      const int row = 32 * (kb >> 1) + 8 * (kb & 1) + krow0;
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc)
+        kf[kc] = *reinterpret_cast<const bf16x8*>(&smk[(buf * KTL + row) * KS + 32 * kc + 8 * g]);
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kc], qf[rb][kc], acc, 0, 0, 0);
+        s[kb][rb] = acc;
+      }
+    }
+  };
+
+  // prologue: K(0), V(0), K(1) into LDS; K(2), V(1) into the prefetch registers
+  load_k(0);
+  load_v(0);
+  store_k(0);
+  store_v(0);
+  if (ntiles > 1) {
+    load_k(1);
+    store_k(1);
+    load_v(1);
+  }
+  if (ntiles > 2) load_k(2);
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) asm volatile("" : "+v"(qf[rb][kc]));  // Q fragments resident before the loop
+  __syncthreads();
+  compute_s(0);
+  __syncthreads();
+  if (group == 1) lds_barrier();  // run one phase behind group 0
+
+  for (int j = 0; j < ntiles; ++j) {
+    // ================= VALU phase: softmax of tile j =================
+    __builtin_amdgcn_sched_barrier(0);
+    if (j == ntiles - 1 && (Lk % KTL) != 0) {
+      const long key0 = (long)j * KTL + 16 * (g >> 1) + 4 * (g & 1);
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const long key = key0 + 32 * (kb >> 1) + 8 * (kb & 1) + i;
+          if (key >= Lk) {
+            s[kb][0][i] = -INFINITY;
+            s[kb][1][i] = -INFINITY;
+          }
+        }
+    }
+    float mxs[2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+      float mx = s[0][rb][0];
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[kb][rb][i]);
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, swap_halves(mx));
+      mxs[rb] = mx * scale_log2;
+    }
+    if (__any(mxs[0] > m_run[0] + 8.0f || mxs[1] > m_run[1] + 8.0f)) {
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+        const float m_new = fmaxf(m_run[rb], mxs[rb]);
+        const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_new);
+        m_run[rb] = m_new;
+#ifdef PP16_LMFMA
+        lacc[rb] *= alpha;
+#else
+        l_run[rb] *= alpha;
+#endif
+#pragma unroll
+        for (int db = 0; db < DB; ++db) o[db][rb] *= alpha;
+      }
+    }
+    bf16x8 pf[NC][2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+      const float mref = m_run[rb];
+#ifndef PP16_LMFMA
+      float lsum = 0.f;
+#endif
+#pragma unroll
+      for (int c = 0; c < NC; ++c)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * c + b][rb][i], scale_log2, -mref));
+#ifndef PP16_LMFMA
+            lsum += p;
+#endif
+            pf[c][rb][4 * b + i] = (bf16_t)p;
+          }
+#ifndef PP16_LMFMA
+      l_run[rb] += lsum;
+#endif
+    }
+    // the probabilities must exist before the barrier (otherwise the compiler sinks the
+    // exponentials into the MFMA phase, which defeats the phase split)
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) asm volatile("" : "+v"(pf[c][rb]));
+    __builtin_amdgcn_sched_barrier(0);
+    lds_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ================= MFMA phase: O += V(j) P(j); S(j+1) = K(j+1) Q^T =================
+    __builtin_amdgcn_s_setprio(1);
+    store_k(j & 1);
+    store_v((j + 1) & 1);
+    load_k(j + 3 < ntiles ? j + 3 : ntiles - 1);
+    load_v(j + 2 < ntiles ? j + 2 : ntiles - 1);
+    {
+      const int vb = j & 1;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        bf16x8 vf[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+          vf[c] = *reinterpret_cast<const bf16x8*>(&smv[(vb * DH + 16 * db + lq) * VS + 32 * c + 8 * g]);
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int c = 0; c < NC; ++c) o[db][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[c], pf[c][rb], o[db][rb], 0, 0, 0);
+      }
+#ifdef PP16_LMFMA
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int c = 0; c < NC; ++c) lacc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pf[c][rb], lacc[rb], 0, 0, 0);
+#endif
+    }
+    compute_s((j + 1) & 1);
+    // issue order: LDS stores, global prefetch, then LDS operand reads kept ahead of the MFMAs (one read feeds two)
+    __builtin_amdgcn_sched_group_barrier(0x200, K_LD + V_LD, 0);
+    __builtin_amdgcn_sched_group_barrier(0x020, K_LD + V_LD, 0);
+#ifndef PP16_AHEAD
+#define PP16_AHEAD 6
+#endif
+    __builtin_amdgcn_sched_group_barrier(0x100, PP16_AHEAD, 0);
+#pragma unroll
+    for (int i = 0; i < DB * NC + KB * KC - PP16_AHEAD; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+#ifdef PP16_LMFMA
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * PP16_AHEAD + 2 * NC, 0);
+#else
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * PP16_AHEAD, 0);
+#endif
+    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+    lds_barrier();  // this wave's LDS stores are done; the global prefetch stays in flight
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  if (group == 0) lds_barrier();  // every wave executes the same number of barriers
+
+  const int D = H * DH;
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+#ifdef PP16_LMFMA
+    const float l = lacc[rb][0];
+#else
+    float l = l_run[rb];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+#endif
+    const float inv = 1.0f / l;
+    const long q = q_wave0 + 16 * rb + lq;
+    if (q < Lq) {
+      uint16_t* op = O + q * (long)D + head * DH + 4 * g;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        uint2 w;
+        w.x = pack_bf16x2(o[db][rb][0] * inv, o[db][rb][1] * inv);
+        w.y = pack_bf16x2(o[db][rb][2] * inv, o[db][rb][3] * inv);
+        *reinterpret_cast<uint2*>(op + 16 * db) = w;
+      }
+    }
+  }
+}
+
+template <int DH>
+int32_t launch_attn_pp16(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, long Lq, long Lk, long LqPad,
+                         long LkPad, int H, hipStream_t s) {
+  long nqt = (Lq + 255) / 256;
+  if (nqt * H > 0x7fffffffL) return CHORUS_E_SHAPE;
+  size_t smem = 2 * ((size_t)128 * (DH + 16) + (size_t)DH * (128 + 16)) * sizeof(uint16_t);
+  auto kern = attention_pp16_kernel<DH>;
+  static DynLdsOnce once;  // the raised dynamic-LDS limit is a per-device property of the kernel
+  CHK_STATUS(once.ensure(reinterpret_cast<const void*>(kern), (int)smem));
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(nqt * H)), dim3(512), smem, s, Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, (int)nqt,
+                     scale_log2);
+  CHORUS_LAUNCH_CHECK();
+  return CHORUS_OK;
+}
+
 template <int DH, int KTL, bool CS>
 int32_t launch_attn_pp(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, const float* cs, long Lq,
                        long Lk, long LqPad, long LkPad, int H, hipStream_t s) {
@@ -294,12 +602,13 @@ int32_t launch_attn_pp(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt,
 
 using namespace chorus;
 
-// variant: 0 = default choice; 3 = 64-key tiles; 4 = 128-key tiles (no column scale, LkPad % 128 == 0)
+// variant: 0 = default choice; 3 = 64-key tiles; 4 = 128-key tiles (no column scale, LkPad % 128 == 0);
+// 5 = 128-key tiles on 16x16x32 MFMAs (same conditions)
 extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O,
                                     const float* col_scale, int64_t Lq, int64_t Lk, int64_t LqPad, int64_t LkPad,
                                     int32_t H, int32_t dh, int32_t variant, void* stream) {
   if (Lq < 0 || Lk < 0 || H <= 0) return CHORUS_E_ARG;
-  if (variant != 0 && variant != 3 && variant != 4) return CHORUS_E_ARG;
+  if (variant != 0 && variant != 3 && variant != 4 && variant != 5) return CHORUS_E_ARG;
   if (Lq == 0) return CHORUS_OK;
   if (Lk < 1) return CHORUS_E_SHAPE;
   if (!Q || !K || !Vt || !O) return CHORUS_E_ARG;
@@ -309,7 +618,12 @@ extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const 
   const bool cs = col_scale != nullptr;
   // 128-key tiles when the padding allows and no column scale is needed (with it that tile size would spill
   // registers, so it is not built)
-  if (variant == 0) variant = (!cs && LkPad % 128 == 0 && Lk >= 2048) ? 4 : 3;
+  if (variant == 0) variant = (!cs && LkPad % 128 == 0 && Lk >= 2048) ? 5 : 3;
+  if (variant == 5) {
+    if (cs || LkPad % 128) return CHORUS_E_SHAPE;
+    return dh == 128 ? launch_attn_pp16<128>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s)
+                     : launch_attn_pp16<64>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s);
+  }
   if (variant == 4) {
     if (cs || LkPad % 128) return CHORUS_E_SHAPE;
     return dh == 128 ? launch_attn_pp<128, 128, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)

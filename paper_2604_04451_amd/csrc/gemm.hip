@@ -311,9 +311,9 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t* __res
 // consecutive output columns n.
 //
 // One loop iteration per k-step, hand-laid for a single wave per SIMD (nothing else hides a gap between two MFMAs):
-// half-step 0 (64 MFMAs) with the LDS reads of half-step 1's fragments and the second half of the next step's loads;
-// the first 32 MFMAs of half-step 1; vmcnt(0) + barrier; the last 32 MFMAs with the LDS reads of the next step's
-// first fragments and the first half of the loads of the step after next (their stage is free behind the barrier).
+// half-step 0 (64 MFMAs) with the LDS reads of half-step 1's fragments; vmcnt(0) + barrier; half-step 1 (64 MFMAs) with
+// the LDS reads of the next step's first fragments and the 16 loads of the step after next (their stage is free behind
+// the barrier). Every read and load stands alone between two MFMAs.
 // The MFMAs are volatile assembly, in place on their accumulators: left to the register allocator every result gets
 // a new home, at the price of several hundred accumulator moves per k-step.
 // ---------------------------------------------------------------------------

@@ -141,9 +141,9 @@ def _attn_case(H, dh, Lq, Lk, variant, col_scale=None, q_std=1.0, seed=0, name="
                  max_abs=max(np.abs(ref).max() * 2 ** -7, 2e-3), rel_l2=5e-3)
 
 
-# variant 0 is the library's own choice (128-key tiles from 2048 keys on, else 64-key tiles), 3 and 4 force the
-# 64- and the 128-key tile kernel: every shape runs through the kernel the block and the benchmark launch.
-ATTN_VARIANTS = [0, 3, 4]
+# variant 0 is the library's own choice (128-key tiles from 2048 keys on, else 64-key tiles), 3, 4 and 5 force the
+# 64-key, the 128-key and the 128-key 16x16x32-MFMA tile kernel: every shape runs through the kernel the block and the benchmark launch.
+ATTN_VARIANTS = [0, 3, 4, 5]
 
 
 @pytest.mark.parametrize("variant", ATTN_VARIANTS)
@@ -178,13 +178,17 @@ def test_attention_variant_argument_errors():
     Oo = torch.zeros(L, H * dh, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(P.ChorusError):
         B.chorus_attention(Q, K, Vt, Oo, torch.ones(L, device=DEV), L, L, 4)
-    for bad in (1, 2, 5, -1):
+    with pytest.raises(P.ChorusError):
+        B.chorus_attention(Q, K, Vt, Oo, torch.ones(L, device=DEV), L, L, 5)
+    for bad in (1, 2, 6, -1):
         with pytest.raises(P.ChorusError):
             B.chorus_attention(Q, K, Vt, Oo, None, L, L, bad)
     K64 = torch.zeros(H, 64, dh, dtype=torch.bfloat16, device=DEV)
     Vt64 = torch.zeros(H * dh, 64, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(P.ChorusError):
         B.chorus_attention(Q, K64, Vt64, Oo, None, L, 64, 4)
+    with pytest.raises(P.ChorusError):
+        B.chorus_attention(Q, K64, Vt64, Oo, None, L, 64, 5)
 
 
 @pytest.mark.parametrize("variant", [0, 3])
