@@ -287,6 +287,10 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
 //   positions 8 g .. 8 g + 7 of the step in the stored V^T order (see chorus_v_transpose), so the V operand is one
 //   16-byte LDS read and the lane's probabilities are its B operand as they stand.
 // LDS rows are padded by 32 bytes: with 16 rows x 4 chunks per fragment read that stride is free of bank conflicts.
+// Two things leave the vector pipe, which in this kernel is as loaded as the matrix pipe: the softmax row sums are
+// taken by the matrix pipe (one more result block per 16 query rows whose V operand is all ones, so the sum is over
+// the same bf16-rounded probabilities that weight V and the weights of a row add up to exactly one), and the global
+// prefetch of the next tiles is issued at the start of the softmax phase instead of the MFMA phase.
 // ---------------------------------------------------------------------------
 template <int DH>
 __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
@@ -334,14 +338,10 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) o[db][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m_run[2] = {-INFINITY, -INFINITY};
-#ifdef PP16_LMFMA
   f32x4 lacc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
   bf16x8 ones;
 #pragma unroll
   for (int e = 0; e < 8; ++e) ones[e] = (bf16_t)1.0f;
-#else
-  float l_run[2] = {0.f, 0.f};
-#endif
 
   const int ntiles = (int)((Lk + KTL - 1) / KTL);
   u32x4 rk[K_LD], rv[V_LD];
@@ -401,9 +401,7 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
   if (ntiles > 1) {
     load_k(1);
     store_k(1);
-    load_v(1);
   }
-  if (ntiles > 2) load_k(2);
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -416,6 +414,9 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
   for (int j = 0; j < ntiles; ++j) {
     // ================= VALU phase: softmax of tile j =================
     __builtin_amdgcn_sched_barrier(0);
+    // the global prefetch of the tiles that the next MFMA phase stores: K(j+2), V(j+1) (past the end the last tile again)
+    load_k(j + 2 < ntiles ? j + 2 : ntiles - 1);
+    load_v(j + 1 < ntiles ? j + 1 : ntiles - 1);
     if (j == ntiles - 1 && (Lk % KTL) != 0) {
       const long key0 = (long)j * KTL + 16 * (g >> 1) + 4 * (g & 1);
 #pragma unroll
@@ -437,7 +438,7 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[kb][rb][i]);
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, swap_rows16(mx));
       mx = fmaxf(mx, swap_halves(mx));
       mxs[rb] = mx * scale_log2;
     }
@@ -447,11 +448,7 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
         const float m_new = fmaxf(m_run[rb], mxs[rb]);
         const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_new);
         m_run[rb] = m_new;
-#ifdef PP16_LMFMA
         lacc[rb] *= alpha;
-#else
-        l_run[rb] *= alpha;
-#endif
 #pragma unroll
         for (int db = 0; db < DB; ++db) o[db][rb] *= alpha;
       }
@@ -460,9 +457,6 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
       const float mref = m_run[rb];
-#ifndef PP16_LMFMA
-      float lsum = 0.f;
-#endif
 #pragma unroll
       for (int c = 0; c < NC; ++c)
 #pragma unroll
@@ -470,14 +464,8 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * c + b][rb][i], scale_log2, -mref));
-#ifndef PP16_LMFMA
-            lsum += p;
-#endif
             pf[c][rb][4 * b + i] = (bf16_t)p;
           }
-#ifndef PP16_LMFMA
-      l_run[rb] += lsum;
-#endif
     }
     // the probabilities must exist before the barrier (otherwise the compiler sinks the
     // exponentials into the MFMA phase, which defeats the phase split)
@@ -493,8 +481,6 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
     __builtin_amdgcn_s_setprio(1);
     store_k(j & 1);
     store_v((j + 1) & 1);
-    load_k(j + 3 < ntiles ? j + 3 : ntiles - 1);
-    load_v(j + 2 < ntiles ? j + 2 : ntiles - 1);
     {
       const int vb = j & 1;
 #pragma unroll
@@ -508,17 +494,14 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
 #pragma unroll
           for (int c = 0; c < NC; ++c) o[db][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[c], pf[c][rb], o[db][rb], 0, 0, 0);
       }
-#ifdef PP16_LMFMA
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
         for (int c = 0; c < NC; ++c) lacc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pf[c][rb], lacc[rb], 0, 0, 0);
-#endif
     }
     compute_s((j + 1) & 1);
     // issue order: LDS stores, global prefetch, then LDS operand reads kept ahead of the MFMAs (one read feeds two)
     __builtin_amdgcn_sched_group_barrier(0x200, K_LD + V_LD, 0);
-    __builtin_amdgcn_sched_group_barrier(0x020, K_LD + V_LD, 0);
 #ifndef PP16_AHEAD
 #define PP16_AHEAD 6
 #endif
@@ -528,11 +511,7 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
       __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
-#ifdef PP16_LMFMA
     __builtin_amdgcn_sched_group_barrier(0x008, 2 * PP16_AHEAD + 2 * NC, 0);
-#else
-    __builtin_amdgcn_sched_group_barrier(0x008, 2 * PP16_AHEAD, 0);
-#endif
     __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
     lds_barrier();  // this wave's LDS stores are done; the global prefetch stays in flight
@@ -543,13 +522,7 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
   const int D = H * DH;
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
-#ifdef PP16_LMFMA
     const float l = lacc[rb][0];
-#else
-    float l = l_run[rb];
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
-#endif
     const float inv = 1.0f / l;
     const long q = q_wave0 + 16 * rb + lq;
     if (q < Lq) {

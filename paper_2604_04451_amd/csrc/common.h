@@ -97,6 +97,13 @@ __device__ __forceinline__ float swap_halves(float v) {
   return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
 }
 
+// value of the lane 16 away (lanes l and l ^ 16 exchange), likewise one register-file swap instruction
+__device__ __forceinline__ float swap_rows16(float v) {
+  const uint32_t b = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane16_swap(b, b, false, false);  // r[0] = rows (0, 0, 2, 2), r[1] = rows (1, 1, 3, 3)
+  return __uint_as_float((threadIdx.x & 16) ? r[0] : r[1]);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
