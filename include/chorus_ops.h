@@ -7,6 +7,8 @@
 #ifndef CHORUS_OPS_H
 #define CHORUS_OPS_H
 
+#include <math.h>
+
 #include "chorus.h"
 
 #ifdef __cplusplus
@@ -57,10 +59,13 @@ int32_t chorus_ln_modulate(const float* x, uint16_t* out, int64_t L, int32_t D, 
  * RoPE at the token's original grid position, written head-major:
  *   in  dev bf16, row i at in + i*ld, D values
  *   out dev bf16 [H, Lpad, dh]; rows L..Lpad-1 are written as zeros
- *   token_idx dev [L] int32 or NULL (identity) */
+ *   token_idx dev [L] int32 or NULL (identity)
+ *   out_scale: finite, > 0; every output is multiplied by it in fp32 before the one rounding to bf16 (1 for the
+ *   plain operation; the block passes CHORUS_ATTENTION_Q_PRESCALE(dh) for the queries of chorus_attention's
+ *   variant 6). CHORUS_E_ARG otherwise. */
 int32_t chorus_qk_norm_rope(const uint16_t* in, int64_t ld, const float* gain, uint16_t* out, int64_t L, int64_t Lpad,
                             int32_t H, int32_t dh, const int32_t* token_idx, int32_t gT, int32_t gH, int32_t gW,
-                            int32_t rope, void* stream);
+                            int32_t rope, float out_scale, void* stream);
 
 /* V [L, D] (row i at in + i*ld) -> Vt [D, Lpad], zero beyond L, with the token order
  * inside every group of 16 permuted to the attention kernel's operand order:
@@ -81,8 +86,11 @@ int32_t chorus_v_transpose(const uint16_t* in, int64_t ld, uint16_t* out, int64_
  * (finite values).
  * variant: 0 = the default choice (128-key tiles on 16x16x32 MFMAs for col_scale == NULL, LkPad % 128 == 0 and
  * Lk >= 2048, else 64-key tiles); 3 = 64-key tiles; 4 = 128-key tiles on 32x32x16 MFMAs; 5 = 128-key tiles on
- * 16x16x32 MFMAs; 4 and 5 give CHORUS_E_SHAPE with a col_scale or LkPad % 128 != 0.
- * Any other value: CHORUS_E_ARG. */
+ * 16x16x32 MFMAs; 6 = as 5 for a Q that holds the queries already multiplied by log2(e) / sqrt(dh)
+ * (CHORUS_ATTENTION_Q_PRESCALE(dh), applied in fp32 by the producer before its rounding to bf16): the same
+ * function of the unscaled queries, with one vector instruction less per logit. 4, 5 and 6 give CHORUS_E_SHAPE
+ * with a col_scale or LkPad % 128 != 0. Any other value: CHORUS_E_ARG. */
+#define CHORUS_ATTENTION_Q_PRESCALE(dh) (1.4426950408889634f / sqrtf((float)(dh)))
 int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O,
                          const float* col_scale, int64_t Lq, int64_t Lk, int64_t LqPad, int64_t LkPad, int32_t H,
                          int32_t dh, int32_t variant, void* stream);

@@ -147,7 +147,7 @@ def _bind_ops(lib):
         "chorus_gemm_bf16": (i32, [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, f32, vp]),
         "chorus_gemm_bf16_kernel": (i32, [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, f32, i32, vp]),
         "chorus_ln_modulate": (i32, [vp, vp, i64, i32, vp, vp, vp, vp, i32, vp]),
-        "chorus_qk_norm_rope": (i32, [vp, i64, vp, vp, i64, i64, i32, i32, vp, i32, i32, i32, i32, vp]),
+        "chorus_qk_norm_rope": (i32, [vp, i64, vp, vp, i64, i64, i32, i32, vp, i32, i32, i32, i32, f32, vp]),
         "chorus_v_transpose": (i32, [vp, i64, vp, i64, i64, i32, vp]),
         "chorus_attention": (i32, [vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, i32, i32, vp]),
         "chorus_glue_workspace_bytes": (sz, [i32, i32, i64]),
@@ -547,8 +547,8 @@ def chorus_ln_modulate(x, out, mul0, mul1, add0, add1, plus_one):
     return out
 
 
-def chorus_qk_norm_rope(inp, col0, gain, out, L, H, dh, token_idx, grid, rope):
-    """inp: bf16 [L, ld]; the D = H*dh columns starting at col0 are normalised."""
+def chorus_qk_norm_rope(inp, col0, gain, out, L, H, dh, token_idx, grid, rope, out_scale=1.0):
+    """inp: bf16 [L, ld]; the D = H*dh columns starting at col0 are normalised (and multiplied by out_scale)."""
     lib = load()
     _chk(inp, torch.bfloat16, "inp")
     _chk(out, torch.bfloat16, "out")
@@ -560,7 +560,7 @@ def chorus_qk_norm_rope(inp, col0, gain, out, L, H, dh, token_idx, grid, rope):
         raise TypeError("shape mismatch")
     ptr = C.c_void_p(inp.data_ptr() + 2 * col0)
     _status("chorus_qk_norm_rope", lib.chorus_qk_norm_rope(ptr, ld, _p(gain), _p(out), L, Lpad, H, dh, _p(token_idx),
-                                                           grid[0], grid[1], grid[2], int(rope), _stream()))
+                                                           grid[0], grid[1], grid[2], int(rope), float(out_scale), _stream()))
     return out
 
 

@@ -292,7 +292,7 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
 // the same bf16-rounded probabilities that weight V and the weights of a row add up to exactly one), and the global
 // prefetch of the next tiles is issued at the start of the softmax phase instead of the MFMA phase.
 // ---------------------------------------------------------------------------
-template <int DH>
+template <int DH, bool PRE>
 __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vt,
     uint16_t* __restrict__ O, long Lq, long Lk, long LqPad, long LkPad, int H, int n_qtiles, float scale_log2) {
@@ -337,7 +337,9 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) o[db][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run[2] = {-INFINITY, -INFINITY};
+  // PRE: Q arrives multiplied by log2(e) / sqrt(dh) and the S^T accumulators start at minus the running reference, so
+  // a logit leaves the MFMA as the exponent of its probability; the reference starts at 0 and the first tile sets it.
+  float m_run[2] = {PRE ? 0.f : -INFINITY, PRE ? 0.f : -INFINITY};
   f32x4 lacc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
   bf16x8 ones;
 #pragma unroll
@@ -385,7 +387,8 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
         kf[kc] = *reinterpret_cast<const bf16x8*>(&smk[(buf * KTL + row) * KS + 32 * kc + 8 * g]);
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        const float a0 = PRE ? -m_run[rb] : 0.f;
+        f32x4 acc = {a0, a0, a0, a0};
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kc], qf[rb][kc], acc, 0, 0, 0);
         s[kb][rb] = acc;
@@ -440,9 +443,26 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
         for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[kb][rb][i]);
       mx = fmaxf(mx, swap_rows16(mx));
       mx = fmaxf(mx, swap_halves(mx));
-      mxs[rb] = mx * scale_log2;
+      mxs[rb] = PRE ? mx : mx * scale_log2;
     }
-    if (__any(mxs[0] > m_run[0] + 8.0f || mxs[1] > m_run[1] + 8.0f)) {
+    if constexpr (PRE) {
+      // logits are relative to the reference already: move it when a row exceeds it by more than 8, and on the first tile
+      if (__any(mxs[0] > 8.0f || mxs[1] > 8.0f) || j == 0) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+          const float delta = j == 0 ? mxs[rb] : fmaxf(mxs[rb], 0.f);
+          const float alpha = j == 0 ? 1.0f : __builtin_amdgcn_exp2f(-delta);  // nothing is accumulated before the first tile
+          m_run[rb] += delta;
+          lacc[rb] *= alpha;
+#pragma unroll
+          for (int db = 0; db < DB; ++db) o[db][rb] *= alpha;
+#pragma unroll
+          for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s[kb][rb][i] -= delta;
+        }
+      }
+    } else if (__any(mxs[0] > m_run[0] + 8.0f || mxs[1] > m_run[1] + 8.0f)) {
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) {
         const float m_new = fmaxf(m_run[rb], mxs[rb]);
@@ -463,7 +483,8 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
         for (int b = 0; b < 2; ++b)
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * c + b][rb][i], scale_log2, -mref));
+            const float p = PRE ? __builtin_amdgcn_exp2f(s[2 * c + b][rb][i])
+                                : __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * c + b][rb][i], scale_log2, -mref));
             pf[c][rb][4 * b + i] = (bf16_t)p;
           }
     }
@@ -538,13 +559,13 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
   }
 }
 
-template <int DH>
+template <int DH, bool PRE>
 int32_t launch_attn_pp16(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, long Lq, long Lk, long LqPad,
                          long LkPad, int H, hipStream_t s) {
   long nqt = (Lq + 255) / 256;
   if (nqt * H > 0x7fffffffL) return CHORUS_E_SHAPE;
   size_t smem = 2 * ((size_t)128 * (DH + 16) + (size_t)DH * (128 + 16)) * sizeof(uint16_t);
-  auto kern = attention_pp16_kernel<DH>;
+  auto kern = attention_pp16_kernel<DH, PRE>;
   static DynLdsOnce once;  // the raised dynamic-LDS limit is a per-device property of the kernel
   CHK_STATUS(once.ensure(reinterpret_cast<const void*>(kern), (int)smem));
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
@@ -581,7 +602,7 @@ extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const 
                                     const float* col_scale, int64_t Lq, int64_t Lk, int64_t LqPad, int64_t LkPad,
                                     int32_t H, int32_t dh, int32_t variant, void* stream) {
   if (Lq < 0 || Lk < 0 || H <= 0) return CHORUS_E_ARG;
-  if (variant != 0 && variant != 3 && variant != 4 && variant != 5) return CHORUS_E_ARG;
+  if (variant != 0 && variant != 3 && variant != 4 && variant != 5 && variant != 6) return CHORUS_E_ARG;
   if (Lq == 0) return CHORUS_OK;
   if (Lk < 1) return CHORUS_E_SHAPE;
   if (!Q || !K || !Vt || !O) return CHORUS_E_ARG;
@@ -592,10 +613,13 @@ extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const 
   // 128-key tiles when the padding allows and no column scale is needed (with it that tile size would spill
   // registers, so it is not built)
   if (variant == 0) variant = (!cs && LkPad % 128 == 0 && Lk >= 2048) ? 5 : 3;
-  if (variant == 5) {
+  if (variant == 5 || variant == 6) {
     if (cs || LkPad % 128) return CHORUS_E_SHAPE;
-    return dh == 128 ? launch_attn_pp16<128>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s)
-                     : launch_attn_pp16<64>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s);
+    if (variant == 6)
+      return dh == 128 ? launch_attn_pp16<128, true>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s)
+                       : launch_attn_pp16<64, true>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s);
+    return dh == 128 ? launch_attn_pp16<128, false>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s)
+                     : launch_attn_pp16<64, false>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s);
   }
   if (variant == 4) {
     if (cs || LkPad % 128) return CHORUS_E_SHAPE;

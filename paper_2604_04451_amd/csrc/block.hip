@@ -167,7 +167,7 @@ int32_t project_text_kv(const chorus_block_shape& sh, const chorus_block_weights
   }
   {
     ProfScope p(CHORUS_PROF_NORM, s);
-    CHK(chorus_qk_norm_rope(tkv, 2L * D, w->g_ck, kc, Lt, LtPad, H, dh, nullptr, sh.gT, sh.gH, sh.gW, 0, stream));
+    CHK(chorus_qk_norm_rope(tkv, 2L * D, w->g_ck, kc, Lt, LtPad, H, dh, nullptr, sh.gT, sh.gH, sh.gW, 0, 1.0f, stream));
     CHK(chorus_v_transpose(tkv + D, 2L * D, vct, Lt, LtPad, D, stream));
   }
   return CHORUS_OK;
@@ -202,17 +202,21 @@ int32_t block_step_impl(const chorus_block_shape* shape, const chorus_block_weig
     ProfScope p(CHORUS_PROF_GEMM, s);
     CHK(chorus_gemm_bf16(b.h, w->w_qkv, Ls, 3 * D, D, CHORUS_EPI_BF16, b.qkv, w->b_qkv, nullptr, nullptr, 1.f, stream));
   }
-  // 2-3. q/k RMSNorm + RoPE into head-major layout; V into key-contiguous layout
+  // 2-3. q/k RMSNorm + RoPE into head-major layout; V into key-contiguous layout.
+  // Long self-attention runs the kernel that takes its queries already multiplied by log2(e) / sqrt(dh): the factor
+  // enters here, in fp32 ahead of the one rounding to bf16 (the same condition as chorus_attention's default choice).
+  const bool q_prescaled = Lpad % 128 == 0 && Ls >= 2048;
   {
     ProfScope p(CHORUS_PROF_NORM, s);
-    CHK(chorus_qk_norm_rope(b.qkv, 3L * D, w->g_q, b.qh, Ls, Lpad, H, dh, token_idx, sh.gT, sh.gH, sh.gW, 1, stream));
-    CHK(chorus_qk_norm_rope(b.qkv + D, 3L * D, w->g_k, b.kh, Ls, Lpad, H, dh, token_idx, sh.gT, sh.gH, sh.gW, 1, stream));
+    CHK(chorus_qk_norm_rope(b.qkv, 3L * D, w->g_q, b.qh, Ls, Lpad, H, dh, token_idx, sh.gT, sh.gH, sh.gW, 1,
+                            q_prescaled ? CHORUS_ATTENTION_Q_PRESCALE(dh) : 1.0f, stream));
+    CHK(chorus_qk_norm_rope(b.qkv + D, 3L * D, w->g_k, b.kh, Ls, Lpad, H, dh, token_idx, sh.gT, sh.gH, sh.gW, 1, 1.0f, stream));
     CHK(chorus_v_transpose(b.qkv + 2 * D, 3L * D, b.vt, Ls, Lpad, D, stream));
   }
   // 4. self-attention over exactly the Ls rows, output projection, gated residual
   {
     ProfScope p(CHORUS_PROF_SELF_ATTN, s);
-    CHK(chorus_attention(b.qh, b.kh, b.vt, b.ao, nullptr, Ls, Ls, Lpad, Lpad, H, dh, 0, stream));
+    CHK(chorus_attention(b.qh, b.kh, b.vt, b.ao, nullptr, Ls, Ls, Lpad, Lpad, H, dh, q_prescaled ? 6 : 0, stream));
   }
   {
     ProfScope p(CHORUS_PROF_GEMM, s);
@@ -237,7 +241,7 @@ int32_t block_step_impl(const chorus_block_shape* shape, const chorus_block_weig
   }
   {
     ProfScope p(CHORUS_PROF_NORM, s);
-    CHK(chorus_qk_norm_rope(b.qkv, D, w->g_cq, b.qh, Ls, Lpad, H, dh, nullptr, sh.gT, sh.gH, sh.gW, 0, stream));
+    CHK(chorus_qk_norm_rope(b.qkv, D, w->g_cq, b.qh, Ls, Lpad, H, dh, nullptr, sh.gT, sh.gH, sh.gW, 0, 1.0f, stream));
   }
   {
     ProfScope p(CHORUS_PROF_CROSS_ATTN, s);

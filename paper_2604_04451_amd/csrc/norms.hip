@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void qk_norm_rope_kernel(const uint16_t* __res
                                                            const float* __restrict__ gain, uint16_t* __restrict__ out,
                                                            long L, long Lpad, int H, int dh,
                                                            const int* __restrict__ token_idx, int gH, int gW,
-                                                           int rope) {
+                                                           int rope, float out_scale) {
   __shared__ float s_cos[4][64];
   __shared__ float s_sin[4][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(256) void qk_norm_rope_kernel(const uint16_t* __res
       }
     }
   }
-  const float rstd = rsqrtf(wave_sum(ss) / (float)D + kEps);
+  const float rstd = rsqrtf(wave_sum(ss) / (float)D + kEps) * out_scale;
   const int iters = NCH > 0 ? NCH : (nchunk + 63) / 64;
 #pragma unroll
   for (int it = 0; it < iters; ++it) {
@@ -275,9 +275,9 @@ int32_t chorus_ln_modulate(const float* x, uint16_t* out, int64_t L, int32_t D, 
 
 int32_t chorus_qk_norm_rope(const uint16_t* in, int64_t ld, const float* gain, uint16_t* out, int64_t L, int64_t Lpad,
                             int32_t H, int32_t dh, const int32_t* token_idx, int32_t gT, int32_t gH, int32_t gW,
-                            int32_t rope, void* stream) {
+                            int32_t rope, float out_scale, void* stream) {
   (void)gT;
-  if (L < 0 || Lpad < L || H <= 0 || dh <= 0) return CHORUS_E_ARG;
+  if (L < 0 || Lpad < L || H <= 0 || dh <= 0 || !(out_scale > 0.f) || !(out_scale < INFINITY)) return CHORUS_E_ARG;
   if (Lpad == 0) return CHORUS_OK;
   if (!in || !gain || !out) return CHORUS_E_ARG;
   if (dh % 8 || dh > 128 || (dh / 6) * 6 > dh || ld % 8) return CHORUS_E_SHAPE;
@@ -287,16 +287,16 @@ int32_t chorus_qk_norm_rope(const uint16_t* in, int64_t ld, const float* gain, u
   const int D_ = H * dh;  // widths with a register-resident row: 512 elements per chunk round
   if (D_ == 1536) {
     hipLaunchKernelGGL(qk_norm_rope_kernel<3>, dim3((unsigned)((Lpad + 3) / 4)), dim3(256), 0, s, in, (long)ld, gain, out,
-                     (long)L, (long)Lpad, H, dh, token_idx, gH, gW, rope);
+                     (long)L, (long)Lpad, H, dh, token_idx, gH, gW, rope, out_scale);
   } else if (D_ == 5120) {
     hipLaunchKernelGGL(qk_norm_rope_kernel<10>, dim3((unsigned)((Lpad + 3) / 4)), dim3(256), 0, s, in, (long)ld, gain, out,
-                     (long)L, (long)Lpad, H, dh, token_idx, gH, gW, rope);
+                     (long)L, (long)Lpad, H, dh, token_idx, gH, gW, rope, out_scale);
   } else if (D_ == 512) {
     hipLaunchKernelGGL(qk_norm_rope_kernel<1>, dim3((unsigned)((Lpad + 3) / 4)), dim3(256), 0, s, in, (long)ld, gain, out,
-                     (long)L, (long)Lpad, H, dh, token_idx, gH, gW, rope);
+                     (long)L, (long)Lpad, H, dh, token_idx, gH, gW, rope, out_scale);
   } else {
     hipLaunchKernelGGL(qk_norm_rope_kernel<0>, dim3((unsigned)((Lpad + 3) / 4)), dim3(256), 0, s, in, (long)ld, gain, out,
-                     (long)L, (long)Lpad, H, dh, token_idx, gH, gW, rope);
+                     (long)L, (long)Lpad, H, dh, token_idx, gH, gW, rope, out_scale);
   }
   CHORUS_LAUNCH_CHECK();
   return CHORUS_OK;

@@ -66,6 +66,18 @@ def test_self_attention_full_length_peaked(H, L):
         got = host_bf16(Oo)
         assert np.isfinite(got).all()
         check(got[rows], ref, f"attention full length H={H} L={L} v{variant}", max_abs=max(np.abs(ref).max() * 2 ** -7, 2e-3), rel_l2=5e-3)
+    # variant 6, the kernel the block and the benchmark launch at these lengths: queries pre-multiplied by
+    # log2(e) / sqrt(dh) ahead of their rounding; the oracle gets the rounded queries with the factor taken out
+    c = np.float32(np.log2(np.e) / np.sqrt(dh))
+    q6 = synth.round_bf16(synth.normal(7, "fa.q", (L, D), 2.0) * c)
+    Q[:, :L] = dev_bf16(q6).reshape(L, H, dh).transpose(0, 1)
+    ref6 = O.attention(q6[rows].astype(np.float64) / np.float64(c), k.astype(np.float64), v.astype(np.float64), H, dh)
+    print(f"[launch] attention full length H={H} L={L} variant=6", flush=True)
+    Oo = torch.empty(L, D, dtype=torch.bfloat16, device=DEV)
+    B.chorus_attention(Q, K, Vt, Oo, None, L, L, 6)
+    got = host_bf16(Oo)
+    assert np.isfinite(got).all()
+    check(got[rows], ref6, f"attention full length H={H} L={L} v6", max_abs=max(np.abs(ref6).max() * 2 ** -7, 2e-3), rel_l2=5e-3)
 
 
 # the region sweep of the benchmark: the box of every fraction (frames x rows x columns of the 21 x 30 x 52 grid) and

@@ -92,6 +92,12 @@ def test_qk_norm_rope(H, dh, grid):
     B.chorus_qk_norm_rope(dev_bf16(z), 0, dev_f32(gain), out, L, H, dh, None, grid, False)
     ref = O.rmsnorm(z[:, :D], gain).reshape(L, H, dh).transpose(1, 0, 2)
     check(host_bf16(out)[:, :L], ref, "rms only", max_abs=np.abs(ref).max() * 2 ** -8, rel_l2=2.5e-3)
+    # with an output factor (the pre-scaled queries of the long self-attention kernel): the same values times the factor
+    c = float(np.log2(np.e) / np.sqrt(dh))
+    B.chorus_qk_norm_rope(dev_bf16(z), 0, dev_f32(gain), out, L, H, dh, None, grid, False, c)
+    check(host_bf16(out)[:, :L], ref * c, "rms only, scaled", max_abs=np.abs(ref).max() * c * 2 ** -8, rel_l2=2.5e-3)
+    with pytest.raises(P.ChorusError):
+        B.chorus_qk_norm_rope(dev_bf16(z), 0, dev_f32(gain), out, L, H, dh, None, grid, False, 0.0)
 
 
 def _vt_reference(v, Lpad):
@@ -122,7 +128,14 @@ def _attn_case(H, dh, Lq, Lk, variant, col_scale=None, q_std=1.0, seed=0, name="
     """One attention launch against the oracle. Keys are padded to 128 for the default choice and the 128-key
     tile kernel (what the block does: it pads rows to 256), to 64 for the 64-key one."""
     D = H * dh
-    q = synth.round_bf16(synth.normal(seed, "at.q", (Lq, D), q_std))
+    q = synth.normal(seed, "at.q", (Lq, D), q_std)
+    if variant == 6:
+        # the kernel is handed bf16(q * c); the oracle gets those same rounded queries with the factor taken out again
+        c = np.float32(np.log2(np.e) / np.sqrt(dh))
+        q_dev = synth.round_bf16(q * c)
+        q = q_dev.astype(np.float64) / np.float64(c)
+    else:
+        q = q_dev = synth.round_bf16(q)
     k = synth.round_bf16(synth.normal(seed, "at.k", (Lk, D), q_std))
     v = synth.round_bf16(synth.normal(seed, "at.v", (Lk, D)))
     LqPad = (Lq + 255) // 256 * 256
@@ -130,20 +143,21 @@ def _attn_case(H, dh, Lq, Lk, variant, col_scale=None, q_std=1.0, seed=0, name="
     LkPad = (Lk + kpad - 1) // kpad * kpad
     Q = torch.zeros(H, LqPad, dh, dtype=torch.bfloat16, device=DEV)
     K = torch.zeros(H, LkPad, dh, dtype=torch.bfloat16, device=DEV)
-    Q[:, :Lq] = dev_bf16(q).reshape(Lq, H, dh).transpose(0, 1)
+    Q[:, :Lq] = dev_bf16(q_dev).reshape(Lq, H, dh).transpose(0, 1)
     K[:, :Lk] = dev_bf16(k).reshape(Lk, H, dh).transpose(0, 1)
     Vt = torch.from_numpy(synth.to_bf16_bits(_vt_reference(v, LkPad).astype(np.float32)).reshape(D, LkPad).view(np.int16)).to(DEV).view(torch.bfloat16)
     Oo = torch.full((Lq, D), 9.0, dtype=torch.bfloat16, device=DEV)
     cs = None if col_scale is None else dev_f32(col_scale)
     B.chorus_attention(Q, K, Vt, Oo, cs, Lq, Lk, variant)
-    ref = O.attention(q.astype(np.float64), O.tgaa_amplify_keys(k.astype(np.float64), col_scale), v.astype(np.float64), H, dh)
+    ref = O.attention(np.asarray(q, np.float64), O.tgaa_amplify_keys(k.astype(np.float64), col_scale), v.astype(np.float64), H, dh)
     return check(host_bf16(Oo), ref, f"attention {name} H={H} dh={dh} Lq={Lq} Lk={Lk} v{variant}",
                  max_abs=max(np.abs(ref).max() * 2 ** -7, 2e-3), rel_l2=5e-3)
 
 
 # variant 0 is the library's own choice (128-key tiles from 2048 keys on, else 64-key tiles), 3, 4 and 5 force the
-# 64-key, the 128-key and the 128-key 16x16x32-MFMA tile kernel: every shape runs through the kernel the block and the benchmark launch.
-ATTN_VARIANTS = [0, 3, 4, 5]
+# 64-key, the 128-key and the 128-key 16x16x32-MFMA tile kernel, 6 is the latter fed with pre-scaled queries (what
+# the block launches for long self-attention): every shape runs through the kernel the block and the benchmark launch.
+ATTN_VARIANTS = [0, 3, 4, 5, 6]
 
 
 @pytest.mark.parametrize("variant", ATTN_VARIANTS)
@@ -178,17 +192,19 @@ def test_attention_variant_argument_errors():
     Oo = torch.zeros(L, H * dh, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(P.ChorusError):
         B.chorus_attention(Q, K, Vt, Oo, torch.ones(L, device=DEV), L, L, 4)
-    with pytest.raises(P.ChorusError):
-        B.chorus_attention(Q, K, Vt, Oo, torch.ones(L, device=DEV), L, L, 5)
-    for bad in (1, 2, 6, -1):
+    for v in (5, 6):
+        with pytest.raises(P.ChorusError):
+            B.chorus_attention(Q, K, Vt, Oo, torch.ones(L, device=DEV), L, L, v)
+    for bad in (1, 2, 7, -1):
         with pytest.raises(P.ChorusError):
             B.chorus_attention(Q, K, Vt, Oo, None, L, L, bad)
     K64 = torch.zeros(H, 64, dh, dtype=torch.bfloat16, device=DEV)
     Vt64 = torch.zeros(H * dh, 64, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(P.ChorusError):
         B.chorus_attention(Q, K64, Vt64, Oo, None, L, 64, 4)
-    with pytest.raises(P.ChorusError):
-        B.chorus_attention(Q, K64, Vt64, Oo, None, L, 64, 5)
+    for v in (5, 6):
+        with pytest.raises(P.ChorusError):
+            B.chorus_attention(Q, K64, Vt64, Oo, None, L, 64, v)
 
 
 @pytest.mark.parametrize("variant", [0, 3])
