@@ -405,14 +405,15 @@ int32_t chorus_prof_reset(void);
 int32_t chorus_prof_read(int32_t kernel_class, double* total_ms, int32_t* launches);
 
 /* ------------------------------------------------------------------------
- * Measured matrix-pipe ceiling, for benchmarks. Runs a loop of bf16 32x32x16 MFMAs on every
- * CU (two waves per SIMD), `launches` launches after a warm-up of twice as many, and
- * returns the sustained TFLOP/s. The part is power-managed, so the result depends on the
- * operand values and on what accompanies the MFMAs:
+ * Measured matrix-pipe ceiling, for benchmarks. Runs a loop of bf16 16x16x32 MFMAs on every
+ * CU (two waves per SIMD, each result block accumulated by four MFMAs in a row, the order of the
+ * self-attention kernel), `launches` launches after a warm-up of twice as many, and returns the
+ * sustained TFLOP/s. The part is power-managed, so the result depends on the operand values and
+ * on what accompanies the MFMAs:
  *   normal_data  0: every operand element is 1.0;  1: N(0,1) values (a fixed hash)
- *   mix          bit 0: the A operand of every MFMA is read from LDS (1 KB per MFMA, what a
- *                       kernel with 32 result rows per wave needs);
- *                bit 1: one exp2 and three vector instructions per MFMA (the softmax ratio)
+ *   mix          bit 0: the A operand of every pair of MFMAs is read from LDS (1 KB per pair, what
+ *                       a kernel with 32 result rows per wave needs);
+ *                bit 1: one exp2 and one maximum per pair of MFMAs (per logit of the softmax)
  *   ws           dev, chorus_mfma_ceiling_workspace_bytes() bytes (results are discarded)
  * Synchronises the stream. Errors: CHORUS_E_ARG, CHORUS_E_WORKSPACE, CHORUS_E_HIP.
  * ------------------------------------------------------------------------ */

@@ -521,21 +521,19 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
         for (int c = 0; c < NC; ++c) lacc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pf[c][rb], lacc[rb], 0, 0, 0);
     }
     compute_s((j + 1) & 1);
-    // issue order: LDS stores, global prefetch, then LDS operand reads kept ahead of the MFMAs (one read feeds two)
+    // issue order: LDS stores, then LDS operand reads kept ahead of the MFMAs (one read feeds two)
+    constexpr int kAhead = 6;  // more reads in flight cost the registers the schedule needs; fewer expose LDS latency
     __builtin_amdgcn_sched_group_barrier(0x200, K_LD + V_LD, 0);
-#ifndef PP16_AHEAD
-#define PP16_AHEAD 6
-#endif
-    __builtin_amdgcn_sched_group_barrier(0x100, PP16_AHEAD, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
 #pragma unroll
-    for (int i = 0; i < DB * NC + KB * KC - PP16_AHEAD; ++i) {
+    for (int i = 0; i < DB * NC + KB * KC - kAhead; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 2 * PP16_AHEAD + 2 * NC, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * kAhead + 2 * NC, 0);
     __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
-    lds_barrier();  // this wave's LDS stores are done; the global prefetch stays in flight
+    lds_barrier();  // this wave's LDS stores are done
     __builtin_amdgcn_sched_barrier(0);
   }
   if (group == 0) lds_barrier();  // every wave executes the same number of barriers

@@ -1,10 +1,10 @@
 // Measured matrix-pipe ceiling of the part for benchmarks: a loop of nothing but
-// v_mfma_f32_32x32x16_bf16 (two waves per SIMD, every CU), optionally with the two companions
-// the attention kernel cannot avoid -- one 1 KB operand read from LDS per MFMA and one exp2
-// (+ 3 vector ops) per MFMA, the softmax ratio. The sustained rate depends on the operand
-// VALUES: the chip is power-managed, constant operands run at the nominal rate, random ones
-// far below it. The roofline fraction of a kernel is quoted against the published peak; this
-// number says how much of that peak the silicon sustains for a given instruction mix and data.
+// v_mfma_f32_16x16x32_bf16 (two waves per SIMD, every CU; every result block accumulated by four MFMAs
+// in a row), optionally with the two companions the self-attention kernel cannot avoid -- one 1 KB
+// operand read from LDS per two MFMAs and one exp2 + maximum per two MFMAs (per logit). The sustained
+// rate depends on the operand VALUES: the chip is power-managed, constant operands run at the nominal
+// rate, random ones far below it. The roofline fraction of a kernel is quoted against the published
+// peak; this number says how much of that peak the silicon sustains for a given instruction mix and data.
 #include "chorus_ops.h"
 #include "common.h"
 
@@ -12,7 +12,7 @@ namespace chorus {
 namespace {
 
 constexpr int kCeilThreads = 512;
-constexpr int kCeilIters = 2000;  // x 32 MFMAs per wave per launch
+constexpr int kCeilIters = 2000;  // x 64 MFMAs per wave per launch
 
 __device__ inline float hash_normal(unsigned idx) {
   unsigned h = idx * 2654435761u + 0x9E3779B9u;
@@ -24,7 +24,7 @@ __device__ inline float hash_normal(unsigned idx) {
   return sqrtf(-2.0f * __logf(u1)) * __cosf(6.2831853f * u2);
 }
 
-// MIX bit 0: the A operand of every MFMA comes from LDS; bit 1: exp2 + fma + add + max per MFMA
+// MIX bit 0: the A operand of every pair of MFMAs comes from LDS; bit 1: exp2 + max per pair of MFMAs
 template <int MIX>
 __global__ __launch_bounds__(kCeilThreads) void mfma_ceiling_kernel(float* __restrict__ out, int normal_data, int iters) {
   __shared__ __attribute__((aligned(16))) uint16_t lds[8 * kCeilThreads * 8];
@@ -45,30 +45,42 @@ __global__ __launch_bounds__(kCeilThreads) void mfma_ceiling_kernel(float* __res
   float e[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) e[i] = (float)a[i][0];
-  float esum = 0.f;
-  f32x16 c[4] = {};
+  float emax = 0.f;
+  f32x4 c[4][4] = {};
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 4; ++t)  // 4 x 16 MFMAs = the flops of 32 MFMAs of the 32x32x16 shape
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        bf16x8 av = a[ks];
-        if (MIX & 1)
-          av = *reinterpret_cast<const bf16x8*>(lds + ((size_t)ks * kCeilThreads + ((threadIdx.x + 64 * t) & (kCeilThreads - 1))) * 8);
-        c[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, b[t], c[t], 0, 0, 0);
-        if (MIX & 2) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(e[ks], 0.125f, -1.0f));
-          esum += p;
-          e[ks] = fmaxf(e[ks], p) * 0.999f;
+      for (int h = 0; h < 2; ++h) {
+        bf16x8 av[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          av[ks] = a[4 * h + ks];
+          if (MIX & 1)
+            av[ks] = *reinterpret_cast<const bf16x8*>(
+                lds + ((size_t)(4 * h + ks) * kCeilThreads + ((threadIdx.x + 64 * t) & (kCeilThreads - 1))) * 8);
         }
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) {  // four MFMAs in a row into one result block
+            c[t][2 * h + r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[ks], b[(ks + r) & 3], c[t][2 * h + r], 0, 0, 0);
+            if ((MIX & 2) && r == 0) {
+              const float p = __builtin_amdgcn_exp2f(-e[4 * h + ks]);
+              emax = fmaxf(emax, p);
+              e[4 * h + ks] = p;
+            }
+          }
       }
     __builtin_amdgcn_sched_barrier(0);
   }
-  float s = esum;
+  float s = emax;
 #pragma unroll
   for (int t = 0; t < 4; ++t)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) s += c[t][i];
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) s += c[t][j][i];
   out[(size_t)blockIdx.x * kCeilThreads + threadIdx.x] = s;
 }
 
@@ -117,7 +129,7 @@ int32_t chorus_mfma_ceiling(int32_t normal_data, int32_t mix, int32_t launches, 
   CHORUS_HIP(hipEventElapsedTime(&ms, e0, e1));
   hipEventDestroy(e0);
   hipEventDestroy(e1);
-  const double flops = (double)cus * (kCeilThreads / 64) * kCeilIters * 32.0 * (2.0 * 32 * 32 * 16) * launches;
+  const double flops = (double)cus * (kCeilThreads / 64) * kCeilIters * 64.0 * (2.0 * 16 * 16 * 32) * launches;
   *tflops = ms > 0.f ? flops / ((double)ms * 1e9) : 0.0;
   return CHORUS_OK;
 }

@@ -177,10 +177,10 @@ def main():
 
     # ---- what the matrix pipe sustains on this device (power-managed: depends on data and instruction mix)
     for data, dname in ((False, "operands all 1.0"), (True, "operands N(0,1)")):
-        for mix, mname in ((0, "registers only"), (1, "A operand from LDS"), (2, "+ exp2 at the softmax ratio"),
+        for mix, mname in ((0, "registers only"), (1, "A operand from LDS"), (2, "+ exp2 and max per logit"),
                            (3, "A from LDS + exp2")):
             tf = B.chorus_mfma_ceiling(data, mix, 20)
-            print(f"mfma_ceiling bf16 32x32x16, {dname}, {mname:<28s} {tf:8.1f} TFLOP/s  ({tf / 2500.0:.3f} of 2.5 PFLOP/s)",
+            print(f"mfma_ceiling bf16 16x16x32, {dname}, {mname:<28s} {tf:8.1f} TFLOP/s  ({tf / 2500.0:.3f} of 2.5 PFLOP/s)",
                   flush=True)
 
 
