@@ -97,6 +97,10 @@ SHAPES = {
     # reduced grid with the 1.3B widths, for whole-schedule oracle runs
     "wan1p3b_small": BlockShape("wan1p3b_small", D=1536, H=12, dh=128, F=8960, Lt=512, text_dim=4096,
                                 grid=(5, 12, 20), blocks=2, cache_N=64, cache_d=4096),
+    # the 1.3B widths on a grid of 2304 tokens: the smallest whole number of 256-row tiles that reaches the 2048 rows
+    # from which the block runs its long-sequence self-attention kernel; still small enough for the full oracle
+    "wan1p3b_mid": BlockShape("wan1p3b_mid", D=1536, H=12, dh=128, F=8960, Lt=512, text_dim=4096,
+                              grid=(6, 16, 24), blocks=2, cache_N=64, cache_d=4096),
     # Wan2.1-14B-shaped 720p: latent 16x21x90x160
     "wan14b_720p": BlockShape("wan14b_720p", D=5120, H=40, dh=128, F=13824, Lt=512, text_dim=4096,
                               grid=(21, 45, 80), blocks=40, cache_N=4096, cache_d=4096),

@@ -195,6 +195,30 @@ def test_block_branches_one_at_a_time(name, stress):
         assert a <= max(np.abs(ref).max() * 2 ** -5, 2e-3), f"{which}: max-abs {a:.3e}"
 
 
+@pytest.mark.parametrize("stress", [False, True])
+def test_block_long_rows_self_attention_path(stress):
+    """1.3B widths on 2304 tokens, full oracle: from 2048 rows on the block multiplies its queries by log2(e)/sqrt(dh)
+    in the q-norm kernel and runs the 16x16x32-MFMA self-attention kernel on them. The whole block, and the
+    self-attention branch on its own (its gate at 1, the other gates and gamma_o at 0)."""
+    print(f"[case] block 1.3B widths, 2304 rows, stress={stress}", flush=True)
+    bs = synth.SHAPES["wan1p3b_mid"]
+    w0 = synth.stress_block_weights(bs, 9) if stress else synth.block_weights(bs, 9)
+    inp = synth.block_inputs(bs, 9, x_std=1.0)
+    g = synth.tdiff_scale(bs.Lt, 1.5, seed=9, n_diff=16)
+    got = _run_block(bs, w0, inp, key_scale=g, gamma_o=1.5)
+    ref = O.dit_block(inp["x"], w0, bs, inp["text_ctx"], inp["t_mod"], key_scale=g, gamma_o=1.5)
+    _compare(got, inp["x"], ref, f"1.3B-mid full stress={stress}", stress)
+    w, go = _isolated(w0, inp["t_mod"], "y_sa")
+    got = _run_block(bs, w, inp, key_scale=g, gamma_o=go)
+    _, br = O.dit_block(inp["x"], w, bs, inp["text_ctx"], inp["t_mod"], key_scale=g, gamma_o=go, return_branches=True)
+    a, r = errs(got - inp["x"], br["y_sa"])
+    print(f"[parity] 1.3B-mid stress={stress} branch y_sa: max_abs={a:.3e} rel_l2={r:.3e} |branch|max={np.abs(br['y_sa']).max():.3e}",
+          flush=True)
+    assert np.isfinite(got).all()
+    assert r <= BRANCH_REL[stress], f"y_sa: rel-L2 {r:.3e}"
+    assert a <= max(np.abs(br["y_sa"]).max() * 2 ** -5, 2e-3), f"y_sa: max-abs {a:.3e}"
+
+
 def test_block_14b_widths_small_grid():
     """Config-5 widths (D 5120, 40 x 128 heads, F 13824, 512 text tokens) on a 3x8x10 grid with a
     50% box mask and TGAA 1.5: the widest GEMM / norm paths (register-resident LayerNorm at D=5120)."""
