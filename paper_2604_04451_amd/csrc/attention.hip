@@ -1,8 +1,11 @@
 // Flash-style attention for gfx950: O = softmax(g_j * (Q K^T) / sqrt(dh)) V, bf16
-// operands on v_mfma_f32_32x32x16_bf16, fp32 online softmax, logits never leave
-// registers. Used for the block's 3-D self-attention (g = 1) and for the text
-// cross-attention with TGAA key amplification (Eq. 2: scaling key j by gamma_k
-// scales logit column j).
+// operands on the matrix pipe, fp32 online softmax, logits never leave registers.
+// Used for the block's 3-D self-attention (g = 1) and for the text cross-attention
+// with TGAA key amplification (Eq. 2: scaling key j by gamma_k scales logit column j).
+// Two kernels of one design: attention_pp_kernel on v_mfma_f32_32x32x16_bf16 (64- or
+// 128-key tiles, optional column scale: cross-attention and short sequences), described
+// first, and attention_pp16_kernel on v_mfma_f32_16x16x32_bf16 (long self-attention),
+// whose differences are described in front of it.
 //
 // Work split: a workgroup of 8 waves owns 256 query rows of one head (32 per wave, held in
 // registers) and sweeps all keys in tiles of 64 or 128. K tiles [keys][dh] and V^T tiles
