@@ -295,10 +295,11 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
 // the same bf16-rounded probabilities that weight V and the weights of a row add up to exactly one), and the global
 // prefetch of the next tiles is issued at the start of the softmax phase instead of the MFMA phase.
 // ---------------------------------------------------------------------------
-template <int DH, bool PRE>
+template <int DH, bool PRE, int RB>
 __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vt,
-    uint16_t* __restrict__ O, long Lq, long Lk, long LqPad, long LkPad, int H, int n_qtiles, float scale_log2) {
+    uint16_t* __restrict__ O, long Lq, long Lk, long LqPad, long LkPad, int H, int n_qtiles, int tile_base,
+    float scale_log2) {
   constexpr int NT = 512;
   constexpr int KTL = 128;
   constexpr int KS = DH + 16, VS = KTL + 16;  // padded LDS row strides (elements)
@@ -308,26 +309,27 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
   constexpr int DB = DH / 16;                  // 16-row blocks of O^T
   constexpr int K_LD = KTL * (DH / 8) / NT;
   constexpr int V_LD = DH * (KTL / 8) / NT;
-  constexpr int QROWS = 8 * 32;
+  constexpr int QROWS = 8 * 16 * RB;  // RB blocks of 16 query rows per wave
 
   extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
   uint16_t* smk = reinterpret_cast<uint16_t*>(smem_raw);   // [2][KTL][KS]
   uint16_t* smv = smk + 2 * KTL * KS;                      // [2][DH][VS]
 
-  const int tile_id = xcd_remap(blockIdx.x, H * n_qtiles);
+  // this launch covers the tiles tile_base .. tile_base + gridDim.x - 1 of the H * n_qtiles of its tile size
+  const int tile_id = tile_base + xcd_remap(blockIdx.x, gridDim.x);
   const int head = tile_id / n_qtiles;
   const int qt = tile_id - head * n_qtiles;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int group = wave >> 2;
   const int lq = lane & 15, g = lane >> 4;
-  const long q_wave0 = (long)qt * QROWS + wave * 32;
+  const long q_wave0 = (long)qt * QROWS + wave * 16 * RB;
 
   const uint16_t* Kh = K + (long)head * LkPad * DH;
   const uint16_t* Vh = Vt + (long)head * DH * LkPad;
 
-  bf16x8 qf[2][KC];
+  bf16x8 qf[RB][KC];
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
+  for (int rb = 0; rb < RB; ++rb) {
     long q = q_wave0 + 16 * rb + lq;
     if (q > Lq - 1) q = Lq - 1;
     const uint16_t* qp = Q + ((long)head * LqPad + q) * DH + 8 * g;
@@ -335,15 +337,20 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
     for (int kc = 0; kc < KC; ++kc) qf[rb][kc] = *reinterpret_cast<const bf16x8*>(qp + 32 * kc);
   }
 
-  f32x4 o[DB][2];
+  f32x4 o[DB][RB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) o[db][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int rb = 0; rb < RB; ++rb) o[db][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
   // PRE: Q arrives multiplied by log2(e) / sqrt(dh) and the S^T accumulators start at minus the running reference, so
   // a logit leaves the MFMA as the exponent of its probability; the reference starts at 0 and the first tile sets it.
-  float m_run[2] = {PRE ? 0.f : -INFINITY, PRE ? 0.f : -INFINITY};
-  f32x4 lacc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+  float m_run[RB];
+  f32x4 lacc[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    m_run[rb] = PRE ? 0.f : -INFINITY;
+    lacc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
   bf16x8 ones;
 #pragma unroll
   for (int e = 0; e < 8; ++e) ones[e] = (bf16_t)1.0f;
@@ -379,7 +386,7 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
   };
   // LDS row of the K tile that fragment row lane % 16 of block kb stands for
   const int krow0 = 16 * (lq >> 3) + (lq & 7);
-  f32x4 s[KB][2];
+  f32x4 s[KB][RB];
   auto compute_s = [&](int buf) {
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb) {
@@ -389,7 +396,7 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
       for (int kc = 0; kc < KC; ++kc)
         kf[kc] = *reinterpret_cast<const bf16x8*>(&smk[(buf * KTL + row) * KS + 32 * kc + 8 * g]);
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
+      for (int rb = 0; rb < RB; ++rb) {
         const float a0 = PRE ? -m_run[rb] : 0.f;
         f32x4 acc = {a0, a0, a0, a0};
 #pragma unroll
@@ -409,7 +416,7 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
     store_k(1);
   }
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
+  for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int kc = 0; kc < KC; ++kc) asm volatile("" : "+v"(qf[rb][kc]));  // Q fragments resident before the loop
   __syncthreads();
@@ -431,14 +438,14 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
         for (int i = 0; i < 4; ++i) {
           const long key = key0 + 32 * (kb >> 1) + 8 * (kb & 1) + i;
           if (key >= Lk) {
-            s[kb][0][i] = -INFINITY;
-            s[kb][1][i] = -INFINITY;
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) s[kb][rb][i] = -INFINITY;
           }
         }
     }
-    float mxs[2];
+    float mxs[RB];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
+    for (int rb = 0; rb < RB; ++rb) {
       float mx = s[0][rb][0];
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
@@ -450,9 +457,12 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
     }
     if constexpr (PRE) {
       // logits are relative to the reference already: move it when a row exceeds it by more than 8, and on the first tile
-      if (__any(mxs[0] > 8.0f || mxs[1] > 8.0f) || j == 0) {
+      bool move = false;
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
+      for (int rb = 0; rb < RB; ++rb) move = move || mxs[rb] > 8.0f;
+      if (__any(move) || j == 0) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
           const float delta = j == 0 ? mxs[rb] : fmaxf(mxs[rb], 0.f);
           const float alpha = j == 0 ? 1.0f : __builtin_amdgcn_exp2f(-delta);  // nothing is accumulated before the first tile
           m_run[rb] += delta;
@@ -465,9 +475,13 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
             for (int i = 0; i < 4; ++i) s[kb][rb][i] -= delta;
         }
       }
-    } else if (__any(mxs[0] > m_run[0] + 8.0f || mxs[1] > m_run[1] + 8.0f)) {
+    } else {
+      bool move = false;
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
+      for (int rb = 0; rb < RB; ++rb) move = move || mxs[rb] > m_run[rb] + 8.0f;
+      if (__any(move)) {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
         const float m_new = fmaxf(m_run[rb], mxs[rb]);
         const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_new);
         m_run[rb] = m_new;
@@ -475,10 +489,11 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
 #pragma unroll
         for (int db = 0; db < DB; ++db) o[db][rb] *= alpha;
       }
+      }
     }
-    bf16x8 pf[NC][2];
+    bf16x8 pf[NC][RB];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
+    for (int rb = 0; rb < RB; ++rb) {
       const float mref = m_run[rb];
 #pragma unroll
       for (int c = 0; c < NC; ++c)
@@ -496,7 +511,7 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
 #pragma unroll
     for (int c = 0; c < NC; ++c)
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) asm volatile("" : "+v"(pf[c][rb]));
+      for (int rb = 0; rb < RB; ++rb) asm volatile("" : "+v"(pf[c][rb]));
     __builtin_amdgcn_sched_barrier(0);
     lds_barrier();
     __builtin_amdgcn_sched_barrier(0);
@@ -514,12 +529,12 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
         for (int c = 0; c < NC; ++c)
           vf[c] = *reinterpret_cast<const bf16x8*>(&smv[(vb * DH + 16 * db + lq) * VS + 32 * c + 8 * g]);
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
           for (int c = 0; c < NC; ++c) o[db][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[c], pf[c][rb], o[db][rb], 0, 0, 0);
       }
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
+      for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int c = 0; c < NC; ++c) lacc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pf[c][rb], lacc[rb], 0, 0, 0);
     }
@@ -530,10 +545,10 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
     __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
 #pragma unroll
     for (int i = 0; i < DB * NC + KB * KC - kAhead; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, RB, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 2 * kAhead + 2 * NC, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, RB * kAhead + RB * NC, 0);
     __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
     lds_barrier();  // this wave's LDS stores are done
@@ -543,7 +558,7 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
 
   const int D = H * DH;
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
+  for (int rb = 0; rb < RB; ++rb) {
     const float l = lacc[rb][0];
     const float inv = 1.0f / l;
     const long q = q_wave0 + 16 * rb + lq;
@@ -560,20 +575,40 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
   }
 }
 
-template <int DH, bool PRE>
-int32_t launch_attn_pp16(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, long Lq, long Lk, long LqPad,
-                         long LkPad, int H, hipStream_t s) {
-  long nqt = (Lq + 255) / 256;
-  if (nqt * H > 0x7fffffffL) return CHORUS_E_SHAPE;
+// One launch of the 16x16x32 kernel with RB blocks of 16 query rows per wave over the tiles tile_base .. + ntile - 1.
+template <int DH, bool PRE, int RB>
+int32_t launch_attn_pp16_tiles(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, long Lq, long Lk,
+                               long LqPad, long LkPad, int H, long nqt, long tile_base, long ntile, hipStream_t s) {
   size_t smem = 2 * ((size_t)128 * (DH + 16) + (size_t)DH * (128 + 16)) * sizeof(uint16_t);
-  auto kern = attention_pp16_kernel<DH, PRE>;
+  auto kern = attention_pp16_kernel<DH, PRE, RB>;
   static DynLdsOnce once;  // the raised dynamic-LDS limit is a per-device property of the kernel
   CHK_STATUS(once.ensure(reinterpret_cast<const void*>(kern), (int)smem));
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-  hipLaunchKernelGGL(kern, dim3((unsigned)(nqt * H)), dim3(512), smem, s, Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, (int)nqt,
-                     scale_log2);
+  hipLaunchKernelGGL(kern, dim3((unsigned)ntile), dim3(512), smem, s, Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, (int)nqt,
+                     (int)tile_base, scale_log2);
   CHORUS_LAUNCH_CHECK();
   return CHORUS_OK;
+}
+
+// 256 query rows per workgroup. One workgroup fits a CU, so a launch runs in rounds of as many workgroups as the device
+// has CUs. When the last round would be at most half full, its tiles run as workgroups of 128 rows instead (one block
+// of 16 rows per wave: the same K / V stream for half the arithmetic, 0.63-0.67 of a full workgroup's time), twice as
+// many of them, in a second launch behind the first: the partly filled round then takes two thirds of a full one.
+template <int DH, bool PRE>
+int32_t launch_attn_pp16(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, long Lq, long Lk, long LqPad,
+                         long LkPad, int H, hipStream_t s) {
+  const long nqt = (Lq + 255) / 256;
+  const long tiles = nqt * H;
+  if (2 * tiles > 0x7fffffffL) return CHORUS_E_SHAPE;
+  int dev = 0, cus = 0;
+  CHORUS_HIP(hipGetDevice(&dev));
+  CHORUS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  const long tail = cus > 0 ? tiles % cus : 0;
+  if (tiles > cus && tail > 0 && 2 * tail <= cus) {
+    CHK_STATUS((launch_attn_pp16_tiles<DH, PRE, 2>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, nqt, 0, tiles - tail, s)));
+    return launch_attn_pp16_tiles<DH, PRE, 1>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, 2 * nqt, 2 * (tiles - tail), 2 * tail, s);
+  }
+  return launch_attn_pp16_tiles<DH, PRE, 2>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, nqt, 0, tiles, s);
 }
 
 template <int DH, int KTL, bool CS>
