@@ -36,7 +36,7 @@ HBM_PEAK_GBS = 8000.0
 # runs (FETCH_SIZE, then WRITE_SIZE) of this same command gave when the summary named below
 # was written (FETCH_SIZE scaled by 1.992, the factor a plain 8.39 MB copy kernel of the same
 # run shows; WRITE_SIZE by 1.000); it is reported for that exact workload only, with its source.
-SELF_ATTN_TRAFFIC_BYTES_DEFAULT = 7.70e8
+SELF_ATTN_TRAFFIC_BYTES_DEFAULT = 7.75e8
 SELF_ATTN_TRAFFIC_SOURCE = "profiles/bench_wan1p3b_480p_pmc_traffic.txt"
 
 
