@@ -295,7 +295,9 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
 // the same bf16-rounded probabilities that weight V and the weights of a row add up to exactly one), and the global
 // prefetch of the next tiles is issued at the start of the softmax phase instead of the MFMA phase.
 // ---------------------------------------------------------------------------
-template <int DH, bool PRE, int RB>
+// CROSS changes nothing in the code: it gives launches with a key sequence other than the query sequence (the text
+// cross-attention) a kernel name of their own, so that a kernel profile lists self- and cross-attention separately.
+template <int DH, bool PRE, int RB, bool CROSS>
 __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vt,
     uint16_t* __restrict__ O, long Lq, long Lk, long LqPad, long LkPad, int H, int n_qtiles, int tile_base,
@@ -576,11 +578,11 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
 }
 
 // One launch of the 16x16x32 kernel with RB blocks of 16 query rows per wave over the tiles tile_base .. + ntile - 1.
-template <int DH, bool PRE, int RB>
+template <int DH, bool PRE, int RB, bool CROSS>
 int32_t launch_attn_pp16_tiles(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, long Lq, long Lk,
                                long LqPad, long LkPad, int H, long nqt, long tile_base, long ntile, hipStream_t s) {
   size_t smem = 2 * ((size_t)128 * (DH + 16) + (size_t)DH * (128 + 16)) * sizeof(uint16_t);
-  auto kern = attention_pp16_kernel<DH, PRE, RB>;
+  auto kern = attention_pp16_kernel<DH, PRE, RB, CROSS>;
   static DynLdsOnce once;  // the raised dynamic-LDS limit is a per-device property of the kernel
   CHK_STATUS(once.ensure(reinterpret_cast<const void*>(kern), (int)smem));
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
@@ -594,8 +596,8 @@ int32_t launch_attn_pp16_tiles(const uint16_t* Q, const uint16_t* K, const uint1
 // has CUs. When the last round would be at most half full, its tiles run as workgroups of 128 rows instead (one block
 // of 16 rows per wave: the same K / V stream for half the arithmetic, 0.63-0.67 of a full workgroup's time), twice as
 // many of them, in a second launch behind the first: the partly filled round then takes two thirds of a full one.
-template <int DH, bool PRE>
-int32_t launch_attn_pp16(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, long Lq, long Lk, long LqPad,
+template <int DH, bool PRE, bool CROSS>
+int32_t launch_attn_pp16_kind(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, long Lq, long Lk, long LqPad,
                          long LkPad, int H, hipStream_t s) {
   const long nqt = (Lq + 255) / 256;
   const long tiles = nqt * H;
@@ -605,10 +607,17 @@ int32_t launch_attn_pp16(const uint16_t* Q, const uint16_t* K, const uint16_t* V
   CHORUS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
   const long tail = cus > 0 ? tiles % cus : 0;
   if (tiles > cus && tail > 0 && 2 * tail <= cus) {
-    CHK_STATUS((launch_attn_pp16_tiles<DH, PRE, 2>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, nqt, 0, tiles - tail, s)));
-    return launch_attn_pp16_tiles<DH, PRE, 1>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, 2 * nqt, 2 * (tiles - tail), 2 * tail, s);
+    CHK_STATUS((launch_attn_pp16_tiles<DH, PRE, 2, CROSS>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, nqt, 0, tiles - tail, s)));
+    return launch_attn_pp16_tiles<DH, PRE, 1, CROSS>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, 2 * nqt, 2 * (tiles - tail), 2 * tail, s);
   }
-  return launch_attn_pp16_tiles<DH, PRE, 2>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, nqt, 0, tiles, s);
+  return launch_attn_pp16_tiles<DH, PRE, 2, CROSS>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, nqt, 0, tiles, s);
+}
+
+template <int DH, bool PRE>
+int32_t launch_attn_pp16(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, long Lq, long Lk, long LqPad,
+                         long LkPad, int H, hipStream_t s) {
+  return Lq == Lk ? launch_attn_pp16_kind<DH, PRE, false>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s)
+                  : launch_attn_pp16_kind<DH, PRE, true>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s);
 }
 
 template <int DH, int KTL, bool CS>
@@ -648,7 +657,7 @@ extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const 
   const bool cs = col_scale != nullptr;
   // 128-key tiles when the padding allows and no column scale is needed (with it that tile size would spill
   // registers, so it is not built)
-  if (variant == 0) variant = (!cs && LkPad % 128 == 0 && Lk >= 2048) ? 5 : 3;
+  if (variant == 0) variant = (!cs && CHORUS_ATTENTION_LONG_KEYS(Lk, LkPad)) ? 5 : 3;
   if (variant == 5 || variant == 6) {
     if (cs || LkPad % 128) return CHORUS_E_SHAPE;
     if (variant == 6)

@@ -203,9 +203,10 @@ int32_t block_step_impl(const chorus_block_shape* shape, const chorus_block_weig
     CHK(chorus_gemm_bf16(b.h, w->w_qkv, Ls, 3 * D, D, CHORUS_EPI_BF16, b.qkv, w->b_qkv, nullptr, nullptr, 1.f, stream));
   }
   // 2-3. q/k RMSNorm + RoPE into head-major layout; V into key-contiguous layout.
-  // Long self-attention runs the kernel that takes its queries already multiplied by log2(e) / sqrt(dh): the factor
-  // enters here, in fp32 ahead of the one rounding to bf16 (the same condition as chorus_attention's default choice).
-  const bool q_prescaled = Lpad % 128 == 0 && Ls >= 2048;
+  // Attention over 512 keys or more without a column scale runs the kernel that takes its queries already multiplied by
+  // log2(e) / sqrt(dh): the factor enters here, in fp32 ahead of the one rounding to bf16 (the same condition as
+  // chorus_attention's default choice).
+  const bool q_prescaled = CHORUS_ATTENTION_LONG_KEYS(Ls, Lpad);
   {
     ProfScope p(CHORUS_PROF_NORM, s);
     CHK(chorus_qk_norm_rope(b.qkv, 3L * D, w->g_q, b.qh, Ls, Lpad, H, dh, token_idx, sh.gT, sh.gH, sh.gW, 1,
@@ -239,13 +240,16 @@ int32_t block_step_impl(const chorus_block_shape* shape, const chorus_block_weig
   } else {
     CHK(project_text_kv(sh, w, text_ctx, b.tkv, b.kc, b.vct, stream));
   }
+  // cross-attention without a TGAA factor (the stage-3 steps) over 512 text tokens or more: pre-scaled queries as above
+  const bool cq_prescaled = tgaa_key_scale == nullptr && CHORUS_ATTENTION_LONG_KEYS(Lt, LtPad);
   {
     ProfScope p(CHORUS_PROF_NORM, s);
-    CHK(chorus_qk_norm_rope(b.qkv, D, w->g_cq, b.qh, Ls, Lpad, H, dh, nullptr, sh.gT, sh.gH, sh.gW, 0, 1.0f, stream));
+    CHK(chorus_qk_norm_rope(b.qkv, D, w->g_cq, b.qh, Ls, Lpad, H, dh, nullptr, sh.gT, sh.gH, sh.gW, 0,
+                            cq_prescaled ? CHORUS_ATTENTION_Q_PRESCALE(dh) : 1.0f, stream));
   }
   {
     ProfScope p(CHORUS_PROF_CROSS_ATTN, s);
-    CHK(chorus_attention(b.qh, kc, vct, b.ao, tgaa_key_scale, Ls, Lt, Lpad, LtPad, H, dh, 0, stream));
+    CHK(chorus_attention(b.qh, kc, vct, b.ao, tgaa_key_scale, Ls, Lt, Lpad, LtPad, H, dh, cq_prescaled ? 6 : 0, stream));
   }
   {
     ProfScope p(CHORUS_PROF_GEMM, s);

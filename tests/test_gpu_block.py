@@ -197,7 +197,7 @@ def test_block_branches_one_at_a_time(name, stress):
 
 @pytest.mark.parametrize("stress", [False, True])
 def test_block_long_rows_self_attention_path(stress):
-    """1.3B widths on 2304 tokens, full oracle: from 2048 rows on the block multiplies its queries by log2(e)/sqrt(dh)
+    """1.3B widths on 2304 tokens, full oracle: from 512 rows on the block multiplies its queries by log2(e)/sqrt(dh)
     in the q-norm kernel and runs the 16x16x32-MFMA self-attention kernel on them. The whole block, and the
     self-attention branch on its own (its gate at 1, the other gates and gamma_o at 0)."""
     print(f"[case] block 1.3B widths, 2304 rows, stress={stress}", flush=True)

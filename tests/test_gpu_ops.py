@@ -154,7 +154,7 @@ def _attn_case(H, dh, Lq, Lk, variant, col_scale=None, q_std=1.0, seed=0, name="
                  max_abs=max(np.abs(ref).max() * 2 ** -7, 2e-3), rel_l2=5e-3)
 
 
-# variant 0 is the library's own choice (128-key tiles from 2048 keys on, else 64-key tiles), 3, 4 and 5 force the
+# variant 0 is the library's own choice (128-key tiles from 512 keys on, else 64-key tiles), 3, 4 and 5 force the
 # 64-key, the 128-key and the 128-key 16x16x32-MFMA tile kernel, 6 is the latter fed with pre-scaled queries (what
 # the block launches for long self-attention): every shape runs through the kernel the block and the benchmark launch.
 ATTN_VARIANTS = [0, 3, 4, 5, 6]
@@ -174,7 +174,7 @@ def test_attention_plain(H, dh, Lq, Lk, variant):
 def test_attention_peaked(variant):
     """Logits with std ~4: rows dominated by few keys; catches masking / rescale mistakes that
     near-uniform rows (output ~ mean V) would hide. Key counts with tails of 4, 16, 1 and 81 keys in the
-    last 128-key tile, above and below the 2048 keys where the default switches tile size."""
+    last 128-key tile, above and below 512 and 2048 keys (the default switches tile size at 512)."""
     print(f"[case] attention peaked variant={variant}", flush=True)
     _attn_case(4, 128, 700, 900, variant, q_std=2.0, seed=3, name="peaked")
     _attn_case(2, 64, 333, 2000, variant, q_std=2.0, seed=4, name="peaked64")
