@@ -681,12 +681,14 @@ extern "C" int32_t chorus_gemm_bf16_kernel(const uint16_t* A, const uint16_t* W,
   if (kernel == 2) return launch_gemm<256, 128, 128, 64>(A, W, (long)M, N, K, epilogue, ep, s);
   if (kernel == 3) return launch_gemm_w16(A, W, (long)M, N, K, epilogue, ep, s);
   // Automatic choice: the estimated time of each tile shape, in microseconds, from fits to measurements on this chip
-  // at K = 1536 and K = 8960 (a constant for prologue and epilogue plus a cost per element of K). The two large tiles
+  // at K = 1536 and K = 8960, M from 512 to 32760 and N = 1536, 4608 and 8960 (a constant for prologue and epilogue
+  // plus a cost per element of K, both for a full round: a round that fills few units runs faster than this, and
+  // there the small tile is chosen anyway). The two large tiles
   // run one workgroup per compute unit, so they go in rounds of 256 workgroups; the small tile keeps several
   // workgroups per unit in flight, so its time grows with the tile count past the first 256.
   const double k = (double)K;
-  const double t256 = (double)((((M + 255) / 256) * ((N + 255) / 256) + 255) / 256) * (16.0 + 0.0233 * k);
-  const double t128 = (double)((((M + 255) / 256) * ((N + 127) / 128) + 255) / 256) * (5.0 + 0.0173 * k);
+  const double t256 = (double)((((M + 255) / 256) * ((N + 255) / 256) + 255) / 256) * (2.0 + 0.0265 * k);
+  const double t128 = (double)((((M + 255) / 256) * ((N + 127) / 128) + 255) / 256) * (9.0 + 0.0177 * k);
   const long small_tiles = ((M + 127) / 128) * ((N + 63) / 64);
   const double t64 = (5.6 + 0.0084 * k) + (small_tiles > 256 ? (double)(small_tiles - 256) / 256.0 * (0.8 + 0.0057 * k) : 0.0);
   if (t256 <= t128 && t256 <= t64) return launch_gemm_w16(A, W, (long)M, N, K, epilogue, ep, s);
