@@ -19,9 +19,11 @@ constexpr int BK = 64;
 constexpr int LS = BK + 8;  // LDS row stride in elements
 
 __device__ __forceinline__ float gelu_tanh_fast(float x) {
-  // 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u)),  u = sqrt(2/pi) (x + 0.044715 x^3)
-  float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-  float e = __builtin_amdgcn_exp2f(-2.0f * 1.4426950408889634f * u);
+  // 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u)),  u = sqrt(2/pi) (x + 0.044715 x^3); the exponent is taken in base 2:
+  // -2u log2(e) = -x (2.3022082 + 0.10294324 x^2)
+  const float t = x * x;
+  const float p = __builtin_fmaf(t, -0.10294324f, -2.3022082f);
+  const float e = __builtin_amdgcn_exp2f(p * x);
   return x * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
