@@ -689,13 +689,38 @@ extern "C" int32_t chorus_gemm_bf16_kernel(const uint16_t* A, const uint16_t* W,
   // run one workgroup per compute unit, so they go in rounds of 256 workgroups; the small tile keeps several
   // workgroups per unit in flight, so its time grows with the tile count past the first 256.
   const double k = (double)K;
-  const double t256 = (double)((((M + 255) / 256) * ((N + 255) / 256) + 255) / 256) * (2.0 + 0.0265 * k);
-  const double t128 = (double)((((M + 255) / 256) * ((N + 127) / 128) + 255) / 256) * (9.0 + 0.0177 * k);
-  const long small_tiles = ((M + 127) / 128) * ((N + 63) / 64);
-  const double t64 = (5.6 + 0.0084 * k) + (small_tiles > 256 ? (double)(small_tiles - 256) / 256.0 * (0.8 + 0.0057 * k) : 0.0);
-  if (t256 <= t128 && t256 <= t64) return launch_gemm_w16(A, W, (long)M, N, K, epilogue, ep, s);
-  if (t128 <= t64) return launch_gemm<256, 128, 128, 64>(A, W, (long)M, N, K, epilogue, ep, s);
-  return launch_gemm<128, 64, 64, 32>(A, W, (long)M, N, K, epilogue, ep, s);
+  const long tiles_n256 = (N + 255) / 256;
+  auto t256 = [&](long m) { return (double)((((m + 255) / 256) * tiles_n256 + 255) / 256) * (2.0 + 0.0265 * k); };
+  auto t128 = [&](long m) { return (double)((((m + 255) / 256) * ((N + 127) / 128) + 255) / 256) * (9.0 + 0.0177 * k); };
+  auto t64 = [&](long m) {
+    const long small_tiles = ((m + 127) / 128) * ((N + 63) / 64);
+    return (5.6 + 0.0084 * k) + (small_tiles > 256 ? (double)(small_tiles - 256) / 256.0 * (0.8 + 0.0057 * k) : 0.0);
+  };
+  auto launch_best = [&](const uint16_t* a, long m, const EpiArgs& e) {
+    const double a256 = t256(m), a128 = t128(m), a64 = t64(m);
+    if (a256 <= a128 && a256 <= a64) return launch_gemm_w16(a, W, m, N, K, epilogue, e, s);
+    if (a128 <= a64) return launch_gemm<256, 128, 128, 64>(a, W, m, N, K, epilogue, e, s);
+    return launch_gemm<128, 64, 64, 32>(a, W, m, N, K, epilogue, e, s);
+  };
+  // A last round of 256 x 256 tiles that fills a small part of the chip costs a whole round. The rows can be cut
+  // instead: the row tiles that make up whole rounds go to the 256 x 256 kernel, the rows left over to whichever
+  // kernel suits that many rows, in a second launch behind the first. Taken when the estimate is better by 5 %.
+  const long tiles256 = ((M + 255) / 256) * tiles_n256;
+  const long head_rows = tiles256 > 256 ? (tiles256 / 256 * 256 / tiles_n256) * 256 : 0;
+  if (head_rows > 0 && head_rows < M) {
+    const long rest = (long)M - head_rows;
+    const double t_rest = fmin(t256(rest), fmin(t128(rest), t64(rest)));
+    const double t_whole = fmin(t256((long)M), fmin(t128((long)M), t64((long)M)));
+    if (t256(head_rows) + t_rest < 0.95 * t_whole) {
+      const int32_t rc = launch_gemm_w16(A, W, head_rows, N, K, epilogue, ep, s);
+      if (rc != CHORUS_OK) return rc;
+      const size_t out_elt = (epilogue == CHORUS_EPI_F32 || epilogue == CHORUS_EPI_RESID) ? 4 : 2;
+      EpiArgs ep_rest = ep;
+      ep_rest.out = static_cast<uint8_t*>(out) + (size_t)head_rows * (size_t)N * out_elt;
+      return launch_best(A + (size_t)head_rows * (size_t)K, rest, ep_rest);
+    }
+  }
+  return launch_best(A, (long)M, ep);
 }
 
 extern "C" int32_t chorus_gemm_bf16(const uint16_t* A, const uint16_t* W, int64_t M, int32_t N, int32_t K,

@@ -18,11 +18,13 @@ pytestmark = pytest.mark.gpu
 # --------------------------------------------------------------------- GEMM
 
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (100, 768, 256), (257, 1536, 1536), (1000, 64, 1536),
-                                   (4099, 4608, 1536), (3000, 1536, 8960), (513, 1024, 64), (70, 8, 128)])
+                                   (4099, 4608, 1536), (3000, 1536, 8960), (513, 1024, 64), (70, 8, 128),
+                                   (4452, 4096, 512)])
 def test_gemm_epilogues(M, N, K):
     """Every tile kernel (1: 128 x 64, 2: 256 x 128, 3: 256 x 256 direct to LDS) and the automatic choice (0), each on
     every shape: tiles with ragged rows and columns, a single row, fewer columns than a tile has, K of one and of
-    many steps; the four epilogues."""
+    many steps; the four epilogues. At 4452 x 4096 x 512 the automatic choice cuts the rows: 4096 of them (one whole
+    round of 256 x 256 tiles) in one launch, the other 356 on the 128 x 64 kernel in a second."""
     A = synth.round_bf16(synth.normal(M, "g.A", (M, K)))
     W = synth.round_bf16(synth.normal(M, "g.W", (N, K), 0.05))
     bias = synth.normal(M, "g.b", (N,), 0.5)
