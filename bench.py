@@ -226,7 +226,7 @@ def main():
                      # Q, K, V read once and O written once per launch, averaged over the request's launches
                      # (one per block at the stage-2 token count, two per block at the full count)
                      "algorithmic_bytes": (4 * 2.0 * Ls * D + 2 * 4 * 2.0 * L * D) / 3.0,
-                     "kernel": "attention_pp16_kernel<128,true,2,false> (self-attention; at 13104 tokens its last, partly filled round runs as attention_pp16_kernel<128,true,1,false>)", "launches": attn_n},
+                     "kernel": "attention_pp16_kernel<128,true,2,0> (self-attention; at 13104 tokens its last, partly filled round runs as attention_pp16_kernel<128,true,1,0>)", "launches": attn_n},
     }
     # what a bare MFMA loop sustains on this device right now (the part is power-managed: the rate depends on the
     # operand values and on the LDS reads and exponentials that accompany the MFMAs); context for roofline.frac

@@ -218,8 +218,8 @@ int32_t chorus_denoise_schedule_stored(float m, float tau, int32_t N, const chor
  *              NULL = identity
  *   text_ctx   dev [Lt, D] bf16, already projected to D
  *   t_mod      dev [6, D] fp32 projected timestep embedding
- *   tgaa_key_scale dev [Lt] fp32 (gamma_k on the differential tokens, 1 elsewhere);
- *              NULL = all 1
+ *   tgaa_key_scale dev [Lt] fp32, 16-byte aligned (gamma_k on the differential tokens,
+ *              1 elsewhere); NULL = all 1
  *   gamma_o    output amplification; 1 = neutral
  * Supported: dh in {64, 128}, H*dh == D, D % 64 == 0, F % 64 == 0, Lt >= 1.
  * Ls == 0 is a no-op.

@@ -295,13 +295,16 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
 // the same bf16-rounded probabilities that weight V and the weights of a row add up to exactly one), and the global
 // prefetch of the next tiles is issued at the start of the softmax phase instead of the MFMA phase.
 // ---------------------------------------------------------------------------
-// CROSS changes nothing in the code: it gives launches with a key sequence other than the query sequence (the text
+// KIND 0 and 1 are the same code: 1 gives launches with a key sequence other than the query sequence (the text
 // cross-attention) a kernel name of their own, so that a kernel profile lists self- and cross-attention separately.
-template <int DH, bool PRE, int RB, bool CROSS>
+// KIND 2 multiplies the logit of key j by col_scale[j] (TGAA's key amplification, Eq. 2, applied to the logit): the
+// S^T accumulators then start at zero and one multiply-add per logit applies the factor and, with PRE, the reference.
+template <int DH, bool PRE, int RB, int KIND>
 __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vt,
-    uint16_t* __restrict__ O, long Lq, long Lk, long LqPad, long LkPad, int H, int n_qtiles, int tile_base,
-    float scale_log2) {
+    uint16_t* __restrict__ O, const float* __restrict__ col_scale, long Lq, long Lk, long LqPad, long LkPad, int H,
+    int n_qtiles, int tile_base, float scale_log2) {
+  constexpr bool CS = KIND == 2;
   constexpr int NT = 512;
   constexpr int KTL = 128;
   constexpr int KS = DH + 16, VS = KTL + 16;  // padded LDS row strides (elements)
@@ -399,7 +402,7 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
         kf[kc] = *reinterpret_cast<const bf16x8*>(&smk[(buf * KTL + row) * KS + 32 * kc + 8 * g]);
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
-        const float a0 = PRE ? -m_run[rb] : 0.f;
+        const float a0 = (PRE && !CS) ? -m_run[rb] : 0.f;
         f32x4 acc = {a0, a0, a0, a0};
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kc], qf[rb][kc], acc, 0, 0, 0);
@@ -429,6 +432,28 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
   for (int j = 0; j < ntiles; ++j) {
     // ================= VALU phase: softmax of tile j =================
     __builtin_amdgcn_sched_barrier(0);
+    if constexpr (CS) {
+      // the column factors of this tile are fetched and applied before the prefetch is issued: loads return in order,
+      // and the 32 registers they take are free again when the prefetch needs its own
+      const long key0 = (long)j * KTL + 16 * (g >> 1) + 4 * (g & 1);
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) {
+        const long key = key0 + 32 * (kb >> 1) + 8 * (kb & 1);
+        f32x4 cf;
+        if (key + 3 < Lk) {
+          cf = *reinterpret_cast<const f32x4*>(col_scale + key);
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) cf[i] = key + i < Lk ? col_scale[key + i] : 1.0f;
+        }
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            s[kb][rb][i] = PRE ? __builtin_fmaf(s[kb][rb][i], cf[i], -m_run[rb]) : s[kb][rb][i] * cf[i];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
     // the global prefetch of the tiles that the next MFMA phase stores: K(j+2), V(j+1) (past the end the last tile again)
     load_k(j + 2 < ntiles ? j + 2 : ntiles - 1);
     load_v(j + 1 < ntiles ? j + 1 : ntiles - 1);
@@ -578,16 +603,17 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
 }
 
 // One launch of the 16x16x32 kernel with RB blocks of 16 query rows per wave over the tiles tile_base .. + ntile - 1.
-template <int DH, bool PRE, int RB, bool CROSS>
-int32_t launch_attn_pp16_tiles(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, long Lq, long Lk,
-                               long LqPad, long LkPad, int H, long nqt, long tile_base, long ntile, hipStream_t s) {
+template <int DH, bool PRE, int RB, int KIND>
+int32_t launch_attn_pp16_tiles(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, const float* cs,
+                               long Lq, long Lk, long LqPad, long LkPad, int H, long nqt, long tile_base, long ntile,
+                               hipStream_t s) {
   size_t smem = 2 * ((size_t)128 * (DH + 16) + (size_t)DH * (128 + 16)) * sizeof(uint16_t);
-  auto kern = attention_pp16_kernel<DH, PRE, RB, CROSS>;
+  auto kern = attention_pp16_kernel<DH, PRE, RB, KIND>;
   static DynLdsOnce once;  // the raised dynamic-LDS limit is a per-device property of the kernel
   CHK_STATUS(once.ensure(reinterpret_cast<const void*>(kern), (int)smem));
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-  hipLaunchKernelGGL(kern, dim3((unsigned)ntile), dim3(512), smem, s, Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, (int)nqt,
-                     (int)tile_base, scale_log2);
+  hipLaunchKernelGGL(kern, dim3((unsigned)ntile), dim3(512), smem, s, Q, K, Vt, O, cs, Lq, Lk, LqPad, LkPad, H,
+                     (int)nqt, (int)tile_base, scale_log2);
   CHORUS_LAUNCH_CHECK();
   return CHORUS_OK;
 }
@@ -596,9 +622,9 @@ int32_t launch_attn_pp16_tiles(const uint16_t* Q, const uint16_t* K, const uint1
 // has CUs. When the last round would be at most half full, its tiles run as workgroups of 128 rows instead (one block
 // of 16 rows per wave: the same K / V stream for half the arithmetic, 0.63-0.67 of a full workgroup's time), twice as
 // many of them, in a second launch behind the first: the partly filled round then takes two thirds of a full one.
-template <int DH, bool PRE, bool CROSS>
-int32_t launch_attn_pp16_kind(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, long Lq, long Lk, long LqPad,
-                         long LkPad, int H, hipStream_t s) {
+template <int DH, bool PRE, int KIND>
+int32_t launch_attn_pp16_kind(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, const float* cs, long Lq,
+                              long Lk, long LqPad, long LkPad, int H, hipStream_t s) {
   const long nqt = (Lq + 255) / 256;
   const long tiles = nqt * H;
   if (2 * tiles > 0x7fffffffL) return CHORUS_E_SHAPE;
@@ -607,17 +633,19 @@ int32_t launch_attn_pp16_kind(const uint16_t* Q, const uint16_t* K, const uint16
   CHORUS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
   const long tail = cus > 0 ? tiles % cus : 0;
   if (tiles > cus && tail > 0 && 2 * tail <= cus) {
-    CHK_STATUS((launch_attn_pp16_tiles<DH, PRE, 2, CROSS>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, nqt, 0, tiles - tail, s)));
-    return launch_attn_pp16_tiles<DH, PRE, 1, CROSS>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, 2 * nqt, 2 * (tiles - tail), 2 * tail, s);
+    CHK_STATUS((launch_attn_pp16_tiles<DH, PRE, 2, KIND>(Q, K, Vt, O, cs, Lq, Lk, LqPad, LkPad, H, nqt, 0, tiles - tail, s)));
+    return launch_attn_pp16_tiles<DH, PRE, 1, KIND>(Q, K, Vt, O, cs, Lq, Lk, LqPad, LkPad, H, 2 * nqt, 2 * (tiles - tail),
+                                                    2 * tail, s);
   }
-  return launch_attn_pp16_tiles<DH, PRE, 2, CROSS>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, nqt, 0, tiles, s);
+  return launch_attn_pp16_tiles<DH, PRE, 2, KIND>(Q, K, Vt, O, cs, Lq, Lk, LqPad, LkPad, H, nqt, 0, tiles, s);
 }
 
 template <int DH, bool PRE>
-int32_t launch_attn_pp16(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, long Lq, long Lk, long LqPad,
-                         long LkPad, int H, hipStream_t s) {
-  return Lq == Lk ? launch_attn_pp16_kind<DH, PRE, false>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s)
-                  : launch_attn_pp16_kind<DH, PRE, true>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s);
+int32_t launch_attn_pp16(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, const float* cs, long Lq,
+                         long Lk, long LqPad, long LkPad, int H, hipStream_t s) {
+  if (cs) return launch_attn_pp16_kind<DH, PRE, 2>(Q, K, Vt, O, cs, Lq, Lk, LqPad, LkPad, H, s);
+  return Lq == Lk ? launch_attn_pp16_kind<DH, PRE, 0>(Q, K, Vt, O, cs, Lq, Lk, LqPad, LkPad, H, s)
+                  : launch_attn_pp16_kind<DH, PRE, 1>(Q, K, Vt, O, cs, Lq, Lk, LqPad, LkPad, H, s);
 }
 
 template <int DH, int KTL, bool CS>
@@ -642,7 +670,7 @@ int32_t launch_attn_pp(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt,
 using namespace chorus;
 
 // variant: 0 = default choice; 3 = 64-key tiles; 4 = 128-key tiles (no column scale, LkPad % 128 == 0);
-// 5 = 128-key tiles on 16x16x32 MFMAs (same conditions)
+// 5 = 128-key tiles on 16x16x32 MFMAs (LkPad % 128 == 0); 6 = the same on pre-scaled queries
 extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O,
                                     const float* col_scale, int64_t Lq, int64_t Lk, int64_t LqPad, int64_t LkPad,
                                     int32_t H, int32_t dh, int32_t variant, void* stream) {
@@ -652,19 +680,18 @@ extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const 
   if (Lk < 1) return CHORUS_E_SHAPE;
   if (!Q || !K || !Vt || !O) return CHORUS_E_ARG;
   if ((dh != 64 && dh != 128) || LkPad % KT || LkPad < Lk || LqPad < Lq) return CHORUS_E_SHAPE;
-  if (!aligned16(Q) || !aligned16(K) || !aligned16(Vt) || !aligned16(O)) return CHORUS_E_ARG;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(Vt) || !aligned16(O) || !aligned16(col_scale)) return CHORUS_E_ARG;
   hipStream_t s = (hipStream_t)stream;
   const bool cs = col_scale != nullptr;
-  // 128-key tiles when the padding allows and no column scale is needed (with it that tile size would spill
-  // registers, so it is not built)
-  if (variant == 0) variant = (!cs && CHORUS_ATTENTION_LONG_KEYS(Lk, LkPad)) ? 5 : 3;
+  // 128-key tiles on the 16x16x32 kernel when the keys are long enough and the padding allows
+  if (variant == 0) variant = CHORUS_ATTENTION_LONG_KEYS(Lk, LkPad) ? 5 : 3;
   if (variant == 5 || variant == 6) {
-    if (cs || LkPad % 128) return CHORUS_E_SHAPE;
+    if (LkPad % 128) return CHORUS_E_SHAPE;
     if (variant == 6)
-      return dh == 128 ? launch_attn_pp16<128, true>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s)
-                       : launch_attn_pp16<64, true>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s);
-    return dh == 128 ? launch_attn_pp16<128, false>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s)
-                     : launch_attn_pp16<64, false>(Q, K, Vt, O, Lq, Lk, LqPad, LkPad, H, s);
+      return dh == 128 ? launch_attn_pp16<128, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
+                       : launch_attn_pp16<64, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
+    return dh == 128 ? launch_attn_pp16<128, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
+                     : launch_attn_pp16<64, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
   }
   if (variant == 4) {
     if (cs || LkPad % 128) return CHORUS_E_SHAPE;

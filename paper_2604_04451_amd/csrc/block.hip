@@ -184,7 +184,9 @@ int32_t block_step_impl(const chorus_block_shape* shape, const chorus_block_weig
   const chorus_block_shape& sh = *shape;
   if (Ls > (int64_t)sh.gT * sh.gH * sh.gW && token_idx == nullptr) return CHORUS_E_SHAPE;
   if (!ws) return CHORUS_E_WORKSPACE;
-  if (!aligned16(ws) || !aligned16(x) || !aligned16(text_ctx) || !aligned16(text_kv) || !aligned16(t_mod)) return CHORUS_E_ARG;
+  if (!aligned16(ws) || !aligned16(x) || !aligned16(text_ctx) || !aligned16(text_kv) || !aligned16(t_mod) ||
+      !aligned16(tgaa_key_scale))
+    return CHORUS_E_ARG;
   BlockWs b = carve(sh, Ls, ws);
   if (ws_bytes < b.bytes) return CHORUS_E_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
@@ -240,8 +242,8 @@ int32_t block_step_impl(const chorus_block_shape* shape, const chorus_block_weig
   } else {
     CHK(project_text_kv(sh, w, text_ctx, b.tkv, b.kc, b.vct, stream));
   }
-  // cross-attention without a TGAA factor (the stage-3 steps) over 512 text tokens or more: pre-scaled queries as above
-  const bool cq_prescaled = tgaa_key_scale == nullptr && CHORUS_ATTENTION_LONG_KEYS(Lt, LtPad);
+  // cross-attention over 512 text tokens or more: pre-scaled queries as above, with or without a TGAA factor
+  const bool cq_prescaled = CHORUS_ATTENTION_LONG_KEYS(Lt, LtPad);
   {
     ProfScope p(CHORUS_PROF_NORM, s);
     CHK(chorus_qk_norm_rope(b.qkv, D, w->g_cq, b.qh, Ls, Lpad, H, dh, nullptr, sh.gT, sh.gH, sh.gW, 0,

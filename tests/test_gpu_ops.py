@@ -186,7 +186,8 @@ def test_attention_peaked(variant):
 
 
 def test_attention_variant_argument_errors():
-    """The 128-key tile kernel is not built with a column scale; unknown variants are refused."""
+    """The 128-key tile kernel on 32x32x16 MFMAs is not built with a column scale; unknown variants, a column scale off
+    a 16-byte boundary and 64-key padding with a 128-key kernel are refused."""
     H, dh, L = 1, 128, 128
     Q = torch.zeros(H, 256, dh, dtype=torch.bfloat16, device=DEV)
     K = torch.zeros(H, 128, dh, dtype=torch.bfloat16, device=DEV)
@@ -194,9 +195,10 @@ def test_attention_variant_argument_errors():
     Oo = torch.zeros(L, H * dh, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(P.ChorusError):
         B.chorus_attention(Q, K, Vt, Oo, torch.ones(L, device=DEV), L, L, 4)
-    for v in (5, 6):
+    unaligned = torch.ones(L + 4, device=DEV)[1:L + 1]  # a column scale must sit on a 16-byte boundary
+    for v in (0, 3, 5, 6):
         with pytest.raises(P.ChorusError):
-            B.chorus_attention(Q, K, Vt, Oo, torch.ones(L, device=DEV), L, L, v)
+            B.chorus_attention(Q, K, Vt, Oo, unaligned, L, L, v)
     for bad in (1, 2, 7, -1):
         with pytest.raises(P.ChorusError):
             B.chorus_attention(Q, K, Vt, Oo, None, L, L, bad)
@@ -209,9 +211,13 @@ def test_attention_variant_argument_errors():
             B.chorus_attention(Q, K64, Vt64, Oo, None, L, 64, v)
 
 
-@pytest.mark.parametrize("variant", [0, 3])
-@pytest.mark.parametrize("H,dh,Lq,Lt", [(4, 64, 256, 16), (12, 128, 700, 512), (2, 128, 100, 77)])
+@pytest.mark.parametrize("variant", [0, 3, 5, 6])
+@pytest.mark.parametrize("H,dh,Lq,Lt", [(4, 64, 256, 16), (12, 128, 700, 512), (2, 128, 100, 77), (2, 128, 300, 700),
+                                        (1, 64, 260, 1027)])
 def test_attention_tgaa_column_scale(H, dh, Lq, Lt, variant):
+    """Eq. 2 as a per-key logit factor, on the 64-key kernel (3), on the 16x16x32 kernel with and without pre-scaled
+    queries (5, 6) and on the default choice (0: the latter from 512 keys on); key counts that end a 128-key tile
+    on a multiple of four and off one."""
     print(f"[case] cross-attention TGAA H={H} dh={dh} Lq={Lq} Lt={Lt} variant={variant}", flush=True)
     _attn_case(H, dh, Lq, Lt, variant, col_scale=synth.tdiff_scale(Lt, 1.5), q_std=1.5, name="tgaa-all")
     _attn_case(H, dh, Lq, Lt, variant, col_scale=synth.tdiff_scale(Lt, 1.5, n_diff=max(1, Lt // 64)), q_std=1.5, name="tgaa-subset")
