@@ -435,22 +435,24 @@ __global__ __launch_bounds__(512, 2) void attention_pp16_kernel(
     if constexpr (CS) {
       // the column factors of this tile are fetched and applied before the prefetch is issued: loads return in order,
       // and the 32 registers they take are free again when the prefetch needs its own
-      const long key0 = (long)j * KTL + 16 * (g >> 1) + 4 * (g & 1);
+      const int key0 = j * KTL + 16 * (g >> 1) + 4 * (g & 1);
+      const int lk = (int)Lk;
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb) {
-        const long key = key0 + 32 * (kb >> 1) + 8 * (kb & 1);
+        const int key = key0 + 32 * (kb >> 1) + 8 * (kb & 1);
         f32x4 cf;
-        if (key + 3 < Lk) {
+        if (key + 3 < lk) {
           cf = *reinterpret_cast<const f32x4*>(col_scale + key);
         } else {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) cf[i] = key + i < Lk ? col_scale[key + i] : 1.0f;
+          for (int i = 0; i < 4; ++i) cf[i] = key + i < lk ? col_scale[key + i] : 1.0f;
         }
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
           for (int i = 0; i < 4; ++i)
             s[kb][rb][i] = PRE ? __builtin_fmaf(s[kb][rb][i], cf[i], -m_run[rb]) : s[kb][rb][i] * cf[i];
+        if (kb % 2 == 1) __builtin_amdgcn_sched_barrier(0);  // two factors in flight at a time: there are no registers for eight
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -679,7 +681,7 @@ extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const 
   if (Lq == 0) return CHORUS_OK;
   if (Lk < 1) return CHORUS_E_SHAPE;
   if (!Q || !K || !Vt || !O) return CHORUS_E_ARG;
-  if ((dh != 64 && dh != 128) || LkPad % KT || LkPad < Lk || LqPad < Lq) return CHORUS_E_SHAPE;
+  if ((dh != 64 && dh != 128) || LkPad % KT || LkPad < Lk || LqPad < Lq || LkPad > 0x7fffffffL) return CHORUS_E_SHAPE;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(Vt) || !aligned16(O) || !aligned16(col_scale)) return CHORUS_E_ARG;
   hipStream_t s = (hipStream_t)stream;
   const bool cs = col_scale != nullptr;
