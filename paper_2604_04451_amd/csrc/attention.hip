@@ -159,12 +159,21 @@ __global__ __launch_bounds__(512, 2) void attention_pp_kernel(
     __builtin_amdgcn_sched_barrier(0);
     const long key0 = (long)j * KTL + 4 * c;
     if (COLSCALE) {
+      // a lane's keys come in runs of four: one 16-byte load per run (the runs that cross the end one key at a time)
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          long key = key0 + 32 * kb + 8 * (r >> 2) + (r & 3);
-          s[kb][r] *= col_scale[key < Lk ? key : Lk - 1] * scale_log2;
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const long key = key0 + 32 * kb + 8 * q4;
+          f32x4 cf;
+          if (key + 3 < Lk) {
+            cf = *reinterpret_cast<const f32x4*>(col_scale + key);
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) cf[i] = key + i < Lk ? col_scale[key + i] : 1.0f;
+          }
+#pragma unroll
+          for (int i = 0; i < 4; ++i) s[kb][4 * q4 + i] *= cf[i] * scale_log2;
         }
     }
     if (j == ntiles - 1 && (Lk % KTL) != 0) {
