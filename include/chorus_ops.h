@@ -86,10 +86,10 @@ int32_t chorus_v_transpose(const uint16_t* in, int64_t ld, uint16_t* out, int64_
  * (finite values).
  * variant: 0 = the default choice (128-key tiles on 16x16x32 MFMAs when
  * CHORUS_ATTENTION_LONG_KEYS(Lk, LkPad): LkPad % 128 == 0 and Lk >= 512; else 64-key tiles on 32x32x16 MFMAs);
- * 3 = 64-key tiles; 4 = 128-key tiles on 32x32x16 MFMAs (CHORUS_E_SHAPE with a col_scale); 5 = 128-key tiles on
+ * 3 = 64-key tiles; 5 = 128-key tiles on
  * 16x16x32 MFMAs; 6 = as 5 for a Q that holds the queries already multiplied by log2(e) / sqrt(dh)
  * (CHORUS_ATTENTION_Q_PRESCALE(dh), applied in fp32 by the producer before its rounding to bf16): the same
- * function of the unscaled queries, with one vector instruction less per logit when col_scale is NULL. 4, 5 and 6
+ * function of the unscaled queries, with one vector instruction less per logit when col_scale is NULL. 5 and 6
  * give CHORUS_E_SHAPE when LkPad % 128 != 0. Any other value: CHORUS_E_ARG. */
 #define CHORUS_ATTENTION_Q_PRESCALE(dh) (1.4426950408889634f / sqrtf((float)(dh)))
 #define CHORUS_ATTENTION_LONG_KEYS(Lk, LkPad) ((LkPad) % 128 == 0 && (Lk) >= 512)

@@ -2,13 +2,14 @@
 // operands on the matrix pipe, fp32 online softmax, logits never leave registers.
 // Used for the block's 3-D self-attention (g = 1) and for the text cross-attention
 // with TGAA key amplification (Eq. 2: scaling key j by gamma_k scales logit column j).
-// Two kernels of one design: attention_pp_kernel on v_mfma_f32_32x32x16_bf16 (64- or
-// 128-key tiles, optional column scale: cross-attention and short sequences), described
-// first, and attention_pp16_kernel on v_mfma_f32_16x16x32_bf16 (long self-attention),
-// whose differences are described in front of it.
+// Two kernels of one design: attention_pp_kernel on v_mfma_f32_32x32x16_bf16 (64-key
+// tiles: key sequences shorter than 512 or padded to 64), described first, and
+// attention_pp16_kernel on v_mfma_f32_16x16x32_bf16 (128-key tiles: self-attention and
+// the text cross-attention from 512 keys on), whose differences are described in front of it.
+// Both take the optional per-key logit factor.
 //
 // Work split: a workgroup of 8 waves owns 256 query rows of one head (32 per wave, held in
-// registers) and sweeps all keys in tiles of 64 or 128. K tiles [keys][dh] and V^T tiles
+// registers) and sweeps all keys in tiles of 64 (128 in the second kernel). K tiles [keys][dh] and V^T tiles
 // [dh][keys] are staged through LDS (double-buffered, rows padded by 16 bytes against bank
 // conflicts) and shared by the 8 waves.
 //
@@ -680,13 +681,13 @@ int32_t launch_attn_pp(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt,
 
 using namespace chorus;
 
-// variant: 0 = default choice; 3 = 64-key tiles; 4 = 128-key tiles (no column scale, LkPad % 128 == 0);
-// 5 = 128-key tiles on 16x16x32 MFMAs (LkPad % 128 == 0); 6 = the same on pre-scaled queries
+// variant: 0 = default choice; 3 = 64-key tiles on 32x32x16 MFMAs; 5 = 128-key tiles on 16x16x32 MFMAs
+// (LkPad % 128 == 0); 6 = the same on pre-scaled queries
 extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O,
                                     const float* col_scale, int64_t Lq, int64_t Lk, int64_t LqPad, int64_t LkPad,
                                     int32_t H, int32_t dh, int32_t variant, void* stream) {
   if (Lq < 0 || Lk < 0 || H <= 0) return CHORUS_E_ARG;
-  if (variant != 0 && variant != 3 && variant != 4 && variant != 5 && variant != 6) return CHORUS_E_ARG;
+  if (variant != 0 && variant != 3 && variant != 5 && variant != 6) return CHORUS_E_ARG;
   if (Lq == 0) return CHORUS_OK;
   if (Lk < 1) return CHORUS_E_SHAPE;
   if (!Q || !K || !Vt || !O) return CHORUS_E_ARG;
@@ -703,11 +704,6 @@ extern "C" int32_t chorus_attention(const uint16_t* Q, const uint16_t* K, const 
                        : launch_attn_pp16<64, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
     return dh == 128 ? launch_attn_pp16<128, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
                      : launch_attn_pp16<64, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
-  }
-  if (variant == 4) {
-    if (cs || LkPad % 128) return CHORUS_E_SHAPE;
-    return dh == 128 ? launch_attn_pp<128, 128, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)
-                     : launch_attn_pp<64, 128, false>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s);
   }
   if (dh == 128)
     return cs ? launch_attn_pp<128, 64, true>(Q, K, Vt, O, col_scale, Lq, Lk, LqPad, LkPad, H, s)

@@ -59,7 +59,7 @@ def test_self_attention_full_length_peaked(H, L):
     B.chorus_v_transpose(dev_bf16(v), 0, Vt, L)
     rows = _rows(L, 96, 7)
     ref = O.attention(q[rows].astype(np.float64), k.astype(np.float64), v.astype(np.float64), H, dh)
-    for variant in (0, 4, 5, 3):
+    for variant in (0, 5, 3):
         print(f"[launch] attention full length H={H} L={L} variant={variant}", flush=True)
         Oo = torch.empty(L, D, dtype=torch.bfloat16, device=DEV)
         B.chorus_attention(Q, K, Vt, Oo, None, L, L, variant)
