@@ -219,6 +219,7 @@ int32_t chorus_text_project(const uint16_t* text, int32_t Lt, int32_t text_dim, 
  *   blocks host array [n_blocks] of structs of device pointers
  *   latent dev [C, T, Hl, Wl] fp32 in/out;  SL same shape
  *   t_mod dev [6, D], t_head dev [2, D] fp32: projected timestep embedding of this step
+ *   tgaa_key_scale dev [Lt] fp32, 16-byte aligned, or NULL; gamma_o: as in chorus_dit_block_step
  * The patch is 1 x ph x pw; the block's token grid must be (T, Hl/ph, Wl/pw).
  * ------------------------------------------------------------------------ */
 typedef struct {
