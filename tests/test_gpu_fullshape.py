@@ -42,7 +42,7 @@ def _rows(L, n, seed):
 @pytest.mark.parametrize("H,L", [(12, 32760), (12, 13104), (2, 75600)])
 def test_self_attention_full_length_peaked(H, L):
     """Self-attention at the benchmark's own lengths with peaked logits (std ~4), sampled query rows against
-    the oracle: the library's default choice (the 128-key tile kernel the benchmark times) and both tile sizes
+    the oracle: the library's default choice, the 128-key 16x16x32 kernel and the 64-key kernel
     forced."""
     dh = 128
     print(f"[case] attention full length H={H} L={L}", flush=True)
