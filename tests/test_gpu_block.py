@@ -114,6 +114,22 @@ def test_block_ragged_rows():
         _compare(got, inp["x"], ref, f"ragged Ls={Ls}")
 
 
+def test_block_refuses_key_factors_off_a_16_byte_boundary():
+    """The TGAA key factors are read 16 bytes at a time: a pointer off that boundary is an argument error, found
+    before anything is launched (the residual stream is untouched)."""
+    bs = synth.SHAPES["c1"]
+    w = synth.stress_block_weights(bs, 4)
+    inp = synth.block_inputs(bs, 4, x_std=1.0)
+    shape = P.make_block_shape(bs.D, bs.H, bs.dh, bs.F, bs.Lt, bs.grid)
+    dw = P.upload_block_weights(w)
+    x = dev_f32(inp["x"])
+    ks = torch.ones(bs.Lt + 4, dtype=torch.float32, device=DEV)[1:bs.Lt + 1]
+    with pytest.raises(P.ChorusError):
+        P.chorus_dit_block_step(shape, dw, x, x.shape[0], None, dev_bf16(inp["text_ctx"]), dev_f32(inp["t_mod"]), ks, 1.0)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(x), inp["x"])
+
+
 def test_block_zero_gates_identity():
     """All gates zero and gamma_o = 0: the block must return its input exactly."""
     bs = synth.SHAPES["c1"]
