@@ -41,8 +41,8 @@ int32_t chorus_gemm_bf16(const uint16_t* A, const uint16_t* W, int64_t M, int32_
 
 /* chorus_gemm_bf16 with the tile kernel named by the caller, for tests and comparisons (every kernel is correct on
  * every shape the call accepts; only the speed differs): kernel 0 = the default choice by problem size,
- * 1 = 128 x 64 register-staged tiles, 2 = 256 x 128 register-staged tiles, 3 = 256 x 256 direct-to-LDS tiles.
- * Anything else: CHORUS_E_ARG. */
+ * 1 = 128 x 64 register-staged tiles, 2 = 256 x 128 register-staged tiles, 3 = 256 x 256 direct-to-LDS tiles,
+ * 4 = 128 x 128 direct-to-LDS tiles. Anything else: CHORUS_E_ARG. */
 int32_t chorus_gemm_bf16_kernel(const uint16_t* A, const uint16_t* W, int64_t M, int32_t N, int32_t K, int32_t epilogue,
                                 void* out, const float* bias, const float* gate0, const float* gate1, float scale,
                                 int32_t kernel, void* stream);

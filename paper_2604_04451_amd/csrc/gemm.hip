@@ -320,28 +320,32 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t* __res
 // a new home, at the price of several hundred accumulator moves per k-step.
 // ---------------------------------------------------------------------------
 
+// WB = 16 x 16 blocks along each side of a wave's quadrant: 8 (256 x 256 tiles) or 4 (128 x 128 tiles).
+//
 // bf16 (optionally GELU) epilogue of the 16x16 layout: 32 output rows at a time go through a private LDS region as
-// [32][128] bf16 (row stride 136), then leave as full 256-byte row segments.
-constexpr int E16_BF_STRIDE = 128 + 8;
-constexpr int E16_BF_WAVE = 32 * E16_BF_STRIDE;  // elements per wave
-template <int EPI>
+// [32][16 WB] bf16 (row stride 16 WB + 8), then leave as full row segments of the quadrant (256 or 128 bytes).
+template <int WB> constexpr int e16_bf_stride() { return 16 * WB + 8; }
+template <int WB> constexpr int e16_bf_wave() { return 32 * e16_bf_stride<WB>(); }  // elements per wave
+template <int EPI, int WB>
 __device__ __forceinline__ void gemm16_epilogue_bf16(const f32x4 (&acc)[8][8], const EpiArgs& ep, uint16_t* cw, long m_wave0,
                                                      int n_wave0, long M, int N, int lane) {
+  constexpr int E16_BF_STRIDE = e16_bf_stride<WB>();
+  constexpr int LPR = 2 * WB, RPI = 64 / LPR;  // read-back: LPR lanes x 16 bytes per row, RPI rows per instruction
   const int lj = lane & 15, lg = lane >> 4;
-  const int rrow = lane >> 4, rcol = (lane & 15) * 8;  // read-back: 4 rows per instruction, 16 lanes x 16 bytes per row
-  float4 bias[8];
+  const int rrow = lane / LPR, rcol = (lane % LPR) * 8;
+  float4 bias[WB];
 #pragma unroll
-  for (int nb = 0; nb < 8; ++nb) {
+  for (int nb = 0; nb < WB; ++nb) {
     const int n = n_wave0 + 16 * nb + 4 * lg;
     bias[nb] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (ep.bias && n < N) bias[nb] = *reinterpret_cast<const float4*>(ep.bias + n);
   }
 #pragma unroll
-  for (int mp = 0; mp < 4; ++mp) {  // pairs of 16-row blocks
+  for (int mp = 0; mp < WB / 2; ++mp) {  // pairs of 16-row blocks
 #pragma unroll
     for (int mh = 0; mh < 2; ++mh)
 #pragma unroll
-      for (int nb = 0; nb < 8; ++nb) {
+      for (int nb = 0; nb < WB; ++nb) {
         const f32x4& a = acc[nb][2 * mp + mh];
         float v0 = a[0] + bias[nb].x, v1 = a[1] + bias[nb].y, v2 = a[2] + bias[nb].z, v3 = a[3] + bias[nb].w;
         if (EPI == CHORUS_EPI_GELU_BF16) {
@@ -354,8 +358,8 @@ __device__ __forceinline__ void gemm16_epilogue_bf16(const f32x4 (&acc)[8][8], c
       }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int row = 4 * it + rrow;
+    for (int it = 0; it < 32 / RPI; ++it) {
+      const int row = RPI * it + rrow;
       const long m = m_wave0 + 32 * mp + row;
       const int n = n_wave0 + rcol;
       const u32x4 v = *reinterpret_cast<const u32x4*>(cw + row * E16_BF_STRIDE + rcol);
@@ -369,14 +373,17 @@ __device__ __forceinline__ void gemm16_epilogue_bf16(const f32x4 (&acc)[8][8], c
 }
 
 // fp32 gated-residual epilogue of the 16x16 layout: 16 output rows at a time through a private LDS region as
-// [16][128] fp32 (row stride 132), read back with 32 lanes per row; the residual rows are requested before the LDS
-// round trip. out[m][n] += gate[n] * scale * (acc + bias[n]).
-constexpr int E16_F32_STRIDE = 128 + 4;
-constexpr int E16_F32_WAVE = 16 * E16_F32_STRIDE;  // floats per wave
+// [16][16 WB] fp32 (row stride 16 WB + 4), read back with 4 WB lanes per row; the residual rows are requested before the
+// LDS round trip. out[m][n] += gate[n] * scale * (acc + bias[n]).
+template <int WB> constexpr int e16_f32_stride() { return 16 * WB + 4; }
+template <int WB> constexpr int e16_f32_wave() { return 16 * e16_f32_stride<WB>(); }  // floats per wave
+template <int WB>
 __device__ __forceinline__ void gemm16_epilogue_resid(const f32x4 (&acc)[8][8], const EpiArgs& ep, float* cw, long m_wave0,
                                                       int n_wave0, long M, int N, int lane) {
+  constexpr int E16_F32_STRIDE = e16_f32_stride<WB>();
+  constexpr int LPR = 4 * WB, RPI = 64 / LPR;  // read-back: LPR lanes x 16 bytes per row, RPI rows per instruction
   const int lj = lane & 15, lg = lane >> 4;
-  const int rrow = lane >> 5, rcol = (lane & 31) * 4;  // read-back: 2 rows per instruction, 32 lanes x 16 bytes per row
+  const int rrow = lane / LPR, rcol = (lane % LPR) * 4;
   const int n = n_wave0 + rcol;
   const bool n_ok = n < N;
   f32x4 bias = {0.f, 0.f, 0.f, 0.f}, gate = {1.f, 1.f, 1.f, 1.f};
@@ -392,27 +399,27 @@ __device__ __forceinline__ void gemm16_epilogue_resid(const f32x4 (&acc)[8][8], 
   float* out = reinterpret_cast<float*>(ep.out);
   // The residual rows of block mb + 1 are requested before the results of block mb are stored: memory operations
   // retire in order, so a load issued behind a block's stores could only be consumed once those stores had drained.
-  f32x4 cur[2][8];
-  auto fetch = [&](int mb, f32x4 (&dst)[8]) {
+  f32x4 cur[2][WB];
+  auto fetch = [&](int mb, f32x4 (&dst)[WB]) {
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      long m = m_wave0 + 16 * mb + 2 * it + rrow;
+    for (int it = 0; it < WB; ++it) {
+      long m = m_wave0 + 16 * mb + RPI * it + rrow;
       if (m > M - 1) m = M - 1;  // rows past the end read the last row (never stored)
       dst[it] = *reinterpret_cast<const f32x4*>(out + m * N + (n_ok ? n : 0));
     }
   };
   fetch(0, cur[0]);
 #pragma unroll
-  for (int mb = 0; mb < 8; ++mb) {
+  for (int mb = 0; mb < WB; ++mb) {
 #pragma unroll
-    for (int nb = 0; nb < 8; ++nb) *reinterpret_cast<f32x4*>(cw + lj * E16_F32_STRIDE + 16 * nb + 4 * lg) = acc[nb][mb];
+    for (int nb = 0; nb < WB; ++nb) *reinterpret_cast<f32x4*>(cw + lj * E16_F32_STRIDE + 16 * nb + 4 * lg) = acc[nb][mb];
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-    if (mb + 1 < 8) fetch(mb + 1, cur[(mb + 1) & 1]);
+    if (mb + 1 < WB) fetch(mb + 1, cur[(mb + 1) & 1]);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const f32x4 v = *reinterpret_cast<const f32x4*>(cw + (2 * it + rrow) * E16_F32_STRIDE + rcol);
-      const long m = m_wave0 + 16 * mb + 2 * it + rrow;
+    for (int it = 0; it < WB; ++it) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(cw + (RPI * it + rrow) * E16_F32_STRIDE + rcol);
+      const long m = m_wave0 + 16 * mb + RPI * it + rrow;
       if (n_ok && m < M) *reinterpret_cast<f32x4*>(out + m * N + n) = cur[mb & 1][it] + gate * (v + bias);
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
@@ -420,37 +427,41 @@ __device__ __forceinline__ void gemm16_epilogue_resid(const f32x4 (&acc)[8][8], 
   }
 }
 
-// Epilogue of the 4-wave 16x16 kernels: wave (wm, wn) holds rows m0 + 128 wm .. +128, columns n0 + 128 wn .. +128.
-template <int EPI>
+// Epilogue of the 4-wave 16x16 kernels: wave (wm, wn) holds rows m0 + 16 WB wm .. + 16 WB, columns n0 + 16 WB wn .. + 16 WB.
+template <int EPI, int WB>
 __device__ __forceinline__ void gemm16_finish(f32x4 (&acc)[8][8], const EpiArgs& ep, uint8_t* smem_raw, int wave, int wm, int wn,
                                               long m0, int n0, long M, int N, int lane) {
+  constexpr int WT = 16 * WB;  // rows and columns of a wave's quadrant
   uint16_t* smem = reinterpret_cast<uint16_t*>(smem_raw);
   const int lj = lane & 15, lg = lane >> 4;
   if constexpr (EPI == CHORUS_EPI_BF16 || EPI == CHORUS_EPI_GELU_BF16) {
-    gemm16_epilogue_bf16<EPI>(acc, ep, smem + wave * E16_BF_WAVE, m0 + wm * 128, n0 + wn * 128, M, N, lane);
+    gemm16_epilogue_bf16<EPI, WB>(acc, ep, smem + wave * e16_bf_wave<WB>(), m0 + wm * WT, n0 + wn * WT, M, N, lane);
   } else if constexpr (EPI == CHORUS_EPI_RESID) {
-    gemm16_epilogue_resid(acc, ep, reinterpret_cast<float*>(smem_raw) + wave * E16_F32_WAVE, m0 + wm * 128, n0 + wn * 128, M, N, lane);
+    gemm16_epilogue_resid<WB>(acc, ep, reinterpret_cast<float*>(smem_raw) + wave * e16_f32_wave<WB>(), m0 + wm * WT, n0 + wn * WT, M,
+                              N, lane);
   } else {
     // plain fp32: a lane stores its four consecutive columns of every block
 #pragma unroll
-    for (int nb = 0; nb < 8; ++nb) {
-      const int n = n0 + wn * 128 + 16 * nb + 4 * lg;
+    for (int nb = 0; nb < WB; ++nb) {
+      const int n = n0 + wn * WT + 16 * nb + 4 * lg;
       if (n >= N) continue;
       f32x4 bias = {0.f, 0.f, 0.f, 0.f};
       if (ep.bias) bias = *reinterpret_cast<const f32x4*>(ep.bias + n);
 #pragma unroll
-      for (int mb = 0; mb < 8; ++mb) {
-        const long m = m0 + wm * 128 + 16 * mb + lj;
+      for (int mb = 0; mb < WB; ++mb) {
+        const long m = m0 + wm * WT + 16 * mb + lj;
         if (m < M) *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(ep.out) + m * N + n) = acc[nb][mb] + bias;
       }
     }
   }
 }
 
-template <int EPI>
+template <int EPI, int WB>
 __global__ __launch_bounds__(256, 1) void gemm_w16_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
                                                           long M, int N, int K, EpiArgs ep, int tiles_m, int tiles_n) {
-  constexpr int BM = 256, BN = 256;
+  static_assert(WB == 8 || WB == 4, "quadrants of 8 x 8 or 4 x 4 blocks");
+  constexpr int BM = 32 * WB, BN = 32 * WB;
+  constexpr int WT = 16 * WB;  // rows and columns of a wave's quadrant
   constexpr int GM = 8;
   constexpr int STAGE = (BM + BN) * BK;  // elements per stage
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem_raw[];
@@ -477,13 +488,15 @@ __global__ __launch_bounds__(256, 1) void gemm_w16_kernel(const uint16_t* __rest
   const int wm = wave >> 1, wn = wave & 1;
   const int lj = lane & 15, lg = lane >> 4;
 
-  // ---- loader: wave w, slot i (0..7) covers tile rows 8*(8w+i) .. +8 of A and of W; lane -> (row, position)
+  // ---- loader: wave w, slot i (0..WB-1) covers tile rows 8*(WB w+i) .. +8 of A and of W; lane -> (row, position)
   const int lr = lane >> 3, lp = lane & 7;
+  // (the arrays that the lambdas below capture have the large tile's size for either tile: a bound that depends on
+  // the template parameter loses the kernel's host-side stub)
   const uint16_t* ga[8];
   const uint16_t* gb[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int r = 8 * (8 * wave + i) + lr;
+  for (int i = 0; i < WB; ++i) {
+    const int r = 8 * (WB * wave + i) + lr;
     const int ch = lp ^ ((r >> 1) & 7);  // global chunk that belongs at position lp
     long ra = m0 + r;
     if (ra > M - 1) ra = M - 1;
@@ -492,13 +505,13 @@ __global__ __launch_bounds__(256, 1) void gemm_w16_kernel(const uint16_t* __rest
     ga[i] = A + ra * (long)K + ch * 8;
     gb[i] = W + (long)rb * K + ch * 8;
   }
-  auto issue = [&](int kt, int stage, int t0, int t1) {  // loads t0 .. t1-1 of the 16 per k-step (even: A rows, odd: W rows)
+  auto issue = [&](int kt, int stage, int t0, int t1) {  // loads t0 .. t1-1 of the 2 WB per k-step (even: A rows, odd: W rows)
     uint16_t* sa = smem + stage * STAGE;
     uint16_t* sb = sa + BM * BK;
 #pragma unroll
     for (int t = t0; t < t1; ++t) {
       const int i = t >> 1;
-      const int rows0 = 8 * (8 * wave + i);
+      const int rows0 = 8 * (WB * wave + i);
       if (t & 1)
         __builtin_amdgcn_global_load_lds(gb[i] + (long)kt * BK, sb + rows0 * BK, 16, 0, 0);
       else
@@ -511,35 +524,37 @@ __global__ __launch_bounds__(256, 1) void gemm_w16_kernel(const uint16_t* __rest
   int koff[2];
 #pragma unroll
   for (int h = 0; h < 2; ++h) koff[h] = ((4 * h + lg) ^ sw) * 8;
-  const int a_row0 = (wm * 128 + lj) * BK;
-  const int b_row0 = BM * BK + (wn * 128 + lj) * BK;
+  const int a_row0 = (wm * WT + lj) * BK;
+  const int b_row0 = BM * BK + (wn * WT + lj) * BK;
 
-  f32x4 acc[8][8];  // [n block][m block]
+  f32x4 acc[8][8];  // [n block][m block]; the WB x WB corner is used
 #pragma unroll
-  for (int nb = 0; nb < 8; ++nb)
+  for (int nb = 0; nb < WB; ++nb)
 #pragma unroll
-    for (int mb = 0; mb < 8; ++mb) acc[nb][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int mb = 0; mb < WB; ++mb) acc[nb][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   bf16x8 af[2][8], bfr[2][8];
-  // fragment f of a half-step: 0-7 the activation blocks (m), 8-15 the weight blocks (n)
+  // fragment f of a half-step: 0 .. WB-1 the activation blocks (m), WB .. 2 WB-1 the weight blocks (n)
   auto read_frag = [&](const uint16_t* st, int h, int set, int f) {
-    if (f < 8)
+    if (f < WB)
       af[set][f] = *reinterpret_cast<const bf16x8*>(st + a_row0 + f * 16 * BK + koff[h]);
     else
-      bfr[set][f - 8] = *reinterpret_cast<const bf16x8*>(st + b_row0 + (f - 8) * 16 * BK + koff[h]);
+      bfr[set][f - WB] = *reinterpret_cast<const bf16x8*>(st + b_row0 + (f - WB) * 16 * BK + koff[h]);
   };
-  // MFMAs g0 .. g1-1 of the 64 of a half-step, weight block major: g = 8 nb + mb. In place on the accumulator
+  // MFMAs g0 .. g1-1 of the WB * WB of a half-step, weight block major: g = WB nb + mb. In place on the accumulator
   // registers (left to itself the register allocator gives every result a new home and pays with hundreds of
   // accumulator moves per k-step); being volatile they also keep their place between the loads written around them.
   auto mfmas = [&](int set, int g0, int g1) {
 #pragma unroll
     for (int g = g0; g < g1; ++g)
-      asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[g >> 3][g & 7]) : "v"(bfr[set][g >> 3]), "v"(af[set][g & 7]));
+      asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[g / WB][g % WB]) : "v"(bfr[set][g / WB]), "v"(af[set][g % WB]));
   };
-  // order in which the fragments of a half-step are fetched: what its first MFMAs need comes first
-  constexpr int kFragOrder[16] = {8, 0, 1, 2, 3, 4, 5, 6, 7, 9, 10, 11, 12, 13, 14, 15};
+  // order in which the fragments of a half-step are fetched: what its first MFMAs need comes first (the first weight
+  // block, the activation blocks, the other weight blocks)
+  auto frag_order = [](int i) { return i == 0 ? WB : (i <= WB ? i - 1 : i); };
 
-  // Schedule of one k-step (128 MFMAs a wave, 32 slots of four). The barrier sits between the two half-steps. In the
+  // Schedule of one k-step (2 WB^2 MFMAs a wave in 4 WB slots of WB / 2: 128 MFMAs in 32 slots of four for the large
+  // tile). The barrier sits between the two half-steps. In the
   // first half a wave fetches its fragments of the second half (same stage); at the barrier every wave holds all its
   // fragments of the current stage in registers and its own pieces of the next stage, requested a whole half-step
   // earlier, have landed. Behind it the stage just consumed is free: the second half issues the loads of the step after
@@ -548,84 +563,95 @@ __global__ __launch_bounds__(256, 1) void gemm_w16_kernel(const uint16_t* __rest
   // wave per SIMD nothing else feeds the matrix pipe while this wave issues something that is not an MFMA, so reads and
   // loads stand one at a time between single MFMAs, where they issue in the shadow of the MFMA in front of them, and
   // the wave index is kept in a scalar register so that the LDS address of a load costs no vector instruction.
-  constexpr int kReadSlots = 12;
+  constexpr int NS = 2 * WB;              // slots of a half-step = fragments of a half-step = loads of a k-step
+  constexpr int MPS = WB / 2;             // MFMAs of a slot
+  constexpr int kReadSlots = 3 * WB / 2;  // 12 of 16 (6 of 8)
   const int KTN = K / BK;
   auto clampk = [&](int k) { return k < KTN ? k : KTN - 1; };  // past the end: re-fetch the last tile into an idle stage
-  // reads of slot f: one fragment, two in the first 16 - kReadSlots slots (which = 0: the first, 1: the second)
+  // reads of slot f: one fragment, two in the first NS - kReadSlots slots (which = 0: the first, 1: the second)
   auto read_of_slot = [&](const uint16_t* stg, int h, int set, int f, int which) {
-    constexpr int kDouble = 16 - kReadSlots;
+    constexpr int kDouble = NS - kReadSlots;
     if (f < kDouble)
-      read_frag(stg, h, set, kFragOrder[2 * f + which]);
+      read_frag(stg, h, set, frag_order(2 * f + which));
     else if (f < kReadSlots && which == 0)
-      read_frag(stg, h, set, kFragOrder[f + kDouble]);
+      read_frag(stg, h, set, frag_order(f + kDouble));
   };
-  issue(0, 0, 0, 16);
-  issue(clampk(1), 1, 0, 16);
-  __builtin_amdgcn_s_waitcnt(0x4F70);  // vmcnt(16): the first step's pieces are in LDS, the second step's may be in flight
+  issue(0, 0, 0, NS);
+  issue(clampk(1), 1, 0, NS);
+  // vmcnt(NS): the first step's pieces are in LDS, the second step's may be in flight
+  if constexpr (WB == 8)
+    __builtin_amdgcn_s_waitcnt(0x4F70);
+  else
+    __builtin_amdgcn_s_waitcnt(0x0F78);
   lds_barrier();
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int f = 0; f < 16; ++f) read_frag(smem, 0, 0, kFragOrder[f]);
+  for (int f = 0; f < NS; ++f) read_frag(smem, 0, 0, frag_order(f));
   __builtin_amdgcn_sched_barrier(0);
 
   for (int kt = 0; kt < KTN; ++kt) {
     const uint16_t* st = smem + (kt & 1) * STAGE;
     const uint16_t* stn = smem + ((kt + 1) & 1) * STAGE;
     const int k2 = clampk(kt + 2);
-    // ---- half-step 0: 64 MFMAs and the fragment reads of half-step 1
+    // ---- half-step 0: WB^2 MFMAs and the fragment reads of half-step 1
 #pragma unroll
-    for (int f = 0; f < 16; ++f) {
-      mfmas(0, 4 * f, 4 * f + 1);
+    for (int f = 0; f < NS; ++f) {
+      mfmas(0, MPS * f, MPS * f + 1);
       __builtin_amdgcn_sched_barrier(0);
       read_of_slot(st, 1, 1, f, 0);
       __builtin_amdgcn_sched_barrier(0);
-      mfmas(0, 4 * f + 1, 4 * f + 2);
+      mfmas(0, MPS * f + 1, MPS * f + 2);
       __builtin_amdgcn_sched_barrier(0);
       read_of_slot(st, 1, 1, f, 1);
       __builtin_amdgcn_sched_barrier(0);
-      mfmas(0, 4 * f + 2, 4 * f + 4);
+      mfmas(0, MPS * f + 2, MPS * f + MPS);
       __builtin_amdgcn_sched_barrier(0);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's pieces of step kt+1 are in LDS
     lds_barrier();                       // every wave has all its fragments of this stage in registers
     __builtin_amdgcn_sched_barrier(0);
-    // ---- half-step 1: 64 MFMAs, the next step's first-half fragments, the loads of step kt+2 into the stage just freed
+    // ---- half-step 1: WB^2 MFMAs, the next step's first-half fragments, the loads of step kt+2 into the stage just freed
 #pragma unroll
-    for (int f = 0; f < 16; ++f) {
-      mfmas(1, 4 * f, 4 * f + 1);
+    for (int f = 0; f < NS; ++f) {
+      mfmas(1, MPS * f, MPS * f + 1);
       __builtin_amdgcn_sched_barrier(0);
       read_of_slot(stn, 0, 0, f, 0);
       __builtin_amdgcn_sched_barrier(0);
-      mfmas(1, 4 * f + 1, 4 * f + 2);
+      mfmas(1, MPS * f + 1, MPS * f + 2);
       __builtin_amdgcn_sched_barrier(0);
       read_of_slot(stn, 0, 0, f, 1);
       __builtin_amdgcn_sched_barrier(0);
-      mfmas(1, 4 * f + 2, 4 * f + 3);
+      mfmas(1, MPS * f + 2, MPS * f + MPS - 1);  // (none for the small tile)
       __builtin_amdgcn_sched_barrier(0);
       issue(k2, kt & 1, f, f + 1);
       __builtin_amdgcn_sched_barrier(0);
-      mfmas(1, 4 * f + 3, 4 * f + 4);
+      if constexpr (MPS > 2) mfmas(1, MPS * f + MPS - 1, MPS * f + MPS);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
 
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the look-ahead loads of the last step have landed
   // The compiler does not know the assembly above for MFMAs and so keeps no distance between the last of them and the
-  // first instruction that reads an accumulator: cover the longest such distance explicitly.
-  asm volatile("s_nop 15\n\ts_nop 15");
+  // first instruction that reads an accumulator: cover the longest such distance explicitly. The wait is tied to the
+  // accumulators of the last four MFMAs (operands of the statement), so that no copy or spill of one of them can be
+  // placed in front of it; every other accumulator was written at least four MFMAs earlier.
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15"
+               : "+a"(acc[WB - 1][WB - 1]), "+a"(acc[WB - 1][WB - 2]), "+a"(acc[WB - 1][WB - 3]), "+a"(acc[WB - 1][WB - 4]));
   lds_barrier();  // the staging regions of the epilogue overlay the operand stages
-  gemm16_finish<EPI>(acc, ep, smem_raw, wave, wm, wn, m0, n0, M, N, lane);
+  gemm16_finish<EPI, WB>(acc, ep, smem_raw, wave, wm, wn, m0, n0, M, N, lane);
 }
 
+template <int WB>
 int32_t launch_gemm_w16(const uint16_t* A, const uint16_t* W, long M, int N, int K, int epi, EpiArgs ep, hipStream_t s) {
-  long tm = (M + 255) / 256;
-  int tn = (N + 255) / 256;
+  constexpr int T = 32 * WB;  // tile side: 256 or 128
+  long tm = (M + T - 1) / T;
+  int tn = (N + T - 1) / T;
   if (tm * tn > 0x7fffffffL) return CHORUS_E_SHAPE;
   dim3 grid((unsigned)(tm * tn)), block(256);
-  const size_t smem = 2 * (256 + 256) * BK * sizeof(uint16_t);  // 128 KB
+  const size_t smem = 2 * (T + T) * BK * sizeof(uint16_t);  // 128 KB (64 KB)
 #define GEMM_W16(E)                                                                             \
   {                                                                                             \
-    auto kern = gemm_w16_kernel<E>;                                                             \
+    auto kern = gemm_w16_kernel<E, WB>;                                                         \
     static DynLdsOnce once;                                                                     \
     CHK_STATUS(once.ensure(reinterpret_cast<const void*>(kern), (int)smem));                    \
     hipLaunchKernelGGL(kern, grid, block, smem, s, A, W, M, N, K, ep, (int)tm, tn);             \
@@ -671,7 +697,7 @@ extern "C" int32_t chorus_gemm_bf16_kernel(const uint16_t* A, const uint16_t* W,
                                            int32_t epilogue, void* out, const float* bias, const float* gate0,
                                            const float* gate1, float scale, int32_t kernel, void* stream) {
   if (M < 0 || N <= 0 || K <= 0) return CHORUS_E_ARG;
-  if (kernel < 0 || kernel > 3) return CHORUS_E_ARG;
+  if (kernel < 0 || kernel > 4) return CHORUS_E_ARG;
   if (M == 0) return CHORUS_OK;
   if (!A || !W || !out) return CHORUS_E_ARG;
   if (K % BK || N % 8) return CHORUS_E_SHAPE;
@@ -681,24 +707,35 @@ extern "C" int32_t chorus_gemm_bf16_kernel(const uint16_t* A, const uint16_t* W,
   hipStream_t s = (hipStream_t)stream;
   if (kernel == 1) return launch_gemm<128, 64, 64, 32>(A, W, (long)M, N, K, epilogue, ep, s);
   if (kernel == 2) return launch_gemm<256, 128, 128, 64>(A, W, (long)M, N, K, epilogue, ep, s);
-  if (kernel == 3) return launch_gemm_w16(A, W, (long)M, N, K, epilogue, ep, s);
+  if (kernel == 3) return launch_gemm_w16<8>(A, W, (long)M, N, K, epilogue, ep, s);
+  if (kernel == 4) return launch_gemm_w16<4>(A, W, (long)M, N, K, epilogue, ep, s);
   // Automatic choice: the estimated time of each tile shape, in microseconds, from fits to measurements on this chip
-  // at K = 1536 and K = 8960, M from 512 to 32760 and N = 1536, 4608 and 8960 (a constant for prologue and epilogue
-  // plus a cost per element of K, both for a full round: a round that fills few units runs faster than this, and
-  // there the small tile is chosen anyway). The two large tiles
-  // run one workgroup per compute unit, so they go in rounds of 256 workgroups; the small tile keeps several
-  // workgroups per unit in flight, so its time grows with the tile count past the first 256.
+  // at K = 1536 and K = 8960, M from 48 to 32760 and N = 1536, 4608 and 8960 (a constant for prologue and epilogue
+  // plus a cost per element of K). The 256 x 256 and 256 x 128 tiles run one workgroup per compute unit, so they go in
+  // rounds of 256 workgroups (the figures are those of a full round: a round that fills few units runs faster, and
+  // there a smaller tile is chosen anyway). The 128 x 128 and 128 x 64 tiles keep several workgroups per unit in
+  // flight, so their time grows with the tile count past the first 256.
   const double k = (double)K;
   const long tiles_n256 = (N + 255) / 256;
+  const bool f32_out = epilogue == CHORUS_EPI_F32 || epilogue == CHORUS_EPI_RESID;
   auto t256 = [&](long m) { return (double)((((m + 255) / 256) * tiles_n256 + 255) / 256) * (2.0 + 0.0265 * k); };
   auto t128 = [&](long m) { return (double)((((m + 255) / 256) * ((N + 127) / 128) + 255) / 256) * (9.0 + 0.0177 * k); };
+  auto t128sq = [&](long m) {  // two workgroups per unit: up to 256 tiles one each, then rounds of 512
+    const long tiles = ((m + 127) / 128) * ((N + 127) / 128);
+    const double one = (f32_out ? 6.0 : -2.0) + 0.0099 * k, round512 = (f32_out ? 9.0 : 1.0) + 0.0162 * k;
+    if (tiles <= 256) return one;
+    if (tiles <= 512) return one + (double)(tiles - 256) / 256.0 * (round512 - one);
+    return (double)((tiles + 511) / 512) * round512;
+  };
   auto t64 = [&](long m) {
     const long small_tiles = ((m + 127) / 128) * ((N + 63) / 64);
     return (5.6 + 0.0084 * k) + (small_tiles > 256 ? (double)(small_tiles - 256) / 256.0 * (0.8 + 0.0057 * k) : 0.0);
   };
+  auto t_best = [&](long m) { return fmin(fmin(t256(m), t128(m)), fmin(t128sq(m), t64(m))); };
   auto launch_best = [&](const uint16_t* a, long m, const EpiArgs& e) {
-    const double a256 = t256(m), a128 = t128(m), a64 = t64(m);
-    if (a256 <= a128 && a256 <= a64) return launch_gemm_w16(a, W, m, N, K, epilogue, e, s);
+    const double a256 = t256(m), a128 = t128(m), a128sq = t128sq(m), a64 = t64(m), best = t_best(m);
+    if (a256 <= best) return launch_gemm_w16<8>(a, W, m, N, K, epilogue, e, s);
+    if (a128sq <= best) return launch_gemm_w16<4>(a, W, m, N, K, epilogue, e, s);
     if (a128 <= a64) return launch_gemm<256, 128, 128, 64>(a, W, m, N, K, epilogue, e, s);
     return launch_gemm<128, 64, 64, 32>(a, W, m, N, K, epilogue, e, s);
   };
@@ -709,10 +746,8 @@ extern "C" int32_t chorus_gemm_bf16_kernel(const uint16_t* A, const uint16_t* W,
   const long head_rows = tiles256 > 256 ? (tiles256 / 256 * 256 / tiles_n256) * 256 : 0;
   if (head_rows > 0 && head_rows < M) {
     const long rest = (long)M - head_rows;
-    const double t_rest = fmin(t256(rest), fmin(t128(rest), t64(rest)));
-    const double t_whole = fmin(t256((long)M), fmin(t128((long)M), t64((long)M)));
-    if (t256(head_rows) + t_rest < 0.95 * t_whole) {
-      const int32_t rc = launch_gemm_w16(A, W, head_rows, N, K, epilogue, ep, s);
+    if (t256(head_rows) + t_best(rest) < 0.95 * t_best((long)M)) {
+      const int32_t rc = launch_gemm_w16<8>(A, W, head_rows, N, K, epilogue, ep, s);
       if (rc != CHORUS_OK) return rc;
       const size_t out_elt = (epilogue == CHORUS_EPI_F32 || epilogue == CHORUS_EPI_RESID) ? 4 : 2;
       EpiArgs ep_rest = ep;

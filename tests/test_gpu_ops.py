@@ -21,7 +21,7 @@ pytestmark = pytest.mark.gpu
                                    (4099, 4608, 1536), (3000, 1536, 8960), (513, 1024, 64), (70, 8, 128),
                                    (4452, 4096, 512)])
 def test_gemm_epilogues(M, N, K):
-    """Every tile kernel (1: 128 x 64, 2: 256 x 128, 3: 256 x 256 direct to LDS) and the automatic choice (0), each on
+    """Every tile kernel (1: 128 x 64, 2: 256 x 128, 3: 256 x 256 and 4: 128 x 128 direct to LDS) and the automatic choice (0), each on
     every shape: tiles with ragged rows and columns, a single row, fewer columns than a tile has, K of one and of
     many steps; the four epilogues. At 4452 x 4096 x 512 the automatic choice cuts the rows: 4096 of them (one whole
     round of 256 x 256 tiles) in one launch, the other 356 on the 128 x 64 kernel in a second."""
@@ -35,7 +35,7 @@ def test_gemm_epilogues(M, N, K):
     ref0 = O.linear(A, W, np.zeros(N))
     gref = O.gelu_tanh(ref)
     dA, dW, db = dev_bf16(A), dev_bf16(W), dev_f32(bias)
-    for kern in (0, 1, 2, 3):
+    for kern in (0, 1, 2, 3, 4):
         print(f"[case] gemm M={M} N={N} K={K} kernel={kern}", flush=True)
         out = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
         B.chorus_gemm_bf16(dA, dW, B.EPI_BF16, out, db, kernel=kern)
